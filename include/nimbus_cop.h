@@ -1,0 +1,120 @@
+/*
+ * nimbus_cop.h -- C ABI of the MI355X (gfx950) library for the client side of
+ * the Client-side Outer Product (COP) linear layer of Nimbus (arXiv 2411.15707).
+ *
+ * What one call computes (Algorithm 1, step 2 and the arithmetic of step 4;
+ * the homomorphic operations (x) and (+) of Appendix B.1):
+ *
+ *     out[j] = ( (+)_{i in [k]}  X[j][i] (x) [[W_i]] )  (+)  mask[j]      j in [m]
+ *
+ * i.e. for every RNS limb l, both ciphertext polynomials p and every
+ * coefficient c of every ring chunk ch
+ *
+ *     out[j][ch][p][l][c] = ( sum_i X[j][i] * ctW[i][ch][p][l][c]
+ *                             + mask[j][ch][p][l][c] )  mod q_l ,
+ *
+ * written as the canonical residue in [0, q_l).  The result is exact; there is
+ * exactly one correct bit pattern.
+ *
+ * Dimension names (the paper's letters in brackets):
+ *   m  tokens = rows of the client's share matrix X = output ciphertexts   [k]
+ *   k  inner dimension = rows of W = number of weight ciphertexts          [m]
+ *   n  output features = used coefficients (row-wise encoding, Eq. (2))    [n]
+ *   N  ring degree, L RNS limbs, Ch = ceil(n / N) ring chunks (the paper
+ *      assumes n <= N; for n > N each weight row is Ch ciphertexts, chunk ch
+ *      holding columns ch*N .. ch*N+N-1 of W).
+ *
+ * Canonical ciphertext layout, row-major:  [row][Ch][2][L][N]  of uint64_t,
+ * polynomial 0 = b-hat, 1 = a-hat.  All N coefficients are processed: after
+ * encryption the positions n..N-1 are as dense as the others.
+ *
+ * Memory: X, ctW, mask, out, prepared and workspace are DEVICE pointers owned by
+ * the caller; `moduli` is a HOST pointer read during the call.  The library
+ * never allocates, frees or synchronises: work is enqueued on `stream`
+ * (a hipStream_t; NULL = the default stream) and the call returns at once.
+ * `out` must not overlap any input.  Calls are re-entrant; calls that share a
+ * workspace must be ordered on one stream.
+ *
+ * Preconditions on device data (not checked): X[j][i] < 2^x_bits,
+ * residues of ctW and mask < q_l.
+ *
+ * Errors: every function returning int gives NIMBUS_COP_OK (0) or a negative
+ * code; on any error nothing was enqueued and `out` is untouched.  No C++
+ * exception crosses this boundary.
+ *
+ * Accepted parameters: m, k, n >= 1; N a power of two in [32, 65536];
+ * L in [1, 4]; x_bits in [1, 32]; every q_l odd with 2^x_bits < q_l < 2^62;
+ * k < 2^24; Ch*2*L*N < 2^31.
+ */
+#ifndef NIMBUS_COP_H
+#define NIMBUS_COP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NIMBUS_COP_OK                 0
+#define NIMBUS_COP_ERR_INVALID_ARG   (-1)  /* null pointer, size or modulus out of range        */
+#define NIMBUS_COP_ERR_UNSUPPORTED   (-2)  /* valid, but outside what this entry point handles  */
+#define NIMBUS_COP_ERR_LAUNCH        (-3)  /* the HIP runtime refused a launch                  */
+#define NIMBUS_COP_ERR_BUFFER_SIZE   (-4)  /* prepared / workspace buffer smaller than required */
+
+/*
+ * COP accumulation + mask on the canonical layout (Algorithm 1 step 2 + step 4).
+ *   X      device [m][k], entries < 2^x_bits
+ *   ctW    device [k][Ch][2][L][N]
+ *   moduli host   [L]
+ *   mask   device [m][Ch][2][L][N], or NULL for no mask
+ *   out    device [m][Ch][2][L][N]
+ * Runs the vector-ALU kernel: any accepted parameter set.
+ */
+int nimbus_cop_matmul(const uint64_t *X, int m, int k, int x_bits,
+                      const uint64_t *ctW, int n, int N, int L,
+                      const uint64_t *moduli,
+                      const uint64_t *mask, uint64_t *out, void *stream);
+
+/*
+ * Setup phase (Section 3.2: the encrypted weights are static, sent once and
+ * reused for every query).  Re-tiles the canonical ctW into the device layout
+ * the matrix-core kernel streams: centred residues split into signed byte
+ * planes, tile order [32-column tile][32-row k block][plane][64 lanes][16 B],
+ * followed by the per-column sums of the residues.
+ *   nimbus_cop_prepared_bytes  size of that buffer (0 on invalid parameters)
+ *   nimbus_cop_prepare         fills it; `prepared` must be 16-byte aligned
+ * Off the timed path: one call per weight matrix.
+ */
+size_t nimbus_cop_prepared_bytes(int k, int n, int N, int L, const uint64_t *moduli);
+int nimbus_cop_prepare(const uint64_t *ctW, int k, int n, int N, int L,
+                       const uint64_t *moduli,
+                       void *prepared, size_t prepared_bytes, void *stream);
+
+/*
+ * COP accumulation + mask on prepared weights (same result, bit for bit, as
+ * nimbus_cop_matmul on the ctW the buffer was prepared from, same k, n, N, L
+ * and moduli).  Runs the int8 matrix-core kernel.
+ *   workspace  device scratch of at least nimbus_cop_workspace_bytes(m, k,
+ *              x_bits) bytes, 16-byte aligned; holds the byte planes of X for
+ *              the duration of the call.
+ * Additional limits (NIMBUS_COP_ERR_UNSUPPORTED beyond them): k <= 32767.
+ */
+size_t nimbus_cop_workspace_bytes(int m, int k, int x_bits);
+int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
+                               const void *prepared, int n, int N, int L,
+                               const uint64_t *moduli,
+                               const uint64_t *mask, uint64_t *out,
+                               void *workspace, size_t workspace_bytes,
+                               void *stream);
+
+/* static, NUL-terminated description of a status code */
+const char *nimbus_cop_strerror(int status);
+
+/* library version, major*10000 + minor*100 + patch */
+int nimbus_cop_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NIMBUS_COP_H */

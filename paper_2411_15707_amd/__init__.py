@@ -1,0 +1,18 @@
+"""MI355X (gfx950) library for the client side of the Nimbus COP linear layer.
+
+Thin ctypes binding over libnimbus_cop.so (C ABI in include/nimbus_cop.h): argument
+marshalling only, every step of the computation runs in the HIP kernels.
+"""
+from .binding import (  # noqa: F401
+    NimbusCopError,
+    lib_path,
+    load_library,
+    nimbus_cop_matmul,
+    nimbus_cop_matmul_prepared,
+    nimbus_cop_prepare,
+    nimbus_cop_prepared_bytes,
+    nimbus_cop_strerror,
+    nimbus_cop_version,
+    nimbus_cop_workspace_bytes,
+    EXPORTED_SYMBOLS,
+)

@@ -1,0 +1,159 @@
+"""ctypes binding of libnimbus_cop.so.  Same names as the C entry points.
+
+Tensors are torch tensors on the GPU holding raw 64-bit words (dtype int64 or
+uint64; the library reads them as uint64_t).  There is no CPU fallback: if the
+shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libnimbus_cop.so"
+_lib = None
+
+EXPORTED_SYMBOLS = (
+    "nimbus_cop_matmul",
+    "nimbus_cop_prepared_bytes",
+    "nimbus_cop_prepare",
+    "nimbus_cop_workspace_bytes",
+    "nimbus_cop_matmul_prepared",
+    "nimbus_cop_strerror",
+    "nimbus_cop_version",
+)
+
+
+class NimbusCopError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {nimbus_cop_strerror(status)} (status {status})")
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """dlopen the HIP library; raises if it has not been built"""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} is missing: build it with `python -m paper_2411_15707_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(path)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.nimbus_cop_matmul.restype = ci
+    lib.nimbus_cop_matmul.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
+    lib.nimbus_cop_prepared_bytes.restype = sz
+    lib.nimbus_cop_prepared_bytes.argtypes = [ci, ci, ci, ci, vp]
+    lib.nimbus_cop_prepare.restype = ci
+    lib.nimbus_cop_prepare.argtypes = [vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.nimbus_cop_workspace_bytes.restype = sz
+    lib.nimbus_cop_workspace_bytes.argtypes = [ci, ci, ci]
+    lib.nimbus_cop_matmul_prepared.restype = ci
+    lib.nimbus_cop_matmul_prepared.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    lib.nimbus_cop_strerror.restype = ctypes.c_char_p
+    lib.nimbus_cop_strerror.argtypes = [ci]
+    lib.nimbus_cop_version.restype = ci
+    lib.nimbus_cop_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _moduli(moduli):
+    arr = (ctypes.c_uint64 * len(moduli))(*[int(q) for q in moduli])
+    return arr
+
+
+def _dev_ptr(t, name, allow_none=False):
+    if t is None:
+        if allow_none:
+            return None
+        raise ValueError(f"{name} is None")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _words(t, name, count):
+    if t.element_size() != 8:
+        raise ValueError(f"{name} must hold 64-bit words")
+    if t.numel() != count:
+        raise ValueError(f"{name} has {t.numel()} words, expected {count}")
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _columns(n, N, L):
+    return (-(-n // N)) * 2 * L * N
+
+
+def nimbus_cop_strerror(status: int) -> str:
+    return load_library().nimbus_cop_strerror(int(status)).decode()
+
+
+def nimbus_cop_version() -> int:
+    return int(load_library().nimbus_cop_version())
+
+
+def nimbus_cop_matmul(X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, stream=None):
+    lib = load_library()
+    C = _columns(n, N, L)
+    _words(X, "X", m * k)
+    _words(ctW, "ctW", k * C)
+    _words(out, "out", m * C)
+    if mask is not None:
+        _words(mask, "mask", m * C)
+    rc = lib.nimbus_cop_matmul(_dev_ptr(X, "X"), m, k, x_bits, _dev_ptr(ctW, "ctW"), n, N, L,
+                               _moduli(moduli), _dev_ptr(mask, "mask", True),
+                               _dev_ptr(out, "out"), _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_matmul")
+
+
+def nimbus_cop_prepared_bytes(k, n, N, L, moduli) -> int:
+    return int(load_library().nimbus_cop_prepared_bytes(k, n, N, L, _moduli(moduli)))
+
+
+def nimbus_cop_prepare(ctW, k, n, N, L, moduli, prepared, stream=None):
+    lib = load_library()
+    _words(ctW, "ctW", k * _columns(n, N, L))
+    nbytes = prepared.numel() * prepared.element_size()
+    rc = lib.nimbus_cop_prepare(_dev_ptr(ctW, "ctW"), k, n, N, L, _moduli(moduli),
+                                _dev_ptr(prepared, "prepared"), nbytes, _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_prepare")
+
+
+def nimbus_cop_workspace_bytes(m, k, x_bits) -> int:
+    return int(load_library().nimbus_cop_workspace_bytes(m, k, x_bits))
+
+
+def nimbus_cop_matmul_prepared(X, m, k, x_bits, prepared, n, N, L, moduli, mask, out,
+                               workspace, stream=None):
+    lib = load_library()
+    C = _columns(n, N, L)
+    _words(X, "X", m * k)
+    _words(out, "out", m * C)
+    if mask is not None:
+        _words(mask, "mask", m * C)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    rc = lib.nimbus_cop_matmul_prepared(
+        _dev_ptr(X, "X"), m, k, x_bits, _dev_ptr(prepared, "prepared"), n, N, L,
+        _moduli(moduli), _dev_ptr(mask, "mask", True), _dev_ptr(out, "out"),
+        _dev_ptr(workspace, "workspace"), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_matmul_prepared")

@@ -1,0 +1,149 @@
+// C ABI of the COP library: argument validation, per-limb constants, dispatch.
+// Declarations and the contract of every entry point: include/nimbus_cop.h.
+#include "cop_common.hpp"
+#include "../../include/nimbus_cop.h"
+
+namespace nimbus {
+
+static int bit_length(uint64_t v)
+{
+    int b = 0;
+    while (v) { ++b; v >>= 1; }
+    return b;
+}
+
+// Shape / modulus checks shared by every entry point.  x_bits <= 0 means "the
+// call has no X" (prepare, size queries) and skips the checks that involve it.
+static int make_problem(int m, int k, int x_bits, int n, int N, int L,
+                        const uint64_t *moduli, bool with_x, Problem *out)
+{
+    if (!moduli) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (k < 1 || n < 1 || k >= (1 << 24)) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (N < 32 || N > 65536 || (N & (N - 1)) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (L < 1 || L > kMaxLimbs) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (with_x && (m < 1 || x_bits < 1 || x_bits > 32)) return NIMBUS_COP_ERR_INVALID_ARG;
+    Problem p{};
+    p.m = with_x ? m : 0;
+    p.k = k;
+    p.x_bits = with_x ? x_bits : 0;
+    p.n = n;
+    p.N = N;
+    p.L = L;
+    p.Ch = (n + N - 1) / N;
+    const unsigned long long C = (unsigned long long)p.Ch * 2ull * (unsigned)L * (unsigned)N;
+    if (C >= (1ull << 31)) return NIMBUS_COP_ERR_INVALID_ARG;
+    p.C = (size_t)C;
+    p.q_bits_max = 0;
+    for (int l = 0; l < L; ++l) {
+        const uint64_t q = moduli[l];
+        if ((q & 1) == 0 || q >= (1ull << 62) || q < 3) return NIMBUS_COP_ERR_INVALID_ARG;
+        if (with_x && q <= (1ull << x_bits)) return NIMBUS_COP_ERR_INVALID_ARG;
+        const int b = bit_length(q);
+        Limb &P = p.limbs.limb[l];
+        P.q = q;
+        P.s1 = (uint32_t)(b - 1);
+        // mu = floor(2^(b+63) / q); b + 63 <= 125
+        P.mu = (uint64_t)((((unsigned __int128)1) << (b + 63)) / q);
+        P.pad = 0;
+        if (b > p.q_bits_max) p.q_bits_max = b;
+    }
+    *out = p;
+    return NIMBUS_COP_OK;
+}
+
+static size_t prepared_bytes_of(const Problem &p)
+{
+    const size_t CT = p.C / kTile;
+    const size_t KB = (size_t)(p.k + kTile - 1) / kTile;
+    const size_t DQ = (size_t)planes_q(p.q_bits_max);
+    return CT * KB * DQ * kTileBytes + p.C * sizeof(uint64_t);
+}
+
+static size_t workspace_bytes_of(int m, int k, int x_bits)
+{
+    const size_t RT = (size_t)(m + kTile - 1) / kTile;
+    const size_t KB = (size_t)(k + kTile - 1) / kTile;
+    return RT * KB * (size_t)planes_x(x_bits) * kTileBytes;
+}
+
+}  // namespace nimbus
+
+using namespace nimbus;
+
+extern "C" {
+
+int nimbus_cop_matmul(const uint64_t *X, int m, int k, int x_bits,
+                      const uint64_t *ctW, int n, int N, int L,
+                      const uint64_t *moduli,
+                      const uint64_t *mask, uint64_t *out, void *stream)
+{
+    if (!X || !ctW || !out) return NIMBUS_COP_ERR_INVALID_ARG;
+    Problem p;
+    const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
+    if (rc != NIMBUS_COP_OK) return rc;
+    const hipError_t e = launch_cop_valu(p, X, ctW, mask, out, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+size_t nimbus_cop_prepared_bytes(int k, int n, int N, int L, const uint64_t *moduli)
+{
+    Problem p;
+    if (make_problem(0, k, 0, n, N, L, moduli, false, &p) != NIMBUS_COP_OK) return 0;
+    return prepared_bytes_of(p);
+}
+
+int nimbus_cop_prepare(const uint64_t *ctW, int k, int n, int N, int L,
+                       const uint64_t *moduli,
+                       void *prepared, size_t prepared_bytes, void *stream)
+{
+    if (!ctW || !prepared) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (((uintptr_t)prepared & 15u) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    Problem p;
+    const int rc = make_problem(0, k, 0, n, N, L, moduli, false, &p);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if (prepared_bytes < prepared_bytes_of(p)) return NIMBUS_COP_ERR_BUFFER_SIZE;
+    const hipError_t e = launch_prepare(p, ctW, prepared, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+size_t nimbus_cop_workspace_bytes(int m, int k, int x_bits)
+{
+    if (m < 1 || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 32) return 0;
+    return workspace_bytes_of(m, k, x_bits);
+}
+
+int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
+                               const void *prepared, int n, int N, int L,
+                               const uint64_t *moduli,
+                               const uint64_t *mask, uint64_t *out,
+                               void *workspace, size_t workspace_bytes,
+                               void *stream)
+{
+    if (!X || !prepared || !out || !workspace) return NIMBUS_COP_ERR_INVALID_ARG;
+    if ((((uintptr_t)prepared | (uintptr_t)workspace) & 15u) != 0)
+        return NIMBUS_COP_ERR_INVALID_ARG;
+    Problem p;
+    const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if (!mfma_supported(p)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
+    const hipError_t e = launch_cop_mfma(p, X, prepared, mask, out, workspace,
+                                         (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+const char *nimbus_cop_strerror(int status)
+{
+    switch (status) {
+    case NIMBUS_COP_OK: return "ok";
+    case NIMBUS_COP_ERR_INVALID_ARG: return "invalid argument (null pointer, size or modulus out of range)";
+    case NIMBUS_COP_ERR_UNSUPPORTED: return "parameters not supported by this entry point";
+    case NIMBUS_COP_ERR_LAUNCH: return "HIP kernel launch failed";
+    case NIMBUS_COP_ERR_BUFFER_SIZE: return "prepared or workspace buffer too small";
+    default: return "unknown status";
+    }
+}
+
+int nimbus_cop_version(void) { return 100; }
+
+}  // extern "C"

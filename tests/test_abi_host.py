@@ -1,0 +1,105 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol,
+and rejects bad arguments before anything reaches a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import cop_inputs as ci
+import paper_2411_15707_amd as nc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "nimbus_cop.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nimbus_cop_\w+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert declared_functions() == sorted(nc.EXPORTED_SYMBOLS)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(nc.lib_path())
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_version_and_strerror():
+    assert nc.nimbus_cop_version() >= 100
+    assert nc.nimbus_cop_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert nc.nimbus_cop_strerror(code)
+
+
+def test_size_queries():
+    cfg = ci.CONFIGS[3]
+    # 7 signed byte planes per residue (k padded to 32) + one column sum per column
+    want = (cfg.C // 32) * (cfg.k // 32) * 7 * 1024 + cfg.C * 8
+    assert nc.nimbus_cop_prepared_bytes(cfg.k, cfg.n, cfg.N, cfg.L, cfg.moduli) == want
+    assert nc.nimbus_cop_workspace_bytes(cfg.m, cfg.k, cfg.t_bits) == 4 * 24 * 3 * 1024
+    # ragged k and m round up to whole 32 x 32 tiles
+    assert nc.nimbus_cop_workspace_bytes(33, 65, 16) == 2 * 3 * 2 * 1024
+    assert nc.nimbus_cop_prepared_bytes(0, 8, 32, 1, (97,)) == 0
+    assert nc.nimbus_cop_workspace_bytes(0, 8, 16) == 0
+
+
+def _raw():
+    lib = nc.load_library()
+    return lib
+
+
+@pytest.mark.parametrize("kw", [
+    dict(m=0), dict(k=0), dict(n=0), dict(N=48), dict(N=16), dict(N=1 << 17), dict(L=0), dict(L=5),
+    dict(x_bits=0), dict(x_bits=33), dict(moduli=(1 << 54,)), dict(moduli=((1 << 62) + 1,)),
+    dict(moduli=(65537,), x_bits=20), dict(X=None), dict(ctW=None), dict(out=None),
+    dict(moduli=None),
+])
+def test_invalid_arguments_are_rejected_on_the_host(kw):
+    """every bad call returns INVALID_ARG without touching the (dummy, never dereferenced) pointers"""
+    lib = _raw()
+    a = dict(X=0x1000, m=4, k=8, x_bits=16, ctW=0x2000, n=32, N=32, L=1,
+             moduli=ci.limb_primes(50, 16, 1), mask=None, out=0x3000)
+    a.update(kw)
+    mod = None
+    if a["moduli"] is not None:
+        mod = (ctypes.c_uint64 * len(a["moduli"]))(*a["moduli"])
+    rc = lib.nimbus_cop_matmul(a["X"], a["m"], a["k"], a["x_bits"], a["ctW"], a["n"], a["N"],
+                               a["L"], mod, a["mask"], a["out"], None)
+    assert rc == -1
+    rc = lib.nimbus_cop_matmul_prepared(a["X"], a["m"], a["k"], a["x_bits"], a["ctW"], a["n"],
+                                        a["N"], a["L"], mod, a["mask"], a["out"], 0x4000, 1 << 30,
+                                        None)
+    assert rc == -1
+
+
+def test_prepared_path_limits_and_buffer_sizes():
+    lib = _raw()
+    mod = (ctypes.c_uint64 * 1)(*ci.limb_primes(54, 20, 1))
+    # k beyond the int32 accumulator bound of the matrix-core kernel
+    rc = lib.nimbus_cop_matmul_prepared(0x1000, 4, 50000, 20, 0x2000, 32, 32, 1, mod, None, 0x3000,
+                                        0x4000, 1 << 40, None)
+    assert rc == -2
+    # workspace too small
+    rc = lib.nimbus_cop_matmul_prepared(0x1000, 4, 64, 20, 0x2000, 32, 32, 1, mod, None, 0x3000,
+                                        0x4000, 16, None)
+    assert rc == -4
+    # misaligned buffers
+    rc = lib.nimbus_cop_matmul_prepared(0x1000, 4, 64, 20, 0x2008, 32, 32, 1, mod, None, 0x3000,
+                                        0x4000, 1 << 30, None)
+    assert rc == -1
+    rc = lib.nimbus_cop_prepare(0x1000, 64, 32, 32, 1, mod, 0x2000, 16, None)
+    assert rc == -4
+    rc = lib.nimbus_cop_prepare(None, 64, 32, 32, 1, mod, 0x2000, 1 << 30, None)
+    assert rc == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    from paper_2411_15707_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_HERE", str(tmp_path))
+    with pytest.raises(FileNotFoundError):
+        binding.load_library()

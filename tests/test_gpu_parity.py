@@ -1,0 +1,236 @@
+"""GPU parity: both C-ABI entry points against the CPU oracle, bit for bit.
+
+Integer work, so the bar is exact equality of every output word.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import cop_inputs as ci
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _inputs(seed, m, k, n, N, moduli, t_bits, with_mask=True):
+    Ch = -(-n // N)
+    X = ci.gen_X(seed, m, k, t_bits)
+    ctW = ci.gen_ctW_uniform(seed, k, Ch, moduli, N)
+    mask = ci.gen_mask_uniform(seed, m, Ch, moduli, N) if with_mask else None
+    return X, ctW, mask
+
+
+def _check_both(oracle, X, ctW, moduli, n, N, x_bits, mask, label):
+    import gpu_util as gu
+    want, _ = oracle.cop_ref(X, ctW, moduli, n, N, mask)
+    _say(f"[parity] {label}: valu kernel")
+    got = gu.run_valu(X, ctW, moduli, n, N, x_bits, mask)
+    assert got.shape == want.shape
+    assert np.array_equal(got, want), "valu: " + gu.first_mismatch(got, want)
+    _say(f"[parity] {label}: matrix-core kernel")
+    got = gu.run_mfma(X, ctW, moduli, n, N, x_bits, mask)
+    assert np.array_equal(got, want), "mfma: " + gu.first_mismatch(got, want)
+    return want
+
+
+# m, k, n, N, L, t_bits, q_bits
+SMALL = [
+    (8, 64, 64, 1024, 1, 16, 50),       # config 1 shape
+    (5, 7, 32, 32, 1, 16, 50),          # k and m far below one tile
+    (33, 100, 40, 64, 2, 20, 54),       # ragged m and k (33 rows, 100 = 3*32 + 4)
+    (130, 131, 64, 64, 2, 20, 54),      # two row blocks, ragged k, several k stages + tail
+    (64, 300, 2500, 1024, 1, 20, 54),   # n > N: three ring chunks, last partial
+    (40, 96, 128, 128, 3, 24, 55),      # three limbs, 24-bit shares
+    (17, 70, 64, 64, 1, 32, 62),        # widest shares and modulus: 4 x 8 byte planes
+    (20, 257, 64, 64, 2, 9, 40),        # small modulus, odd share width
+    (1, 1, 32, 32, 1, 16, 50),          # k = 1, m = 1
+]
+
+
+@pytest.mark.parametrize("m,k,n,N,L,t_bits,q_bits", SMALL)
+def test_small_and_ragged_shapes(oracle, m, k, n, N, L, t_bits, q_bits):
+    moduli = ci.limb_primes(q_bits, t_bits, L)
+    X, ctW, mask = _inputs(1000 + m + k, m, k, n, N, moduli, t_bits)
+    # extremes: largest share, largest residues in a few places
+    X[0, 0] = (1 << t_bits) - 1
+    X[-1, -1] = (1 << t_bits) - 1
+    for l, q in enumerate(moduli):
+        ctW[:, 0, :, l, :4] = q - 1
+        mask[0, 0, :, l, :4] = q - 1
+    _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, f"small m={m} k={k} n={n} N={N} L={L}")
+    _check_both(oracle, X, ctW, moduli, n, N, t_bits, None, f"small/no-mask m={m} k={k}")
+
+
+def test_all_maximal_operands(oracle):
+    """every share t-1 and every residue q-1: the largest sums the accumulators can see"""
+    m, k, n, N, L, t_bits = 32, 512, 64, 64, 2, 24
+    moduli = ci.limb_primes(55, t_bits, L)
+    qv = np.array(moduli, dtype=np.uint64).reshape(1, 1, 1, L, 1)
+    X = np.full((m, k), (1 << t_bits) - 1, dtype=np.uint64)
+    ctW = np.broadcast_to(qv - np.uint64(1), (k, 1, 2, L, N)).copy()
+    mask = np.broadcast_to(qv - np.uint64(1), (m, 1, 2, L, N)).copy()
+    _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, "maximal")
+    # residues just above and below q/2 exercise both branches of the centring
+    half = (qv - np.uint64(1)) // np.uint64(2)
+    ctW[::2] = np.broadcast_to(half, (1, 2, L, N))
+    ctW[1::2] = np.broadcast_to(half + np.uint64(1), (1, 2, L, N))
+    _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, "half-modulus")
+    X[:] = 0
+    _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, "zero shares")
+
+
+def test_special_cases_on_gpu(oracle):
+    import gpu_util as gu
+    m = k = 48
+    n = N = 64
+    L, t_bits = 2, 20
+    moduli = ci.limb_primes(54, t_bits, L)
+    _, ctW, mask = _inputs(5, m, k, n, N, moduli, t_bits)
+    qv = np.array(moduli, dtype=np.uint64).reshape(1, 1, 1, L, 1)
+    for run in (gu.run_valu, gu.run_mfma):
+        out = run(np.zeros((m, k), np.uint64), ctW, moduli, n, N, t_bits, mask)
+        assert np.array_equal(out, mask)                         # X = 0: the mask
+        out = run(np.eye(m, dtype=np.uint64), ctW, moduli, n, N, t_bits, mask)
+        s = ctW + mask
+        assert np.array_equal(out, np.where(s >= qv, s - qv, s))   # X = I: vector add mod q
+        out = run(np.eye(m, dtype=np.uint64), ctW, moduli, n, N, t_bits, None)
+        assert np.array_equal(out, ctW)                          # X = I, no mask: a copy
+
+
+def test_config1_real_encryption_and_decrypt_invariant(oracle):
+    """config 1 in full: weights encrypted for real, GPU output decrypted, Dec(out_j) + R_j
+    must equal (X W)_j mod t (Algorithm 1, output condition)"""
+    import gpu_util as gu
+    cfg = ci.CONFIGS[1]
+    seed = ci.config_seed(1)
+    t = cfg.t
+    X = ci.gen_X(seed, cfg.m, cfg.k, cfg.t_bits)
+    W = ci.gen_W(seed, cfg.k, cfg.n, cfg.t_bits)
+    s = ci.gen_secret(seed, cfg.N)
+    a, e = ci.gen_enc_randomness(seed, cfg.k, 1, cfg.moduli, cfg.N)
+    R = ci.gen_R(seed, cfg.m, cfg.N, cfg.t_bits)
+    w_hat = oracle.encode_rows(W, cfg.N)
+    ct = oracle.encrypt(w_hat[:, 0], s, a[:, 0], e[:, 0], cfg.moduli, cfg.t_bits)
+    ctW = ct.reshape(cfg.k, 1, 2, cfg.L, cfg.N)
+    mask = np.stack([oracle.share_mask(R[j], cfg.moduli, cfg.t_bits)[None] for j in range(cfg.m)])
+    want, _ = oracle.cop_ref(X, ctW, cfg.moduli, cfg.n, cfg.N, mask)
+    XW = X.astype(object) @ W.astype(object)
+    for run in (gu.run_valu, gu.run_mfma):
+        out = run(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask)
+        assert np.array_equal(out, want)
+        for j in range(cfg.m):
+            dec = oracle.decrypt(out[j, 0], s, cfg.moduli, cfg.t_bits)
+            got = (dec + R[j]) % np.uint64(t)
+            assert np.array_equal(got[:cfg.n], (XW[j] % t).astype(np.uint64))
+            assert (got[cfg.n:] == 0).all()
+
+
+@pytest.mark.parametrize("cfg_id", [2, 3, 4])
+def test_bert_base_configs_full(oracle, cfg_id):
+    """configs 2-4 at full size, every output word compared"""
+    cfg = ci.CONFIGS[cfg_id]
+    seed = ci.config_seed(cfg_id)
+    _say(f"[parity] config {cfg_id}: generating inputs")
+    X, ctW, mask = _inputs(seed, cfg.m, cfg.k, cfg.n, cfg.N, cfg.moduli, cfg.t_bits)
+    _check_both(oracle, X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask, f"config {cfg_id}")
+
+
+def test_config3_real_encryption_spot_check(oracle):
+    """config 3 shape with every weight row encrypted for real; four output rows of the
+    GPU result are decrypted and compared with the brute-force X W mod t"""
+    import gpu_util as gu
+    cfg = ci.CONFIGS[3]
+    seed = ci.config_seed(3) + 500
+    t = cfg.t
+    rows = [0, 1, cfg.m // 2, cfg.m - 1]
+    X = ci.gen_X(seed, cfg.m, cfg.k, cfg.t_bits)
+    W = ci.gen_W(seed, cfg.k, cfg.n, cfg.t_bits)
+    s = ci.gen_secret(seed, cfg.N)
+    a, e = ci.gen_enc_randomness(seed, cfg.k, 1, cfg.moduli, cfg.N)
+    R = ci.gen_R(seed, cfg.m, cfg.N, cfg.t_bits)
+    _say("[parity] config 3 real encryption: encrypting 768 rows on the CPU")
+    ct = oracle.encrypt(oracle.encode_rows(W, cfg.N)[:, 0], s, a[:, 0], e[:, 0], cfg.moduli,
+                        cfg.t_bits)
+    ctW = ct.reshape(cfg.k, 1, 2, cfg.L, cfg.N)
+    mask = ci.gen_mask_uniform(seed, cfg.m, 1, cfg.moduli, cfg.N)
+    for j in rows:
+        mask[j, 0] = oracle.share_mask(R[j], cfg.moduli, cfg.t_bits)
+    _say("[parity] config 3 real encryption: matrix-core kernel")
+    out = gu.run_mfma(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask)
+    XW = X[rows].astype(object) @ W.astype(object)
+    for r, j in enumerate(rows):
+        dec, noise = oracle.decrypt(out[j, 0], s, cfg.moduli, cfg.t_bits, with_noise=True)
+        got = (dec + R[j]) % np.uint64(t)
+        assert np.array_equal(got[:cfg.n], (XW[r] % t).astype(np.uint64))
+        assert (got[cfg.n:] == 0).all()
+        assert np.abs(noise).max() <= cfg.k * t * 20
+
+
+def test_config5_layer_stack_on_one_stream(oracle):
+    """config 5: 12 back-to-back calls with distinct inputs on one stream, no host
+    synchronisation in between; four rows of every call compared over all columns"""
+    import torch
+    import paper_2411_15707_amd as nc
+    import gpu_util as gu
+    cfg = ci.CONFIGS[5]
+    rows = [0, 129, 300, cfg.m - 1]
+    stream = torch.cuda.Stream()
+    ws = torch.empty(nc.nimbus_cop_workspace_bytes(cfg.m, cfg.k, cfg.t_bits), dtype=torch.uint8,
+                     device="cuda")
+    held = []
+    for call in range(cfg.calls):
+        seed = ci.config_seed(5, call)
+        _say(f"[parity] config 5 call {call}: inputs + oracle rows")
+        X, ctW, mask = _inputs(seed, cfg.m, cfg.k, cfg.n, cfg.N, cfg.moduli, cfg.t_bits)
+        want, _ = oracle.cop_ref(X[rows], ctW, cfg.moduli, cfg.n, cfg.N, mask[rows])
+        prepared = gu.prepare(ctW, cfg.moduli, cfg.n, cfg.N)
+        dX, dM = gu.dev(X), gu.dev(mask)
+        out = torch.full((cfg.m, cfg.Ch, 2, cfg.L, cfg.N), -1, dtype=torch.int64, device="cuda")
+        held.append((dX, prepared, dM, out, want))
+        del ctW, mask
+    torch.cuda.synchronize()
+    _say("[parity] config 5: launching 12 calls back to back")
+    with torch.cuda.stream(stream):
+        for dX, prepared, dM, out, _ in held:
+            nc.nimbus_cop_matmul_prepared(dX, cfg.m, cfg.k, cfg.t_bits, prepared, cfg.n, cfg.N,
+                                          cfg.L, cfg.moduli, dM, out, ws, stream)
+    stream.synchronize()
+    for call, (_, _, _, out, want) in enumerate(held):
+        got = gu.host(out[rows])
+        assert np.array_equal(got, want), f"call {call}: " + gu.first_mismatch(got, want)
+    # the canonical-layout kernel on the last call's shape, same rows
+    seed = ci.config_seed(5, cfg.calls - 1)
+    X, ctW, mask = _inputs(seed, cfg.m, cfg.k, cfg.n, cfg.N, cfg.moduli, cfg.t_bits)
+    _say("[parity] config 5: valu kernel, last call")
+    got = gu.run_valu(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask)
+    assert np.array_equal(got[rows], held[-1][4])
+
+
+def test_repeat_runs_are_identical(oracle):
+    """integer sums are order independent: two runs that differ point at a race"""
+    import gpu_util as gu
+    cfg = ci.CONFIGS[2]
+    X, ctW, mask = _inputs(42, cfg.m, 256, cfg.n, cfg.N, cfg.moduli, cfg.t_bits)
+    prepared = gu.prepare(ctW, cfg.moduli, cfg.n, cfg.N)
+    a = gu.run_mfma(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask, prepared)
+    b = gu.run_mfma(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask, prepared)
+    assert np.array_equal(a, b)
+
+
+def test_errors_leave_out_untouched():
+    import torch
+    import paper_2411_15707_amd as nc
+    moduli = ci.limb_primes(50, 16, 1)
+    X = torch.zeros((4, 8), dtype=torch.int64, device="cuda")
+    ctW = torch.zeros((8, 1, 2, 1, 32), dtype=torch.int64, device="cuda")
+    out = torch.full((4, 1, 2, 1, 32), 7, dtype=torch.int64, device="cuda")
+    with pytest.raises(nc.NimbusCopError) as ei:
+        nc.nimbus_cop_matmul(X, 4, 8, 16, ctW, 32, 32, 1, (moduli[0] + 1,), None, out)
+    assert ei.value.status == -1
+    torch.cuda.synchronize()
+    assert (out == 7).all()
