@@ -77,8 +77,8 @@ def test_all_maximal_operands(oracle):
     _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, "maximal")
     # residues just above and below q/2 exercise both branches of the centring
     half = (qv - np.uint64(1)) // np.uint64(2)
-    ctW[::2] = np.broadcast_to(half, (1, 2, L, N))
-    ctW[1::2] = np.broadcast_to(half + np.uint64(1), (1, 2, L, N))
+    ctW[::2] = half
+    ctW[1::2] = half + np.uint64(1)
     _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, "half-modulus")
     X[:] = 0
     _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, "zero shares")
