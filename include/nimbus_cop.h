@@ -94,13 +94,30 @@ int nimbus_cop_prepare(const uint64_t *ctW, int k, int n, int N, int L,
 /*
  * COP accumulation + mask on prepared weights (same result, bit for bit, as
  * nimbus_cop_matmul on the ctW the buffer was prepared from, same k, n, N, L
- * and moduli).  Runs the int8 matrix-core kernel.
- *   workspace  device scratch of at least nimbus_cop_workspace_bytes(m, k,
- *              x_bits) bytes, 16-byte aligned; holds the byte planes of X for
- *              the duration of the call.
- * Additional limits (NIMBUS_COP_ERR_UNSUPPORTED beyond them): k <= 32767.
+ * and moduli).  Runs the int8 matrix-core kernel.  Two steps, and a call that
+ * enqueues both:
+ *
+ *   nimbus_cop_stage_shares    X -> signed byte planes in matrix-core tile
+ *                              order, written to `workspace` (the client's
+ *                              shares are used as plain scalars, Section 3.2
+ *                              "Row-wise Encoding"; this is only a re-layout)
+ *   nimbus_cop_matmul_staged   Algorithm 1 step 2 + step 4 from staged shares
+ *                              and prepared weights
+ *   nimbus_cop_matmul_prepared stage_shares then matmul_staged on `stream`
+ *
+ *   workspace  device buffer of at least nimbus_cop_workspace_bytes(m, k,
+ *              x_bits) bytes, 16-byte aligned; holds the byte planes of X.
+ *              (0 is returned for invalid parameters.)
+ * Additional limit (NIMBUS_COP_ERR_UNSUPPORTED beyond it): k <= 32767, so that
+ * the int32 accumulators of the byte products cannot overflow.
  */
 size_t nimbus_cop_workspace_bytes(int m, int k, int x_bits);
+int nimbus_cop_stage_shares(const uint64_t *X, int m, int k, int x_bits,
+                            void *workspace, size_t workspace_bytes, void *stream);
+int nimbus_cop_matmul_staged(const void *staged_shares, int m, int k, int x_bits,
+                             const void *prepared, int n, int N, int L,
+                             const uint64_t *moduli,
+                             const uint64_t *mask, uint64_t *out, void *stream);
 int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
                                const void *prepared, int n, int N, int L,
                                const uint64_t *moduli,

@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     load_library,
     nimbus_cop_matmul,
     nimbus_cop_matmul_prepared,
+    nimbus_cop_matmul_staged,
+    nimbus_cop_stage_shares,
     nimbus_cop_prepare,
     nimbus_cop_prepared_bytes,
     nimbus_cop_strerror,

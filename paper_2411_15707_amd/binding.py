@@ -18,6 +18,8 @@ EXPORTED_SYMBOLS = (
     "nimbus_cop_prepared_bytes",
     "nimbus_cop_prepare",
     "nimbus_cop_workspace_bytes",
+    "nimbus_cop_stage_shares",
+    "nimbus_cop_matmul_staged",
     "nimbus_cop_matmul_prepared",
     "nimbus_cop_strerror",
     "nimbus_cop_version",
@@ -54,6 +56,10 @@ def load_library():
     lib.nimbus_cop_prepare.argtypes = [vp, ci, ci, ci, ci, vp, vp, sz, vp]
     lib.nimbus_cop_workspace_bytes.restype = sz
     lib.nimbus_cop_workspace_bytes.argtypes = [ci, ci, ci]
+    lib.nimbus_cop_stage_shares.restype = ci
+    lib.nimbus_cop_stage_shares.argtypes = [vp, ci, ci, ci, vp, sz, vp]
+    lib.nimbus_cop_matmul_staged.restype = ci
+    lib.nimbus_cop_matmul_staged.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.nimbus_cop_matmul_prepared.restype = ci
     lib.nimbus_cop_matmul_prepared.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
     lib.nimbus_cop_strerror.restype = ctypes.c_char_p
@@ -140,6 +146,32 @@ def nimbus_cop_prepare(ctW, k, n, N, L, moduli, prepared, stream=None):
 
 def nimbus_cop_workspace_bytes(m, k, x_bits) -> int:
     return int(load_library().nimbus_cop_workspace_bytes(m, k, x_bits))
+
+
+def nimbus_cop_stage_shares(X, m, k, x_bits, workspace, stream=None):
+    lib = load_library()
+    _words(X, "X", m * k)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    rc = lib.nimbus_cop_stage_shares(_dev_ptr(X, "X"), m, k, x_bits,
+                                     _dev_ptr(workspace, "workspace"), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_stage_shares")
+
+
+def nimbus_cop_matmul_staged(staged, m, k, x_bits, prepared, n, N, L, moduli, mask, out,
+                             stream=None):
+    lib = load_library()
+    C = _columns(n, N, L)
+    _words(out, "out", m * C)
+    if mask is not None:
+        _words(mask, "mask", m * C)
+    if staged.numel() * staged.element_size() < nimbus_cop_workspace_bytes(m, k, x_bits):
+        raise ValueError("staged shares buffer is smaller than nimbus_cop_workspace_bytes")
+    rc = lib.nimbus_cop_matmul_staged(
+        _dev_ptr(staged, "staged"), m, k, x_bits, _dev_ptr(prepared, "prepared"), n, N, L,
+        _moduli(moduli), _dev_ptr(mask, "mask", True), _dev_ptr(out, "out"), _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_matmul_staged")
 
 
 def nimbus_cop_matmul_prepared(X, m, k, x_bits, prepared, n, N, L, moduli, mask, out,

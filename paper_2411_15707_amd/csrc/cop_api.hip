@@ -112,6 +112,38 @@ size_t nimbus_cop_workspace_bytes(int m, int k, int x_bits)
     return workspace_bytes_of(m, k, x_bits);
 }
 
+int nimbus_cop_stage_shares(const uint64_t *X, int m, int k, int x_bits,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!X || !workspace || ((uintptr_t)workspace & 15u) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (m < 1 || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 32)
+        return NIMBUS_COP_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
+    Problem p{};
+    p.m = m;
+    p.k = k;
+    p.x_bits = x_bits;
+    const hipError_t e = launch_stage_shares(p, X, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+int nimbus_cop_matmul_staged(const void *staged_shares, int m, int k, int x_bits,
+                             const void *prepared, int n, int N, int L,
+                             const uint64_t *moduli,
+                             const uint64_t *mask, uint64_t *out, void *stream)
+{
+    if (!staged_shares || !prepared || !out) return NIMBUS_COP_ERR_INVALID_ARG;
+    if ((((uintptr_t)prepared | (uintptr_t)staged_shares) & 15u) != 0)
+        return NIMBUS_COP_ERR_INVALID_ARG;
+    Problem p;
+    const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if (!mfma_supported(p)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    const hipError_t e = launch_cop_mfma(p, staged_shares, prepared, mask, out,
+                                         (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
 int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
                                const void *prepared, int n, int N, int L,
                                const uint64_t *moduli,
@@ -127,8 +159,9 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
     if (rc != NIMBUS_COP_OK) return rc;
     if (!mfma_supported(p)) return NIMBUS_COP_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
-    const hipError_t e = launch_cop_mfma(p, X, prepared, mask, out, workspace,
-                                         (hipStream_t)stream);
+    hipError_t e = launch_stage_shares(p, X, workspace, (hipStream_t)stream);
+    if (e != hipSuccess) return NIMBUS_COP_ERR_LAUNCH;
+    e = launch_cop_mfma(p, workspace, prepared, mask, out, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 

@@ -343,23 +343,37 @@ hipError_t launch_prepare(const Problem &p, const uint64_t *ctW, void *prepared,
     return prepare_impl<8>(p, ctW, prepared, stream);
 }
 
-template <int DX, int DQ>
-static hipError_t mfma_impl(const Problem &p, const uint64_t *X, const void *prepared,
-                            const uint64_t *mask, uint64_t *out, void *workspace,
-                            hipStream_t stream)
+template <int DX>
+static hipError_t stage_impl(const Problem &p, const uint64_t *X, void *workspace,
+                             hipStream_t stream)
 {
     const int KB = (p.k + kTile - 1) / kTile;
     const int RT = (p.m + kTile - 1) / kTile;
-    const uint32_t CT = (uint32_t)(p.C / kTile);
-
     const uint32_t xtotal = (uint32_t)RT * KB * 64;
     hipLaunchKernelGGL(x_planes_kernel<DX>, dim3((xtotal + 255) / 256), dim3(256), 0, stream,
                        X, p.m, p.k, KB, xtotal, (uint4 *)workspace);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_stage_shares(const Problem &p, const uint64_t *X, void *workspace,
+                               hipStream_t stream)
+{
+    switch (planes_x(p.x_bits)) {
+    case 2: return stage_impl<2>(p, X, workspace, stream);
+    case 3: return stage_impl<3>(p, X, workspace, stream);
+    default: return stage_impl<4>(p, X, workspace, stream);
+    }
+}
+
+template <int DX, int DQ>
+static hipError_t mfma_impl(const Problem &p, const void *staged, const void *prepared,
+                            const uint64_t *mask, uint64_t *out, hipStream_t stream)
+{
+    const int KB = (p.k + kTile - 1) / kTile;
+    const uint32_t CT = (uint32_t)(p.C / kTile);
 
     MfmaArgs a{};
-    a.xd = (const uint4 *)workspace;
+    a.xd = (const uint4 *)staged;
     a.planes = (const uint4 *)prepared;
     a.colsum = (const uint64_t *)((const char *)prepared + (size_t)CT * KB * DQ * kTileBytes);
     a.mask = mask;
@@ -385,13 +399,12 @@ static hipError_t mfma_impl(const Problem &p, const uint64_t *X, const void *pre
     return hipGetLastError();
 }
 
-hipError_t launch_cop_mfma(const Problem &p, const uint64_t *X, const void *prepared,
-                           const uint64_t *mask, uint64_t *out, void *workspace,
-                           hipStream_t stream)
+hipError_t launch_cop_mfma(const Problem &p, const void *staged, const void *prepared,
+                           const uint64_t *mask, uint64_t *out, hipStream_t stream)
 {
     const int DX = planes_x(p.x_bits), DQ = planes_q(p.q_bits_max);
 #define NIMBUS_CASE(dx, dq) \
-    if (DX == dx && DQ == dq) return mfma_impl<dx, dq>(p, X, prepared, mask, out, workspace, stream);
+    if (DX == dx && DQ == dq) return mfma_impl<dx, dq>(p, staged, prepared, mask, out, stream);
     NIMBUS_CASE(2, 7)
     NIMBUS_CASE(3, 7)
     NIMBUS_CASE(4, 7)

@@ -234,3 +234,22 @@ def test_errors_leave_out_untouched():
     assert ei.value.status == -1
     torch.cuda.synchronize()
     assert (out == 7).all()
+
+
+def test_two_step_entry_points_match_the_fused_call(oracle):
+    """nimbus_cop_stage_shares + nimbus_cop_matmul_staged == nimbus_cop_matmul_prepared == oracle"""
+    import torch
+    import paper_2411_15707_amd as nc
+    import gpu_util as gu
+    m, k, n, N, L, t_bits = 70, 200, 128, 128, 2, 20
+    moduli = ci.limb_primes(54, t_bits, L)
+    X, ctW, mask = _inputs(77, m, k, n, N, moduli, t_bits)
+    want, _ = oracle.cop_ref(X, ctW, moduli, n, N, mask)
+    prepared = gu.prepare(ctW, moduli, n, N)
+    ws = torch.empty(nc.nimbus_cop_workspace_bytes(m, k, t_bits), dtype=torch.uint8, device="cuda")
+    out = torch.full((m, 1, 2, L, N), -1, dtype=torch.int64, device="cuda")
+    nc.nimbus_cop_stage_shares(gu.dev(X), m, k, t_bits, ws)
+    nc.nimbus_cop_matmul_staged(ws, m, k, t_bits, prepared, n, N, L, moduli, gu.dev(mask), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(gu.host(out), want)
+    assert np.array_equal(gu.run_mfma(X, ctW, moduli, n, N, t_bits, mask, prepared), want)
