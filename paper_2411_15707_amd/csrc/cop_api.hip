@@ -54,7 +54,7 @@ static int make_problem(int m, int k, int x_bits, int n, int N, int L,
 static size_t prepared_bytes_of(const Problem &p)
 {
     const size_t CT = p.C / kTile;
-    const size_t KB = (size_t)(p.k + kTile - 1) / kTile;
+    const size_t KB = (size_t)kblocks(p.k);
     const size_t DQ = (size_t)planes_q(p.q_bits_max);
     return CT * KB * DQ * kTileBytes + p.C * sizeof(uint64_t);
 }
@@ -62,7 +62,7 @@ static size_t prepared_bytes_of(const Problem &p)
 static size_t workspace_bytes_of(int m, int k, int x_bits)
 {
     const size_t RT = (size_t)(m + kTile - 1) / kTile;
-    const size_t KB = (size_t)(k + kTile - 1) / kTile;
+    const size_t KB = (size_t)kblocks(k);
     return RT * KB * (size_t)planes_x(x_bits) * kTileBytes;
 }
 

@@ -52,6 +52,8 @@ inline int planes_x(int x_bits) { const int d = (x_bits + 7) / 8; return d < 2 ?
 inline int planes_q(int q_bits) { const int d = (q_bits + 1 + 7) / 8; return d < 7 ? 7 : d; }
 constexpr int kTile = 32;            // rows / columns / k per matrix-core tile
 constexpr int kTileBytes = 1024;     // one 32 x 32 int8 operand tile
+// k is padded with zero byte planes to whole 32-value k-blocks
+inline int kblocks(int k) { return (k + kTile - 1) / kTile; }
 
 // launchers implemented in the kernel files; all return hipError_t
 hipError_t launch_cop_valu(const Problem &p, const uint64_t *X, const uint64_t *ctW,

@@ -26,6 +26,7 @@
 // use the same lane/byte -> k mapping, so any fixed assignment of k-slots to
 // actual k indices gives the same sum as long as both sides share it.
 #include "cop_common.hpp"
+#include <type_traits>
 
 namespace nimbus {
 
@@ -155,19 +156,84 @@ struct MfmaArgs {
     uint64_t bias_hi[kMaxLimbs], bias_lo[kMaxLimbs];   // q_l << sh
 };
 
-constexpr int KS = 4;         // k-blocks (of 32) per LDS stage
+#define NIMBUS_AS1 __attribute__((address_space(1)))
+#define NIMBUS_AS3 __attribute__((address_space(3)))
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// 16 bytes per lane from LDS byte address addr + OFF
+template <int OFF>
+__device__ __forceinline__ v4i lds_read_b128(uint32_t addr)
+{
+    v4i r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+    return r;
+}
+
+// wait until at most PENDING of this wave's LDS reads are outstanding; tied to the
+// register that the oldest still-awaited read fills so that its users stay behind it
+template <int PENDING>
+__device__ __forceinline__ void wait_lds(v4i &x)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(PENDING) : "memory");
+}
+
+// wait until at most PENDING of this wave's global loads (here: direct-to-LDS loads) are
+// outstanding
+template <int PENDING>
+__device__ __forceinline__ void wait_vmem()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
+}
+
+// one wave copies 64 x 16 B (a whole operand tile) or 64 x 4 B (a quarter tile) from
+// global memory straight into LDS; lane l's bytes land at dst + l*16 (resp. l*4)
+__device__ __forceinline__ void dma_tile(const void *src_lane, void *dst_wave)
+{
+    __builtin_amdgcn_global_load_lds((const NIMBUS_AS1 void *)src_lane,
+                                     (NIMBUS_AS3 void *)dst_wave, 16, 0, 0);
+}
+__device__ __forceinline__ void dma_quarter(const void *src_lane, void *dst_wave)
+{
+    __builtin_amdgcn_global_load_lds((const NIMBUS_AS1 void *)src_lane,
+                                     (NIMBUS_AS3 void *)dst_wave, 4, 0, 0);
+}
+
+// The pipeline: a stage is one k-block (32 values of k): the workgroup's 4*DX operand
+// tiles of X and the DQ operand tiles of the ciphertext planes, STAGE_TILES KB in all.
+// Stages live in a ring of RING LDS buffers filled by direct-to-LDS loads issued
+// RING-1 stages ahead; nothing passes through registers on the way in.  Every wave
+// issues the same number of loads per stage (its own DX tiles of X, one whole ciphertext
+// tile, and a quarter of each remaining ciphertext tile), so "stage s has landed" is the
+// wait "at most (stages issued after s) * LOADS loads pending" followed by the barrier.
+template <int DX, int DQ>
+struct Pipe {
+    static constexpr int A_TILES = 4 * DX;
+    static constexpr int STAGE_TILES = A_TILES + DQ;
+    static constexpr int STAGE_BYTES = STAGE_TILES * kTileBytes;
+    static constexpr int RING = (4 * STAGE_BYTES <= 80 * 1024) ? 4 : 3;
+    static constexpr int LOADS = DX + 1 + (DQ - 4);
+    static_assert(DQ >= 4, "each of the four waves moves one whole ciphertext tile");
+};
 
 template <int DX, int DQ>
-__global__ __launch_bounds__(256) void cop_mfma_kernel(const MfmaArgs a)
+__global__ __launch_bounds__(256, 2) void cop_mfma_kernel(const MfmaArgs a)
 {
+    using P_ = Pipe<DX, DQ>;
     constexpr int ND = DX + DQ - 1;
-    constexpr int STAGE = KS * DQ * 64;             // uint4 per stage
-    constexpr int PER_THREAD = STAGE / 256;         // = DQ for KS = 4
-    static_assert(STAGE % 256 == 0, "stage must split evenly over the workgroup");
-    __shared__ uint4 ldsB[2][STAGE];
+    constexpr int RING = P_::RING;
+    constexpr int LOADS = P_::LOADS;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[RING * P_::STAGE_BYTES];
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     // workgroup -> (column tile, row block).  Workgroups are dealt round-robin to
     // the 8 XCDs; the RB row blocks that share a column tile are kept on one XCD
@@ -186,10 +252,27 @@ __global__ __launch_bounds__(256) void cop_mfma_kernel(const MfmaArgs a)
     }
     const int rt = (int)rb * 4 + wave;
     const bool active = rt * kTile < a.m;           // wave-uniform
+    // a wave without rows still moves its share of every stage (reading the last real
+    // row tile in place of its own) so that all waves count the same loads
+    const int rt_load = active ? rt : (a.m - 1) / kTile;
 
     const int KB = a.KB;
-    const uint4 *gB = a.planes + (size_t)ct * KB * (DQ * 64);
-    const uint4 *gA = a.xd + (size_t)rt * KB * (DX * 64) + lane;   // dereferenced only if active
+    const unsigned char *gA = (const unsigned char *)(a.xd + (size_t)rt_load * KB * (DX * 64));
+    const unsigned char *gB = (const unsigned char *)(a.planes + (size_t)ct * KB * (DQ * 64));
+
+    auto issue = [&](int kb, int buf) {
+        unsigned char *dst = lds + buf * P_::STAGE_BYTES;
+        const unsigned char *srcA = gA + (size_t)kb * (DX * kTileBytes);
+        const unsigned char *srcB = gB + (size_t)kb * (DQ * kTileBytes);
+#pragma unroll
+        for (int d = 0; d < DX; ++d)
+            dma_tile(srcA + d * kTileBytes + lane * 16, dst + (wave * DX + d) * kTileBytes);
+        dma_tile(srcB + wave * kTileBytes + lane * 16, dst + (P_::A_TILES + wave) * kTileBytes);
+#pragma unroll
+        for (int d = 4; d < DQ; ++d)
+            dma_quarter(srcB + d * kTileBytes + wave * 256 + lane * 4,
+                        dst + (P_::A_TILES + d) * kTileBytes + wave * 256);
+    };
 
     v16i acc[ND];
 #pragma unroll
@@ -197,75 +280,59 @@ __global__ __launch_bounds__(256) void cop_mfma_kernel(const MfmaArgs a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[d][r] = 0;
 
-    const int nstages = (KB + KS - 1) / KS;
-    const int total_u4 = KB * DQ * 64;              // uint4 of B for this column tile
-
-    // prologue: stage 0 -> LDS buffer 0
-    {
+    // Operands come out of LDS through explicit ds_read_b128 instructions: reads the
+    // compiler can see would each be made to wait for every direct-to-LDS load in
+    // flight.  All reads of a k-block are issued at once; the matrix-core work on
+    // ciphertext plane dq starts as soon as that plane is back.
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(NIMBUS_AS3 void *)&lds[0];
+    const uint32_t laneA = lds0 + (uint32_t)(wave * DX) * kTileBytes + (uint32_t)lane * 16u;
+    const uint32_t laneB = lds0 + (uint32_t)P_::A_TILES * kTileBytes + (uint32_t)lane * 16u;
+    auto compute = [&](int buf) {
+        const uint32_t off = (uint32_t)buf * P_::STAGE_BYTES;
+        v4i xa[DX], b[DQ];
+        static_for<0, DX>([&](auto d_c) {
+            constexpr int d = decltype(d_c)::value;
+            xa[d] = lds_read_b128<d * kTileBytes>(laneA + off);
+        });
+        static_for<0, DQ>([&](auto d_c) {
+            constexpr int d = decltype(d_c)::value;
+            b[d] = lds_read_b128<d * kTileBytes>(laneB + off);
+        });
+        static_for<0, DQ>([&](auto dq_c) {
+            constexpr int dq = decltype(dq_c)::value;
+            wait_lds<DQ - 1 - dq>(b[dq]);
+            if constexpr (dq == 0) {
 #pragma unroll
-        for (int u = 0; u < PER_THREAD; ++u) {
-            const int idx = u * 256 + (int)threadIdx.x;
-            if (idx < total_u4) ldsB[0][idx] = gB[idx];
-        }
-    }
-    v4i a_nxt[DX];
-    if (active) {
-#pragma unroll
-        for (int d = 0; d < DX; ++d) {
-            const uint4 t = gA[d * 64];
-            a_nxt[d] = (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w};
-        }
-    }
-    __syncthreads();
-
-    for (int s = 0; s < nstages; ++s) {
-        const int buf = s & 1;
-        // global loads of the next stage, kept in registers until this stage is consumed
-        uint4 stg[PER_THREAD];
-        const int next_base = (s + 1) * STAGE;
-#pragma unroll
-        for (int u = 0; u < PER_THREAD; ++u) {
-            const int idx = next_base + u * 256 + (int)threadIdx.x;
-            if (idx < total_u4) stg[u] = gB[idx];
-        }
-
-        if (active) {
-            const int kb_end = (s * KS + KS < KB) ? KS : (KB - s * KS);
-            for (int kk = 0; kk < kb_end; ++kk) {
-                v4i a_cur[DX];
-#pragma unroll
-                for (int d = 0; d < DX; ++d) a_cur[d] = a_nxt[d];
-                const int kb_next = s * KS + kk + 1;
-                if (kb_next < KB) {
-#pragma unroll
-                    for (int d = 0; d < DX; ++d) {
-                        const uint4 t = gA[((size_t)kb_next * DX + d) * 64];
-                        a_nxt[d] = (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w};
-                    }
-                }
-                v4i b[DQ];
-#pragma unroll
-                for (int d = 0; d < DQ; ++d) {
-                    const uint4 t = ldsB[buf][(kk * DQ + d) * 64 + lane];
-                    b[d] = (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w};
-                }
-#pragma unroll
-                for (int dq = 0; dq < DQ; ++dq)
-#pragma unroll
-                    for (int dx = 0; dx < DX; ++dx)
-                        acc[dx + dq] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                            a_cur[dx], b[dq], acc[dx + dq], 0, 0, 0);
+                for (int dx = 0; dx < DX; ++dx) asm volatile("" : "+v"(xa[dx]));
             }
-        }
-
 #pragma unroll
-        for (int u = 0; u < PER_THREAD; ++u) {
-            const int idx = next_base + u * 256 + (int)threadIdx.x;
-            if (idx < total_u4) ldsB[buf ^ 1][idx - next_base] = stg[u];
-        }
-        __syncthreads();
-    }
+            for (int dx = 0; dx < DX; ++dx)
+                acc[dx + dq] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                    xa[dx], b[dq], acc[dx + dq], 0, 0, 0);
+        });
+    };
 
+    // prologue: stages 0 .. RING-2
+#pragma unroll
+    for (int s = 0; s < RING - 1; ++s)
+        if (s < KB) issue(s, s);
+    asm volatile("" ::: "memory");
+
+    for (int s = 0; s < KB; ++s) {
+        // stages issued so far: 0 .. min(KB-1, s+RING-2); those after s are still allowed
+        // to be in flight
+        const int last = (s + RING - 2 < KB - 1) ? (s + RING - 2) : (KB - 1);
+        const int younger = last - s;
+        if (younger >= 2) wait_vmem<2 * LOADS>();
+        else if (younger == 1) wait_vmem<LOADS>();
+        else wait_vmem<0>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // every wave is past stage s-1: its buffer can take stage s+RING-1
+        if (s + RING - 1 < KB) issue(s + RING - 1, (s + RING - 1) % RING);
+        asm volatile("" ::: "memory");
+        if (active) compute(s % RING);
+    }
     if (!active) return;
 
     // ---- epilogue: rebuild, add q*2^sh + OFFX*S + mask, reduce, store ----
@@ -278,6 +345,13 @@ __global__ __launch_bounds__(256) void cop_mfma_kernel(const MfmaArgs a)
         add128(base_hi, base_lo, __umul64hi(S, (uint64_t)a.offx), S * (uint64_t)a.offx);
     }
     const int row0 = rt * kTile + 4 * (lane >> 5);
+    // all mask words first, so that their latencies overlap
+    uint64_t mk[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = row0 + 8 * (r >> 2) + (r & 3);
+        mk[r] = (a.mask && row < a.m) ? a.mask[(size_t)row * a.C + col] : 0;
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int row = row0 + 8 * (r >> 2) + (r & 3);
@@ -292,9 +366,8 @@ __global__ __launch_bounds__(256) void cop_mfma_kernel(const MfmaArgs a)
             add128(hi, lo, (uint64_t)(W[1] >> 32), (uint64_t)W[1] << 32);
             hi += (uint64_t)W[2];
             add128(hi, lo, base_hi, base_lo);
-            const size_t idx = (size_t)row * a.C + col;
-            if (a.mask) add128(hi, lo, 0, a.mask[idx]);
-            a.out[idx] = barrett128(hi, lo, P);
+            add128(hi, lo, 0, mk[r]);
+            a.out[(size_t)row * a.C + col] = barrett128(hi, lo, P);
         }
     }
 }
@@ -322,7 +395,7 @@ template <int DQ>
 static hipError_t prepare_impl(const Problem &p, const uint64_t *ctW, void *prepared,
                                hipStream_t stream)
 {
-    const int KB = (p.k + kTile - 1) / kTile;
+    const int KB = kblocks(p.k);
     const uint32_t CT = (uint32_t)(p.C / kTile);
     const uint64_t total = (uint64_t)CT * KB * 64;
     uint4 *planes = (uint4 *)prepared;
@@ -347,7 +420,7 @@ template <int DX>
 static hipError_t stage_impl(const Problem &p, const uint64_t *X, void *workspace,
                              hipStream_t stream)
 {
-    const int KB = (p.k + kTile - 1) / kTile;
+    const int KB = kblocks(p.k);
     const int RT = (p.m + kTile - 1) / kTile;
     const uint32_t xtotal = (uint32_t)RT * KB * 64;
     hipLaunchKernelGGL(x_planes_kernel<DX>, dim3((xtotal + 255) / 256), dim3(256), 0, stream,
@@ -369,7 +442,7 @@ template <int DX, int DQ>
 static hipError_t mfma_impl(const Problem &p, const void *staged, const void *prepared,
                             const uint64_t *mask, uint64_t *out, hipStream_t stream)
 {
-    const int KB = (p.k + kTile - 1) / kTile;
+    const int KB = kblocks(p.k);
     const uint32_t CT = (uint32_t)(p.C / kTile);
 
     MfmaArgs a{};

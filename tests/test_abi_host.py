@@ -41,7 +41,7 @@ def test_size_queries():
     want = (cfg.C // 32) * (cfg.k // 32) * 7 * 1024 + cfg.C * 8
     assert nc.nimbus_cop_prepared_bytes(cfg.k, cfg.n, cfg.N, cfg.L, cfg.moduli) == want
     assert nc.nimbus_cop_workspace_bytes(cfg.m, cfg.k, cfg.t_bits) == 4 * 24 * 3 * 1024
-    # ragged k and m round up to whole 32 x 32 tiles
+    # ragged m and k round up to whole 32 x 32 tiles
     assert nc.nimbus_cop_workspace_bytes(33, 65, 16) == 2 * 3 * 2 * 1024
     assert nc.nimbus_cop_prepared_bytes(0, 8, 32, 1, (97,)) == 0
     assert nc.nimbus_cop_workspace_bytes(0, 8, 16) == 0
