@@ -108,7 +108,7 @@ int nimbus_cop_prepare(const uint64_t *ctW, int k, int n, int N, int L,
  *   workspace  device buffer of at least nimbus_cop_workspace_bytes(m, k,
  *              x_bits) bytes, 16-byte aligned; holds the byte planes of X.
  *              (0 is returned for invalid parameters.)
- * Additional limit (NIMBUS_COP_ERR_UNSUPPORTED beyond it): k <= 32767, so that
+ * Additional limit (NIMBUS_COP_ERR_UNSUPPORTED beyond it): k <= 16383, so that
  * the int32 accumulators of the byte products cannot overflow.
  */
 size_t nimbus_cop_workspace_bytes(int m, int k, int x_bits);

@@ -16,9 +16,11 @@
 //
 // Each D_d is one int32 MFMA accumulator (all byte pairs of one diagonal d
 // accumulate into the same tile).  |dx dq| <= 2^14, at most min(DX,DQ) pairs per
-// diagonal, so |D_d| <= k * min(DX,DQ) * 2^14, which the host keeps below 2^31.
-// The epilogue rebuilds the 128-bit signed sum, adds a multiple of q that makes
-// it non-negative, OFFX*S and the mask, and reduces once.
+// diagonal, so |D_d| <= k * min(DX,DQ) * 2^14, which the host keeps below 2^30.
+// The accumulators start at 2^30, so what comes out is D_d + 2^30 in [0, 2^31):
+// the epilogue rebuilds sum_d (D_d + 2^30) 256^d with unsigned 32-bit pieces, adds
+// one 128-bit constant (a multiple of q that makes the total non-negative, plus
+// OFFX*S, minus the 2^30 offsets), adds the mask, and reduces once.
 //
 // Operand tiles are 32 x 32 bytes stored in the register order of the MFMA: the
 // 16 bytes of lane l belong to row (or column) l % 32 and to k-slots
@@ -152,9 +154,33 @@ struct MfmaArgs {
     int m, KB, RB, N, L;
     uint32_t C, CT;
     uint32_t offx;            // OFFX
-    LimbTable limbs;
-    uint64_t bias_hi[kMaxLimbs], bias_lo[kMaxLimbs];   // q_l << sh
+    uint64_t q[kMaxLimbs];
+    double qinv[kMaxLimbs];   // 1 / q_l, rounded
+    // (q_l << sh) - 2^30 * sum_d 256^d  modulo 2^128
+    uint64_t cst_hi[kMaxLimbs], cst_lo[kMaxLimbs];
 };
+
+// V mod q for 0 <= V = hi:lo < 2^47 * q, q < 2^62.
+// The quotient is estimated in double precision: V converted with three roundings, times
+// the rounded 1/q, has a relative error below 2^-50, so below 2^47 the estimate is off
+// by less than 1/8; taking 1/4 off before truncating gives floor(V/q) or one less,
+// never more.  The remainder is then formed modulo 2^64 and corrected once.
+__device__ __forceinline__ uint64_t reduce_fp(uint64_t hi, uint64_t lo, uint64_t q, double qinv)
+{
+    const double two32 = 4294967296.0;
+    double vd = fma((double)(uint32_t)(lo >> 32), two32, (double)(uint32_t)lo);
+    vd = fma((double)(uint32_t)hi, two32 * two32, vd);
+    vd = fma((double)(uint32_t)(hi >> 32), two32 * two32 * two32, vd);
+    const double qd = fmax(fma(vd, qinv, -0.25), 0.0);
+    const uint32_t qh = (uint32_t)(qd * (1.0 / two32));
+    const uint32_t ql = (uint32_t)fma(-(double)qh, two32, qd);
+    const uint32_t q_lo = (uint32_t)q, q_hi = (uint32_t)(q >> 32);
+    uint64_t p = (uint64_t)ql * q_lo;
+    p += (uint64_t)(ql * q_hi + qh * q_lo) << 32;
+    uint64_t r = lo - p;
+    if (r >= q) r -= q;
+    return r;
+}
 
 #define NIMBUS_AS1 __attribute__((address_space(1)))
 #define NIMBUS_AS3 __attribute__((address_space(3)))
@@ -278,7 +304,7 @@ __global__ __launch_bounds__(256, 2) void cop_mfma_kernel(const MfmaArgs a)
 #pragma unroll
     for (int d = 0; d < ND; ++d)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[d][r] = 0;
+        for (int r = 0; r < 16; ++r) acc[d][r] = 1 << 30;
 
     // Operands come out of LDS through explicit ds_read_b128 instructions: reads the
     // compiler can see would each be made to wait for every direct-to-LDS load in
@@ -335,14 +361,15 @@ __global__ __launch_bounds__(256, 2) void cop_mfma_kernel(const MfmaArgs a)
     }
     if (!active) return;
 
-    // ---- epilogue: rebuild, add q*2^sh + OFFX*S + mask, reduce, store ----
+    // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
     const uint32_t col = ct * kTile + (uint32_t)(lane & 31);
-    const uint32_t limb = (col / (uint32_t)a.N) % (uint32_t)a.L;
-    const Limb P = a.limbs.limb[limb];
-    uint64_t base_hi = a.bias_hi[limb], base_lo = a.bias_lo[limb];
+    const uint32_t limb = (ct * kTile / (uint32_t)a.N) % (uint32_t)a.L;   // uniform
+    const uint64_t q = a.q[limb];
+    const double qinv = a.qinv[limb];
+    uint64_t cst_hi = a.cst_hi[limb], cst_lo = a.cst_lo[limb];
     {
         const uint64_t S = a.colsum[col];
-        add128(base_hi, base_lo, __umul64hi(S, (uint64_t)a.offx), S * (uint64_t)a.offx);
+        add128(cst_hi, cst_lo, __umul64hi(S, (uint64_t)a.offx), S * (uint64_t)a.offx);
     }
     const int row0 = rt * kTile + 4 * (lane >> 5);
     // all mask words first, so that their latencies overlap
@@ -356,18 +383,21 @@ __global__ __launch_bounds__(256, 2) void cop_mfma_kernel(const MfmaArgs a)
     for (int r = 0; r < 16; ++r) {
         const int row = row0 + 8 * (r >> 2) + (r & 3);
         if (row < a.m) {
-            // W0 = sum_{d<4} D_d 2^(8d), W1 = sum_{4<=d<8} D_d 2^(8(d-4)), W2 = rest
-            int64_t W[3] = {0, 0, 0};
+            // E_d = D_d + 2^30 < 2^31.  Z_b = E_b + 2^32 E_{b+4} is a register pair;
+            // sum_d E_d 256^d = Z_0 + 2^8 Z_1 + 2^16 Z_2 + 2^24 Z_3 + 2^64 (E_8 + ...)
+            auto E = [&](int d) -> uint64_t { return d < ND ? (uint64_t)(uint32_t)acc[d][r] : 0; };
+            uint64_t lo = E(0) | (E(4) << 32);
+            uint64_t hi = E(8) + (E(9) << 8) + (E(10) << 16);
 #pragma unroll
-            for (int d = 0; d < ND; ++d)
-                W[d >> 2] += (int64_t)acc[d][r] * (int64_t)(1 << (8 * (d & 3)));
-            uint64_t lo = (uint64_t)W[0];
-            uint64_t hi = (uint64_t)(W[0] >> 63);
-            add128(hi, lo, (uint64_t)(W[1] >> 32), (uint64_t)W[1] << 32);
-            hi += (uint64_t)W[2];
-            add128(hi, lo, base_hi, base_lo);
+            for (int b = 1; b < 4; ++b) {
+                const uint64_t Z = E(b) | (E(b + 4) << 32);
+                const uint64_t t = Z << (8 * b);
+                lo += t;
+                hi += (Z >> (64 - 8 * b)) + (lo < t ? 1u : 0u);
+            }
+            add128(hi, lo, cst_hi, cst_lo);
             add128(hi, lo, 0, mk[r]);
-            a.out[(size_t)row * a.C + col] = barrett128(hi, lo, P);
+            a.out[(size_t)row * a.C + col] = reduce_fp(hi, lo, q, qinv);
         }
     }
 }
@@ -382,13 +412,23 @@ static int ceil_log2(unsigned v)
     return b;
 }
 
+// q * 2^sh is added to make the signed sum non-negative: 2^sh >= k * 2^(8 DX - 1)
+// bounds |sum_i x'_i c'_i| / q from above (|x'| < 2^(8 DX - 1) * 1.01, |c'| <= q / 2)
+static int bias_shift(const Problem &p)
+{
+    return ceil_log2((unsigned)p.k) + 8 * planes_x(p.x_bits) - 1;
+}
+
 bool mfma_supported(const Problem &p)
 {
     const int DX = planes_x(p.x_bits), DQ = planes_q(p.q_bits_max);
     if (DX < 2 || DX > 4 || DQ < 7 || DQ > 8) return false;
     const long long pairs = DX < DQ ? DX : DQ;
-    // zero padding of k adds nothing to |D_d|
-    return (long long)p.k * pairs * 16384ll <= 2147483647ll;
+    // |D_d| < 2^30 (zero padding of k adds nothing)
+    if ((long long)p.k * pairs * 16384ll >= (1ll << 30)) return false;
+    // the value reduced in the epilogue is below (2^(sh+1) + 2^32 + 1) * q; the
+    // floating-point quotient needs it below 2^47 * q
+    return bias_shift(p) + 2 <= 47;
 }
 
 template <int DQ>
@@ -460,13 +500,16 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
     a.CT = CT;
     a.offx = 0;
     for (int d = 0; d < DX; ++d) a.offx |= 0x80u << (8 * d);
-    a.limbs = p.limbs;
-    // q * 2^sh with 2^sh >= k * 2^(8 DX - 1) >= |sum x' c'| / q
-    const int sh = ceil_log2((unsigned)p.k) + 8 * DX - 1;
+    const int sh = bias_shift(p);
+    unsigned __int128 offsets = 0;                  // 2^30 * sum_d 256^d
+    for (int d = 0; d < DX + DQ - 1; ++d) offsets += (unsigned __int128)1 << (30 + 8 * d);
     for (int l = 0; l < p.L; ++l) {
-        const unsigned __int128 b = (unsigned __int128)p.limbs.limb[l].q << sh;
-        a.bias_hi[l] = (uint64_t)(b >> 64);
-        a.bias_lo[l] = (uint64_t)b;
+        const uint64_t q = p.limbs.limb[l].q;
+        const unsigned __int128 c = ((unsigned __int128)q << sh) - offsets;   // modulo 2^128
+        a.q[l] = q;
+        a.qinv[l] = 1.0 / (double)q;
+        a.cst_hi[l] = (uint64_t)(c >> 64);
+        a.cst_lo[l] = (uint64_t)c;
     }
     hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ>), dim3(CT * (uint32_t)a.RB), dim3(256), 0, stream, a);
     return hipGetLastError();
