@@ -211,6 +211,11 @@ __device__ __forceinline__ void wait_lds(v4i &x)
     asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(PENDING) : "memory");
 }
 
+// keeps the users of x behind the preceding volatile asm statements (and the producer of
+// x before the following ones)
+__device__ __forceinline__ void tie(v4i &x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void tie_acc(v16i &x) { asm volatile("" : "+v"(x)); }
+
 // wait until at most PENDING of this wave's global loads (here: direct-to-LDS loads) are
 // outstanding
 template <int PENDING>
@@ -232,72 +237,157 @@ __device__ __forceinline__ void dma_quarter(const void *src_lane, void *dst_wave
                                      (NIMBUS_AS3 void *)dst_wave, 4, 0, 0);
 }
 
-// The pipeline: a stage is one k-block (32 values of k): the workgroup's 4*DX operand
-// tiles of X and the DQ operand tiles of the ciphertext planes, STAGE_TILES KB in all.
-// Stages live in a ring of RING LDS buffers filled by direct-to-LDS loads issued
-// RING-1 stages ahead; nothing passes through registers on the way in.  Every wave
-// issues the same number of loads per stage (its own DX tiles of X, one whole ciphertext
-// tile, and a quarter of each remaining ciphertext tile), so "stage s has landed" is the
-// wait "at most (stages issued after s) * LOADS loads pending" followed by the barrier.
+// The pipeline.  A workgroup of eight waves (two per SIMD) owns 128 token rows x 64
+// coefficient columns; wave (wr, wc) owns the 32 x 32 output tile of row tile wr and
+// column tile wc, with DX+DQ-1 int32 accumulator tiles.
+//
+// A stage is one k-block (32 values of k): 4*DX operand tiles of X (12 KB for DX = 3)
+// and 2*DQ operand tiles of ciphertext planes (14 KB for DQ = 7).  X tiles come from
+// L2, ciphertext tiles from HBM, so the two have their own LDS rings: a shallow one
+// for X and a deep one for the ciphertext stream (about 100 KB in flight per CU).
+// Both are filled by direct-to-LDS loads of whole tiles (64 lanes x 16 B; the texture
+// address unit spends the same time on narrower loads); nothing passes through
+// registers on the way in.  A wave knows how many loads it issues per stage, so "stage
+// s has landed" is a wait on the number of its younger loads, then the barrier.
+//
+// Inside a wave the loop is software pipelined: the LDS reads of stage s+1 are issued
+// before the matrix-core instructions of stage s, into the other of two operand sets.
+#ifndef NIMBUS_RING_A
+#define NIMBUS_RING_A 3
+#endif
+#ifndef NIMBUS_RING_B_MAX
+#define NIMBUS_RING_B_MAX 8
+#endif
 template <int DX, int DQ>
 struct Pipe {
     static constexpr int A_TILES = 4 * DX;
-    static constexpr int STAGE_TILES = A_TILES + DQ;
-    static constexpr int STAGE_BYTES = STAGE_TILES * kTileBytes;
-    static constexpr int RING = (4 * STAGE_BYTES <= 80 * 1024) ? 4 : 3;
-    static constexpr int LOADS = DX + 1 + (DQ - 4);
-    static_assert(DQ >= 4, "each of the four waves moves one whole ciphertext tile");
+    static constexpr int B_TILES = 2 * DQ;
+    static constexpr int A_BYTES = A_TILES * kTileBytes;
+    static constexpr int B_BYTES = B_TILES * kTileBytes;
+    // Waves 0-3 move the X tiles of a stage (tile t to wave t % 4), waves 4-7 the
+    // ciphertext tiles, one whole-tile load each.  A wave's loads then all belong to one
+    // ring, and the in-order load counter of the wave can say "my loads of stage j have
+    // landed" without also waiting for loads of the other, deeper ring.
+    static constexpr int MAXU = ((A_TILES > B_TILES ? A_TILES : B_TILES) + 3) / 4;
+    static constexpr int RING_A = NIMBUS_RING_A;
+    static constexpr int RING_B_FIT = (152 * 1024 - RING_A * A_BYTES) / B_BYTES;
+    static constexpr int RING_B = RING_B_FIT > NIMBUS_RING_B_MAX ? NIMBUS_RING_B_MAX : RING_B_FIT;
+    static constexpr int LDS_BYTES = RING_A * A_BYTES + RING_B * B_BYTES;
+    // most loads of a wave that can be younger than its loads of the next stage
+    static constexpr int MAX_YOUNGER = ((RING_A > RING_B ? RING_A : RING_B) - 2) * MAXU;
+    static_assert(MAX_YOUNGER + MAXU <= 63, "pending-load count must fit the wait counter");
 };
 
+// wait until at most n (LO <= n <= HI) loads are pending; n is wave-uniform.  The wait
+// instruction takes an immediate, hence the binary search down to a constant.
+template <int LO, int HI>
+__device__ __forceinline__ void wait_vmem_range(int n)
+{
+    if constexpr (LO >= HI) {
+        wait_vmem<LO>();
+    } else {
+        constexpr int MID = (LO + HI + 1) / 2;
+        if (n >= MID) wait_vmem_range<MID, HI>(n);
+        else wait_vmem_range<LO, MID - 1>(n);
+    }
+}
+template <int MAX>
+__device__ __forceinline__ void wait_vmem_upto(int n)
+{
+    wait_vmem_range<0, MAX>(n);
+}
+
 template <int DX, int DQ>
-__global__ __launch_bounds__(256, 2) void cop_mfma_kernel(const MfmaArgs a)
+__global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 {
     using P_ = Pipe<DX, DQ>;
     constexpr int ND = DX + DQ - 1;
-    constexpr int RING = P_::RING;
-    constexpr int LOADS = P_::LOADS;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[RING * P_::STAGE_BYTES];
+    constexpr int RA = P_::RING_A, RB = P_::RING_B;
+    // accumulators + two operand sets + addressing must fit 256 registers (two waves per SIMD)
+    constexpr bool PIPELINED = ND * 16 + 2 * (DX + DQ) * 4 + 12 <= 256;
+    constexpr int AHEAD = PIPELINED ? 1 : 0;
+    constexpr int SETS = PIPELINED ? 2 : 1;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[P_::LDS_BYTES];
+    unsigned char *const ldsA = lds;
+    unsigned char *const ldsB = lds + RA * P_::A_BYTES;
 
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // 0..7
+    const int wr = wave >> 1, wc = wave & 1;
 
-    // workgroup -> (column tile, row block).  Workgroups are dealt round-robin to
+    // workgroup -> (64-column tile, row block).  Workgroups are dealt round-robin to
     // the 8 XCDs; the RB row blocks that share a column tile are kept on one XCD
     // and adjacent in launch order so that tile is fetched from HBM once.
-    uint32_t ct, rb;
+    uint32_t ct2, rb;
     {
         const uint32_t id = blockIdx.x;
-        if ((a.CT & 7u) == 0) {
+        const uint32_t CT2 = a.CT >> 1;
+        if ((CT2 & 7u) == 0) {
             const uint32_t xcd = id & 7u, slot = id >> 3;
             rb = slot % (uint32_t)a.RB;
-            ct = (slot / (uint32_t)a.RB) * 8u + xcd;
+            ct2 = (slot / (uint32_t)a.RB) * 8u + xcd;
         } else {
             rb = id % (uint32_t)a.RB;
-            ct = id / (uint32_t)a.RB;
+            ct2 = id / (uint32_t)a.RB;
         }
     }
-    const int rt = (int)rb * 4 + wave;
-    const bool active = rt * kTile < a.m;           // wave-uniform
-    // a wave without rows still moves its share of every stage (reading the last real
-    // row tile in place of its own) so that all waves count the same loads
-    const int rt_load = active ? rt : (a.m - 1) / kTile;
-
+    const int RT = (a.m + kTile - 1) / kTile;       // row tiles that exist in the workspace
+    const int rt = (int)rb * 4 + wr;                // this wave's row tile
+    const bool active = rt < RT;                    // wave-uniform
     const int KB = a.KB;
-    const unsigned char *gA = (const unsigned char *)(a.xd + (size_t)rt_load * KB * (DX * 64));
-    const unsigned char *gB = (const unsigned char *)(a.planes + (size_t)ct * KB * (DQ * 64));
 
-    auto issue = [&](int kb, int buf) {
-        unsigned char *dst = lds + buf * P_::STAGE_BYTES;
-        const unsigned char *srcA = gA + (size_t)kb * (DX * kTileBytes);
-        const unsigned char *srcB = gB + (size_t)kb * (DQ * kTileBytes);
+    // ---- this wave's share of the loads of one stage (sources at k-block 0) ----
+    // X tile t of a stage, t in [0, 4 DX): row tile t / DX (clamped to an existing one;
+    // rows past m are never used), plane t % DX.  Ciphertext tile u in [0, 2 DQ):
+    // column tile u / DQ, plane u % DQ.
+    auto a_src = [&](int t) -> const unsigned char * {
+        int r = (int)rb * 4 + t / DX;
+        if (r > RT - 1) r = RT - 1;
+        return (const unsigned char *)(a.xd + ((size_t)r * KB * DX + (size_t)(t % DX)) * 64);
+    };
+    auto b_src = [&](int u) -> const unsigned char * {
+        return (const unsigned char *)(a.planes +
+                                       ((size_t)(ct2 * 2u + (uint32_t)(u / DQ)) * KB * DQ +
+                                        (size_t)(u % DQ)) * 64);
+    };
+    // this wave's loads of a stage: load u (u < MAXU) moves tile (wave % 4) + 4 u of its ring
+    const bool loads_x = wave < 4;                  // waves 0-3: X ring, waves 4-7: ciphertext ring
+    const int ring = loads_x ? RA : RB;             // depth of this wave's ring
+    const unsigned char *src[P_::MAXU];             // lane's source address at k-block 0
+    int n_loads = 0;                                // loads per stage
 #pragma unroll
-        for (int d = 0; d < DX; ++d)
-            dma_tile(srcA + d * kTileBytes + lane * 16, dst + (wave * DX + d) * kTileBytes);
-        dma_tile(srcB + wave * kTileBytes + lane * 16, dst + (P_::A_TILES + wave) * kTileBytes);
-#pragma unroll
-        for (int d = 4; d < DQ; ++d)
-            dma_quarter(srcB + d * kTileBytes + wave * 256 + lane * 4,
-                        dst + (P_::A_TILES + d) * kTileBytes + wave * 256);
+    for (int u = 0; u < P_::MAXU; ++u) {
+        const int t = (wave & 3) + 4 * u;
+        if (loads_x ? (t < P_::A_TILES) : (t < P_::B_TILES)) {
+            src[u] = (loads_x ? a_src(t) : b_src(t)) + lane * 16;
+            ++n_loads;
+        } else {
+            src[u] = nullptr;
+        }
+    }
+    const size_t src_step = (size_t)(loads_x ? DX : DQ) * kTileBytes;   // per k-block
+    // Stage s of this workgroup is k-block (s + k_start) mod KB: the sum over k does not
+    // care about the order, and workgroups that walk their (equally spaced) ciphertext
+    // regions in lockstep would otherwise ask the same memory channels for data at the
+    // same moment.
+    const int k_start = (int)(blockIdx.x % (uint32_t)KB);
+    auto rotated = [&](int kb) -> int {
+        const int r = kb + k_start;
+        return r >= KB ? r - KB : r;
+    };
+    unsigned char *const ring_base = loads_x ? ldsA : ldsB;
+    const uint32_t stage_bytes = loads_x ? P_::A_BYTES : P_::B_BYTES;
+    // load u of stage kb of this wave's ring (kb < KB is the caller's business)
+    auto issue_one = [&](int kb, bool exists, auto u_c) {
+        constexpr int u = decltype(u_c)::value;
+        if (exists && u < n_loads)
+            dma_tile(src[u] + (size_t)rotated(kb) * src_step,
+                     ring_base + (uint32_t)(kb % ring) * stage_bytes +
+                         (uint32_t)((wave & 3) + 4 * u) * kTileBytes);
+    };
+    auto issue_stage = [&](int kb) {
+        const bool exists = kb >= 0 && kb < KB;
+        static_for<0, P_::MAXU>([&](auto u_c) { issue_one(kb, exists, u_c); });
     };
 
     v16i acc[ND];
@@ -307,77 +397,139 @@ __global__ __launch_bounds__(256, 2) void cop_mfma_kernel(const MfmaArgs a)
         for (int r = 0; r < 16; ++r) acc[d][r] = 1 << 30;
 
     // Operands come out of LDS through explicit ds_read_b128 instructions: reads the
-    // compiler can see would each be made to wait for every direct-to-LDS load in
-    // flight.  All reads of a k-block are issued at once; the matrix-core work on
-    // ciphertext plane dq starts as soon as that plane is back.
+    // compiler can see would each be made to wait for every direct-to-LDS load in flight.
     const uint32_t lds0 = (uint32_t)(uintptr_t)(NIMBUS_AS3 void *)&lds[0];
-    const uint32_t laneA = lds0 + (uint32_t)(wave * DX) * kTileBytes + (uint32_t)lane * 16u;
-    const uint32_t laneB = lds0 + (uint32_t)P_::A_TILES * kTileBytes + (uint32_t)lane * 16u;
-    auto compute = [&](int buf) {
-        const uint32_t off = (uint32_t)buf * P_::STAGE_BYTES;
-        v4i xa[DX], b[DQ];
-        static_for<0, DX>([&](auto d_c) {
-            constexpr int d = decltype(d_c)::value;
-            xa[d] = lds_read_b128<d * kTileBytes>(laneA + off);
-        });
-        static_for<0, DQ>([&](auto d_c) {
-            constexpr int d = decltype(d_c)::value;
-            b[d] = lds_read_b128<d * kTileBytes>(laneB + off);
-        });
-        static_for<0, DQ>([&](auto dq_c) {
-            constexpr int dq = decltype(dq_c)::value;
-            wait_lds<DQ - 1 - dq>(b[dq]);
-            if constexpr (dq == 0) {
+    const uint32_t laneA = lds0 + (uint32_t)(wr * DX) * kTileBytes + (uint32_t)lane * 16u;
+    const uint32_t laneB = lds0 + (uint32_t)(RA * P_::A_BYTES) +
+                           (uint32_t)(wc * DQ) * kTileBytes + (uint32_t)lane * 16u;
+    v4i xa[SETS][DX], xb[SETS][DQ];                 // [operand set][plane]
+    // read number i (0 <= i < DX+DQ) of stage kb into operand set SET
+    auto read_one = [&](int kb, auto set_c, auto i_c) {
+        constexpr int SET = decltype(set_c)::value;
+        constexpr int i = decltype(i_c)::value;
+        if constexpr (i < DX)
+            xa[SET][i] = lds_read_b128<i * kTileBytes>(laneA + (uint32_t)(kb % RA) * P_::A_BYTES);
+        else
+            xb[SET][i - DX] =
+                lds_read_b128<(i - DX) * kTileBytes>(laneB + (uint32_t)(kb % RB) * P_::B_BYTES);
+    };
+    auto read_ops = [&](int kb, auto set_c) {
+        static_for<0, DX + DQ>([&](auto i_c) { read_one(kb, set_c, i_c); });
+    };
+    // all LDS reads of this wave are back; ties every register of the set to the wait
+    auto wait_ops = [&](auto set_c) {
+        constexpr int SET = decltype(set_c)::value;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-                for (int dx = 0; dx < DX; ++dx) asm volatile("" : "+v"(xa[dx]));
-            }
+        for (int d = 0; d < DX; ++d) tie(xa[SET][d]);
 #pragma unroll
-            for (int dx = 0; dx < DX; ++dx)
-                acc[dx + dq] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                    xa[dx], b[dq], acc[dx + dq], 0, 0, 0);
-        });
+        for (int d = 0; d < DQ; ++d) tie(xb[SET][d]);
     };
 
-    // prologue: stages 0 .. RING-2
-#pragma unroll
-    for (int s = 0; s < RING - 1; ++s)
-        if (s < KB) issue(s, s);
+    // Issue order.  "Slot i" (i = -ring .. KB-1) issues this wave's loads of stage
+    // i+ring of its ring.  The prologue runs slots up to AHEAD-2; iteration s runs slot
+    // s+AHEAD-1 after its barrier (the ring slot it refills was read out before that
+    // barrier).  Stage j is needed at the top of iteration j-AHEAD, when slots up to j-2
+    // have run; the wave's loads younger than those of stage j (slot j-ring) are the
+    // ones of slots j-ring+1 .. j-2.
+    auto younger_than = [&](int j) -> int {
+        int first = j + 1, last = j - 2 + ring;     // stages issued by those slots
+        if (last > KB - 1) last = KB - 1;
+        return last >= first ? (last - first + 1) * n_loads : 0;
+    };
+    for (int i = -ring; i <= AHEAD - 2; ++i) issue_stage(i + ring);
     asm volatile("" ::: "memory");
-
-    for (int s = 0; s < KB; ++s) {
-        // stages issued so far: 0 .. min(KB-1, s+RING-2); those after s are still allowed
-        // to be in flight
-        const int last = (s + RING - 2 < KB - 1) ? (s + RING - 2) : (KB - 1);
-        const int younger = last - s;
-        if (younger >= 2) wait_vmem<2 * LOADS>();
-        else if (younger == 1) wait_vmem<LOADS>();
-        else wait_vmem<0>();
+    if constexpr (PIPELINED) {
+        // stage 0 is read before the loop; slot -1 has run as well and is younger
+        const int n = younger_than(0) + ((ring - 1 < KB) ? n_loads : 0);
+        wait_vmem_upto<P_::MAX_YOUNGER + P_::MAXU>(n);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        // every wave is past stage s-1: its buffer can take stage s+RING-1
-        if (s + RING - 1 < KB) issue(s + RING - 1, (s + RING - 1) % RING);
-        asm volatile("" ::: "memory");
-        if (active) compute(s % RING);
+        if (active) read_ops(0, std::integral_constant<int, 0>{});
     }
-    if (!active) return;
+
+    // iteration s, pipelined: make stage s+1 visible, refill the ring slots of stage s
+    // (already in registers), read stage s+1 into the other operand set, run the matrix
+    // cores on stage s.  Not pipelined (register budget of the widest variants): make
+    // stage s visible, refill the slots of stage s-1, read stage s, wait, run.
+    //
+    // The matrix-core instructions of a stage are issued with one other instruction
+    // between consecutive ones: first the LDS reads of stage s+1 (pipelined variants),
+    // then the direct-to-LDS loads of slot j-1.  Issued in a burst those would fill the
+    // LDS and texture-address queues of the CU (all eight waves leave the barrier
+    // together) and hold back the matrix-core instructions queued behind them.  The
+    // empty volatile asm statements pin this order.
+    constexpr int R0 = PIPELINED ? DX + DQ : 0;
+    static_assert(DX * DQ >= R0 + P_::MAXU, "not enough slots between the MFMAs");
+    // ACTIVE: the wave has rows.  READ_NEXT: stage s+1 exists (pipelined only).
+    auto iteration = [&](int s, auto set_c, auto active_c, auto read_next_c) {
+        constexpr int SET = decltype(set_c)::value;
+        constexpr bool ACTIVE = decltype(active_c)::value;
+        constexpr bool READ_NEXT = decltype(read_next_c)::value;
+        const int j = s + AHEAD;
+        if (j < KB) wait_vmem_upto<P_::MAX_YOUNGER>(younger_than(j));
+        if constexpr (PIPELINED && ACTIVE) wait_ops(set_c);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if constexpr (!PIPELINED && ACTIVE) {
+            read_ops(s, set_c);
+            wait_ops(set_c);
+        }
+        const int refill = j - 1 + ring;            // slot j-1
+        const bool refill_exists = refill < KB;
+        static_for<0, DX * DQ>([&](auto i_c) {
+            constexpr int i = decltype(i_c)::value;
+            constexpr int dq = i / DX, dx = i % DX;
+            if constexpr (ACTIVE) {
+                tie(xa[SET][dx]);
+                tie(xb[SET][dq]);
+                acc[dx + dq] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                    xa[SET][dx], xb[SET][dq], acc[dx + dq], 0, 0, 0);
+                tie_acc(acc[dx + dq]);
+            }
+            if constexpr (i < R0) {
+                if constexpr (ACTIVE && READ_NEXT)
+                    read_one(s + 1, std::integral_constant<int, (PIPELINED ? 1 - SET : SET)>{}, i_c);
+            } else if constexpr (i - R0 < P_::MAXU) {
+                issue_one(refill, refill_exists, std::integral_constant<int, i - R0>{});
+            }
+        });
+        asm volatile("" ::: "memory");
+    };
+    using C0 = std::integral_constant<int, 0>;
+    using C1 = std::integral_constant<int, 1>;
+    if (!active) {
+        for (int s = 0; s < KB; ++s) iteration(s, C0{}, std::false_type{}, std::false_type{});
+        return;
+    }
+    if constexpr (PIPELINED) {
+        // the last iteration also "reads stage KB": a stale ring slot, valid LDS, never used
+        for (int s = 0; s < KB; s += 2) {
+            iteration(s, C0{}, std::true_type{}, std::true_type{});
+            if (s + 1 < KB) iteration(s + 1, C1{}, std::true_type{}, std::true_type{});
+        }
+    } else {
+        for (int s = 0; s < KB; ++s) iteration(s, C0{}, std::true_type{}, std::false_type{});
+    }
 
     // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
-    const uint32_t col = ct * kTile + (uint32_t)(lane & 31);
-    const uint32_t limb = (ct * kTile / (uint32_t)a.N) % (uint32_t)a.L;   // uniform
+    const uint32_t col = (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
+    const uint32_t limb = (ct2 * 2u * kTile / (uint32_t)a.N) % (uint32_t)a.L;   // uniform
     const uint64_t q = a.q[limb];
     const double qinv = a.qinv[limb];
-    uint64_t cst_hi = a.cst_hi[limb], cst_lo = a.cst_lo[limb];
-    {
-        const uint64_t S = a.colsum[col];
-        add128(cst_hi, cst_lo, __umul64hi(S, (uint64_t)a.offx), S * (uint64_t)a.offx);
-    }
     const int row0 = rt * kTile + 4 * (lane >> 5);
-    // all mask words first, so that their latencies overlap
+    // every load of the epilogue first (mask words, then the column sum), so that their
+    // latencies overlap
     uint64_t mk[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int row = row0 + 8 * (r >> 2) + (r & 3);
         mk[r] = (a.mask && row < a.m) ? a.mask[(size_t)row * a.C + col] : 0;
+    }
+    uint64_t cst_hi = a.cst_hi[limb], cst_lo = a.cst_lo[limb];
+    {
+        const uint64_t S = a.colsum[col];
+        add128(cst_hi, cst_lo, __umul64hi(S, (uint64_t)a.offx), S * (uint64_t)a.offx);
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -385,15 +537,17 @@ __global__ __launch_bounds__(256, 2) void cop_mfma_kernel(const MfmaArgs a)
         if (row < a.m) {
             // E_d = D_d + 2^30 < 2^31.  Z_b = E_b + 2^32 E_{b+4} is a register pair;
             // sum_d E_d 256^d = Z_0 + 2^8 Z_1 + 2^16 Z_2 + 2^24 Z_3 + 2^64 (E_8 + ...)
-            auto E = [&](int d) -> uint64_t { return d < ND ? (uint64_t)(uint32_t)acc[d][r] : 0; };
+            auto E = [&](int d) -> uint64_t {
+                return d < ND ? (uint64_t)(uint32_t)acc[d][r] : 0;
+            };
             uint64_t lo = E(0) | (E(4) << 32);
             uint64_t hi = E(8) + (E(9) << 8) + (E(10) << 16);
 #pragma unroll
             for (int b = 1; b < 4; ++b) {
                 const uint64_t Z = E(b) | (E(b + 4) << 32);
-                const uint64_t t = Z << (8 * b);
-                lo += t;
-                hi += (Z >> (64 - 8 * b)) + (lo < t ? 1u : 0u);
+                const uint64_t sh = Z << (8 * b);
+                lo += sh;
+                hi += (Z >> (64 - 8 * b)) + (lo < sh ? 1u : 0u);
             }
             add128(hi, lo, cst_hi, cst_lo);
             add128(hi, lo, 0, mk[r]);
@@ -511,7 +665,7 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
         a.cst_hi[l] = (uint64_t)(c >> 64);
         a.cst_lo[l] = (uint64_t)c;
     }
-    hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ>), dim3(CT * (uint32_t)a.RB), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ>), dim3((CT / 2) * (uint32_t)a.RB), dim3(512), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -47,6 +47,8 @@ SMALL = [
     (64, 300, 2500, 1024, 1, 20, 54),   # n > N: three ring chunks, last partial
     (40, 96, 128, 128, 3, 24, 55),      # three limbs, 24-bit shares
     (17, 70, 64, 64, 1, 32, 62),        # widest shares and modulus: 4 x 8 byte planes
+    (17, 70, 64, 64, 1, 32, 54),        # 32-bit shares: 4 x 7 byte planes
+    (19, 65, 64, 64, 2, 24, 62),        # 62-bit moduli: 3 x 8 byte planes
     (20, 257, 64, 64, 2, 9, 40),        # small modulus, odd share width
     (1, 1, 32, 32, 1, 16, 50),          # k = 1, m = 1
 ]
