@@ -59,6 +59,13 @@ static size_t prepared_bytes_of(const Problem &p)
     return CT * KB * DQ * kTileBytes + p.C * sizeof(uint64_t);
 }
 
+// the staging kernel indexes its threads with 32 bits
+static bool staging_fits(int m, int k)
+{
+    const uint64_t RT = (uint64_t)(m + kTile - 1) / kTile, KB = (uint64_t)kblocks(k);
+    return RT * KB <= (1ull << 23);
+}
+
 static size_t workspace_bytes_of(int m, int k, int x_bits)
 {
     const size_t RT = (size_t)(m + kTile - 1) / kTile;
@@ -118,6 +125,7 @@ int nimbus_cop_stage_shares(const uint64_t *X, int m, int k, int x_bits,
     if (!X || !workspace || ((uintptr_t)workspace & 15u) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
     if (m < 1 || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 32)
         return NIMBUS_COP_ERR_INVALID_ARG;
+    if (!staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
     Problem p{};
     p.m = m;
@@ -157,7 +165,7 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
     Problem p;
     const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
     if (rc != NIMBUS_COP_OK) return rc;
-    if (!mfma_supported(p)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    if (!mfma_supported(p) || !staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
     hipError_t e = launch_stage_shares(p, X, workspace, (hipStream_t)stream);
     if (e != hipSuccess) return NIMBUS_COP_ERR_LAUNCH;

@@ -107,35 +107,36 @@ __global__ __launch_bounds__(256) void column_sums_kernel(
 template <int DX>
 __global__ __launch_bounds__(256) void x_planes_kernel(
     const uint64_t *__restrict__ X, int m, int k, int KB, uint32_t total,
-    uint4 *__restrict__ xd)
+    uint32_t *__restrict__ xd)
 {
+    // one thread = four consecutive k of one row: one 32-bit word in each of the DX planes
     const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
     if (gid >= total) return;
-    const uint32_t lane = gid & 63u;
-    const uint32_t tile = gid >> 6;                 // rt * KB + kb
+    const uint32_t word = gid & 3u;                 // which 4 of the lane's 16 k-slots
+    const uint32_t lane = (gid >> 2) & 63u;
+    const uint32_t tile = gid >> 8;                 // rt * KB + kb
     const uint32_t kb = tile % (uint32_t)KB;
     const uint32_t rt = tile / (uint32_t)KB;
     const int row = (int)rt * kTile + (int)(lane & 31u);
-    const int kbase = (int)kb * kTile + (int)(lane >> 5) * 16;
+    const int kbase = (int)kb * kTile + (int)(lane >> 5) * 16 + (int)word * 4;
 
-    uint32_t w[DX][4];
+    uint32_t w[DX];
 #pragma unroll
-    for (int d = 0; d < DX; ++d) { w[d][0] = w[d][1] = w[d][2] = w[d][3] = 0; }
+    for (int d = 0; d < DX; ++d) w[d] = 0;
     if (row < m) {
 #pragma unroll
-        for (int b = 0; b < 16; ++b) {
+        for (int b = 0; b < 4; ++b) {
             const int i = kbase + b;
             if (i < k) {
                 const uint32_t x = (uint32_t)X[(size_t)row * k + i] ^ 0x80808080u;
 #pragma unroll
-                for (int d = 0; d < DX; ++d)
-                    w[d][b >> 2] |= ((x >> (8 * d)) & 0xffu) << (8 * (b & 3));
+                for (int d = 0; d < DX; ++d) w[d] |= ((x >> (8 * d)) & 0xffu) << (8 * b);
             }
         }
     }
 #pragma unroll
     for (int d = 0; d < DX; ++d)
-        xd[((size_t)tile * DX + d) * 64u + lane] = make_uint4(w[d][0], w[d][1], w[d][2], w[d][3]);
+        xd[(((size_t)tile * DX + d) * 64u + lane) * 4u + word] = w[d];
 }
 
 // ---------------------------------------------------------------------------
@@ -616,9 +617,9 @@ static hipError_t stage_impl(const Problem &p, const uint64_t *X, void *workspac
 {
     const int KB = kblocks(p.k);
     const int RT = (p.m + kTile - 1) / kTile;
-    const uint32_t xtotal = (uint32_t)RT * KB * 64;
+    const uint32_t xtotal = (uint32_t)RT * KB * 256;
     hipLaunchKernelGGL(x_planes_kernel<DX>, dim3((xtotal + 255) / 256), dim3(256), 0, stream,
-                       X, p.m, p.k, KB, xtotal, (uint4 *)workspace);
+                       X, p.m, p.k, KB, xtotal, (uint32_t *)workspace);
     return hipGetLastError();
 }
 
