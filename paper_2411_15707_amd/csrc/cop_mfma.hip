@@ -216,6 +216,7 @@ __device__ __forceinline__ void wait_lds(v4i &x)
 // x before the following ones)
 __device__ __forceinline__ void tie(v4i &x) { asm volatile("" : "+v"(x)); }
 __device__ __forceinline__ void tie_acc(v16i &x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void tie(int &x) { asm volatile("" : "+v"(x)); }
 
 // wait until at most PENDING of this wave's global loads (here: direct-to-LDS loads) are
 // outstanding
@@ -244,20 +245,30 @@ __device__ __forceinline__ void dma_quarter(const void *src_lane, void *dst_wave
 //
 // A stage is one k-block (32 values of k): 4*DX operand tiles of X (12 KB for DX = 3)
 // and 2*DQ operand tiles of ciphertext planes (14 KB for DQ = 7).  X tiles come from
-// L2, ciphertext tiles from HBM, so the two have their own LDS rings: a shallow one
-// for X and a deep one for the ciphertext stream (about 100 KB in flight per CU).
-// Both are filled by direct-to-LDS loads of whole tiles (64 lanes x 16 B; the texture
-// address unit spends the same time on narrower loads); nothing passes through
-// registers on the way in.  A wave knows how many loads it issues per stage, so "stage
-// s has landed" is a wait on the number of its younger loads, then the barrier.
+// L2, ciphertext tiles from HBM, so the two have their own LDS rings and their own lead
+// (how many stages ahead of the matrix cores the loads run).  Both are filled by
+// direct-to-LDS loads of whole tiles (64 lanes x 16 B; the texture address unit spends
+// the same time on narrower loads); nothing passes through registers on the way in.  A
+// wave knows how many loads it issues per stage, so "stage s has landed" is a wait on
+// the number of its younger loads, then the barrier.
 //
 // Inside a wave the loop is software pipelined: the LDS reads of stage s+1 are issued
-// before the matrix-core instructions of stage s, into the other of two operand sets.
+// between the matrix-core instructions of stage s, into the other of two operand sets.
+//
+// The loop is bound by instruction issue as much as by the matrix cores: a wave issues
+// an instruction every four or five cycles at best and all eight waves run in lockstep
+// between barriers, so every scalar instruction of the loop costs.  Hence: one stage
+// issued per iteration from the first iteration on (constant lead, no ramp), ring
+// offsets carried and wrapped instead of recomputed, and the wait for "at most n loads
+// pending" (an immediate in the instruction) done by a computed jump.
 #ifndef NIMBUS_RING_A
 #define NIMBUS_RING_A 3
 #endif
 #ifndef NIMBUS_RING_B_MAX
 #define NIMBUS_RING_B_MAX 8
+#endif
+#ifndef NIMBUS_LEAD_B
+#define NIMBUS_LEAD_B 3
 #endif
 template <int DX, int DQ>
 struct Pipe {
@@ -268,34 +279,36 @@ struct Pipe {
     // Waves 0-3 move the X tiles of a stage (tile t to wave t % 4), waves 4-7 the
     // ciphertext tiles, one whole-tile load each.  A wave's loads then all belong to one
     // ring, and the in-order load counter of the wave can say "my loads of stage j have
-    // landed" without also waiting for loads of the other, deeper ring.
+    // landed" without also waiting for loads of the other ring.
     static constexpr int MAXU = ((A_TILES > B_TILES ? A_TILES : B_TILES) + 3) / 4;
     static constexpr int RING_A = NIMBUS_RING_A;
     static constexpr int RING_B_FIT = (152 * 1024 - RING_A * A_BYTES) / B_BYTES;
     static constexpr int RING_B = RING_B_FIT > NIMBUS_RING_B_MAX ? NIMBUS_RING_B_MAX : RING_B_FIT;
     static constexpr int LDS_BYTES = RING_A * A_BYTES + RING_B * B_BYTES;
-    // most loads of a wave that can be younger than its loads of the next stage
-    static constexpr int MAX_YOUNGER = ((RING_A > RING_B ? RING_A : RING_B) - 2) * MAXU;
-    static_assert(MAX_YOUNGER + MAXU <= 63, "pending-load count must fit the wait counter");
 };
 
-// wait until at most n (LO <= n <= HI) loads are pending; n is wave-uniform.  The wait
-// instruction takes an immediate, hence the binary search down to a constant.
-template <int LO, int HI>
-__device__ __forceinline__ void wait_vmem_range(int n)
+// Wait until at most n of this wave's loads are pending, 0 <= n <= 63, n wave-uniform.
+// The count is an immediate of the wait instruction: jump into a table of 64 entries
+// of 8 bytes, entry i = { wait for at most i pending; branch to the end }.  The five
+// instructions between the program counter read and the table take 20 bytes.
+__device__ __forceinline__ void wait_vmem_n(int n)
 {
-    if constexpr (LO >= HI) {
-        wait_vmem<LO>();
-    } else {
-        constexpr int MID = (LO + HI + 1) / 2;
-        if (n >= MID) wait_vmem_range<MID, HI>(n);
-        else wait_vmem_range<LO, MID - 1>(n);
-    }
-}
-template <int MAX>
-__device__ __forceinline__ void wait_vmem_upto(int n)
-{
-    wait_vmem_range<0, MAX>(n);
+    asm volatile(
+        "s_getpc_b64 s[98:99]\n\t"
+        "s_lshl_b32 s100, %0, 3\n\t"
+        "s_add_u32 s100, s100, 20\n\t"
+        "s_add_u32 s98, s98, s100\n\t"
+        "s_addc_u32 s99, s99, 0\n\t"
+        "s_setpc_b64 s[98:99]\n\t"
+        ".irp cnt,0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,"
+        "32,33,34,35,36,37,38,39,40,41,42,43,44,45,46,47,48,49,50,51,52,53,54,55,56,57,58,59,60,61,62,63\n\t"
+        "s_waitcnt vmcnt(\\cnt)\n\t"
+        "s_branch .Lwait_vmem_end_%=\n\t"
+        ".endr\n"
+        ".Lwait_vmem_end_%=:"
+        :
+        : "s"(n)
+        : "s98", "s99", "s100", "scc", "memory");
 }
 
 template <int DX, int DQ>
@@ -308,6 +321,15 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     constexpr bool PIPELINED = ND * 16 + 2 * (DX + DQ) * 4 + 12 <= 256;
     constexpr int AHEAD = PIPELINED ? 1 : 0;
     constexpr int SETS = PIPELINED ? 2 : 1;
+    // Lead of a ring: stages 0 .. lead-1 are issued up front, iteration s issues stage
+    // s + lead after its barrier, into the slot of stage s + lead - ring.  That slot has
+    // been read by every wave once all have passed the barrier of iteration
+    // s + lead - ring + 1 - AHEAD, so lead <= ring - 1 + AHEAD.
+    constexpr int LEAD_A = RA - 1 + AHEAD;
+    constexpr int LEAD_B = NIMBUS_LEAD_B < RB - 1 + AHEAD ? NIMBUS_LEAD_B : RB - 1 + AHEAD;
+    static_assert(LEAD_A >= 1 + AHEAD && LEAD_B >= 1 + AHEAD, "rings too shallow");
+    static_assert((LEAD_B > LEAD_A ? LEAD_B : LEAD_A) * P_::MAXU <= 63,
+                  "pending-load count must fit the wait counter");
     __shared__ __attribute__((aligned(1024))) unsigned char lds[P_::LDS_BYTES];
     unsigned char *const ldsA = lds;
     unsigned char *const ldsB = lds + RA * P_::A_BYTES;
@@ -353,7 +375,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     };
     // this wave's loads of a stage: load u (u < MAXU) moves tile (wave % 4) + 4 u of its ring
     const bool loads_x = wave < 4;                  // waves 0-3: X ring, waves 4-7: ciphertext ring
-    const int ring = loads_x ? RA : RB;             // depth of this wave's ring
+    const int lead = loads_x ? LEAD_A : LEAD_B;
     const unsigned char *src[P_::MAXU];             // lane's source address at k-block 0
     int n_loads = 0;                                // loads per stage
 #pragma unroll
@@ -366,29 +388,30 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
             src[u] = nullptr;
         }
     }
-    const size_t src_step = (size_t)(loads_x ? DX : DQ) * kTileBytes;   // per k-block
     // Stage s of this workgroup is k-block (s + k_start) mod KB: the sum over k does not
     // care about the order, and workgroups that walk their (equally spaced) ciphertext
     // regions in lockstep would otherwise ask the same memory channels for data at the
     // same moment.
-    const int k_start = (int)(blockIdx.x % (uint32_t)KB);
-    auto rotated = [&](int kb) -> int {
-        const int r = kb + k_start;
-        return r >= KB ? r - KB : r;
+    const uint32_t k_start = blockIdx.x % (uint32_t)KB;
+    // Wave-uniform state of the issue side, for the next stage to issue: byte offset of
+    // its k-block in the source, byte offset of its slot in the ring.  Carried and
+    // wrapped, never recomputed.
+    const uint32_t src_step = (uint32_t)(loads_x ? DX : DQ) * kTileBytes;   // per k-block
+    const uint32_t src_end = (uint32_t)KB * src_step;
+    const uint32_t slot_step = loads_x ? P_::A_BYTES : P_::B_BYTES;
+    const uint32_t slot_end = loads_x ? RA * P_::A_BYTES : RB * P_::B_BYTES;
+    uint32_t src_off = k_start * src_step;
+    uint32_t slot_off = 0;
+    auto bump = [](uint32_t v, uint32_t step, uint32_t end) -> uint32_t {
+        v += step;
+        return v == end ? 0u : v;
     };
-    unsigned char *const ring_base = loads_x ? ldsA : ldsB;
-    const uint32_t stage_bytes = loads_x ? P_::A_BYTES : P_::B_BYTES;
-    // load u of stage kb of this wave's ring (kb < KB is the caller's business)
-    auto issue_one = [&](int kb, bool exists, auto u_c) {
+    // where the first tile of this wave goes inside a ring slot
+    unsigned char *const wave_dst = (loads_x ? ldsA : ldsB) + (uint32_t)(wave & 3) * kTileBytes;
+    // load u of the stage at (src_off, slot_off)
+    auto issue_one = [&](auto u_c) {
         constexpr int u = decltype(u_c)::value;
-        if (exists && u < n_loads)
-            dma_tile(src[u] + (size_t)rotated(kb) * src_step,
-                     ring_base + (uint32_t)(kb % ring) * stage_bytes +
-                         (uint32_t)((wave & 3) + 4 * u) * kTileBytes);
-    };
-    auto issue_stage = [&](int kb) {
-        const bool exists = kb >= 0 && kb < KB;
-        static_for<0, P_::MAXU>([&](auto u_c) { issue_one(kb, exists, u_c); });
+        dma_tile(src[u] + src_off, wave_dst + slot_off + (uint32_t)(4 * u) * kTileBytes);
     };
 
     v16i acc[ND];
@@ -397,25 +420,35 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[d][r] = 1 << 30;
 
+    // ---- up front: stages 0 .. lead-1 ----
+    for (int st = 0; st < lead && st < KB; ++st) {
+        static_for<0, P_::MAXU>([&](auto u_c) {
+            if (decltype(u_c)::value < n_loads) issue_one(u_c);
+        });
+        src_off = bump(src_off, src_step, src_end);
+        slot_off = bump(slot_off, slot_step, slot_end);
+    }
+
     // Operands come out of LDS through explicit ds_read_b128 instructions: reads the
     // compiler can see would each be made to wait for every direct-to-LDS load in flight.
     const uint32_t lds0 = (uint32_t)(uintptr_t)(NIMBUS_AS3 void *)&lds[0];
     const uint32_t laneA = lds0 + (uint32_t)(wr * DX) * kTileBytes + (uint32_t)lane * 16u;
     const uint32_t laneB = lds0 + (uint32_t)(RA * P_::A_BYTES) +
                            (uint32_t)(wc * DQ) * kTileBytes + (uint32_t)lane * 16u;
+    // ring offsets of the stage that is read next
+    uint32_t rdA = 0, rdB = 0;
     v4i xa[SETS][DX], xb[SETS][DQ];                 // [operand set][plane]
-    // read number i (0 <= i < DX+DQ) of stage kb into operand set SET
-    auto read_one = [&](int kb, auto set_c, auto i_c) {
+    // read number i (0 <= i < DX+DQ) of the stage at (rdA, rdB) into operand set SET
+    auto read_one = [&](auto set_c, auto i_c) {
         constexpr int SET = decltype(set_c)::value;
         constexpr int i = decltype(i_c)::value;
         if constexpr (i < DX)
-            xa[SET][i] = lds_read_b128<i * kTileBytes>(laneA + (uint32_t)(kb % RA) * P_::A_BYTES);
+            xa[SET][i] = lds_read_b128<i * kTileBytes>(laneA + rdA);
         else
-            xb[SET][i - DX] =
-                lds_read_b128<(i - DX) * kTileBytes>(laneB + (uint32_t)(kb % RB) * P_::B_BYTES);
+            xb[SET][i - DX] = lds_read_b128<(i - DX) * kTileBytes>(laneB + rdB);
     };
-    auto read_ops = [&](int kb, auto set_c) {
-        static_for<0, DX + DQ>([&](auto i_c) { read_one(kb, set_c, i_c); });
+    auto read_ops = [&](auto set_c) {
+        static_for<0, DX + DQ>([&](auto i_c) { read_one(set_c, i_c); });
     };
     // all LDS reads of this wave are back; ties every register of the set to the wait
     auto wait_ops = [&](auto set_c) {
@@ -427,57 +460,52 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         for (int d = 0; d < DQ; ++d) tie(xb[SET][d]);
     };
 
-    // Issue order.  "Slot i" (i = -ring .. KB-1) issues this wave's loads of stage
-    // i+ring of its ring.  The prologue runs slots up to AHEAD-2; iteration s runs slot
-    // s+AHEAD-1 after its barrier (the ring slot it refills was read out before that
-    // barrier).  Stage j is needed at the top of iteration j-AHEAD, when slots up to j-2
-    // have run; the wave's loads younger than those of stage j (slot j-ring) are the
-    // ones of slots j-ring+1 .. j-2.
-    auto younger_than = [&](int j) -> int {
-        int first = j + 1, last = j - 2 + ring;     // stages issued by those slots
-        if (last > KB - 1) last = KB - 1;
-        return last >= first ? (last - first + 1) * n_loads : 0;
+    // Loads of this wave younger than those of stage j, before iteration s = j - AHEAD:
+    // stages j+1 .. min(KB, s + lead) - 1, that is min(lead - 1 - AHEAD, KB - 1 - j) stages.
+    auto younger = [&](int j) -> int {
+        int st = KB - 1 - j;
+        if (st > lead - 1 - AHEAD) st = lead - 1 - AHEAD;
+        if (st < 0) st = 0;
+        return st * n_loads;
     };
-    for (int i = -ring; i <= AHEAD - 2; ++i) issue_stage(i + ring);
     asm volatile("" ::: "memory");
     if constexpr (PIPELINED) {
-        // stage 0 is read before the loop; slot -1 has run as well and is younger
-        const int n = younger_than(0) + ((ring - 1 < KB) ? n_loads : 0);
-        wait_vmem_upto<P_::MAX_YOUNGER + P_::MAXU>(n);
+        // stage 0 is read before the loop; its younger loads are those of stages 1 .. lead-1
+        int st = (KB < lead ? KB : lead) - 1;
+        wait_vmem_n(st * n_loads);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (active) read_ops(0, std::integral_constant<int, 0>{});
+        if (active) read_ops(std::integral_constant<int, 0>{});
+        rdA = bump(rdA, P_::A_BYTES, RA * P_::A_BYTES);
+        rdB = bump(rdB, P_::B_BYTES, RB * P_::B_BYTES);
     }
 
-    // iteration s, pipelined: make stage s+1 visible, refill the ring slots of stage s
-    // (already in registers), read stage s+1 into the other operand set, run the matrix
-    // cores on stage s.  Not pipelined (register budget of the widest variants): make
-    // stage s visible, refill the slots of stage s-1, read stage s, wait, run.
+    // iteration s, pipelined: make stage s+1 visible, issue stage s+lead into a slot
+    // whose stage every wave has in registers, read stage s+1 into the other operand
+    // set, run the matrix cores on stage s.  Not pipelined (register budget of the
+    // widest variants): make stage s visible, issue, read stage s, wait, run.
     //
     // The matrix-core instructions of a stage are issued with one other instruction
     // between consecutive ones: first the LDS reads of stage s+1 (pipelined variants),
-    // then the direct-to-LDS loads of slot j-1.  Issued in a burst those would fill the
-    // LDS and texture-address queues of the CU (all eight waves leave the barrier
-    // together) and hold back the matrix-core instructions queued behind them.  The
-    // empty volatile asm statements pin this order.
-    constexpr int R0 = PIPELINED ? DX + DQ : 0;
+    // then the direct-to-LDS loads.  Issued in a burst those would fill the LDS and
+    // texture-address queues of the CU (all eight waves leave the barrier together)
+    // and hold back the matrix-core instructions queued behind them.  The empty volatile
+    // asm statements pin this order.
+    constexpr int R0 = PIPELINED ? DX + DQ : 0;     // MFMA positions taken by LDS reads
     static_assert(DX * DQ >= R0 + P_::MAXU, "not enough slots between the MFMAs");
-    // ACTIVE: the wave has rows.  READ_NEXT: stage s+1 exists (pipelined only).
-    auto iteration = [&](int s, auto set_c, auto active_c, auto read_next_c) {
+    // ACTIVE: the wave has rows.
+    auto iteration = [&](int s, auto set_c, auto active_c) {
         constexpr int SET = decltype(set_c)::value;
         constexpr bool ACTIVE = decltype(active_c)::value;
-        constexpr bool READ_NEXT = decltype(read_next_c)::value;
-        const int j = s + AHEAD;
-        if (j < KB) wait_vmem_upto<P_::MAX_YOUNGER>(younger_than(j));
+        wait_vmem_n(younger(s + AHEAD));
         if constexpr (PIPELINED && ACTIVE) wait_ops(set_c);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if constexpr (!PIPELINED && ACTIVE) {
-            read_ops(s, set_c);
+            read_ops(set_c);
             wait_ops(set_c);
         }
-        const int refill = j - 1 + ring;            // slot j-1
-        const bool refill_exists = refill < KB;
+        const int issue_n = s + lead < KB ? n_loads : 0;    // stage s + lead exists: its loads
         static_for<0, DX * DQ>([&](auto i_c) {
             constexpr int i = decltype(i_c)::value;
             constexpr int dq = i / DX, dx = i % DX;
@@ -489,29 +517,49 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
                 tie_acc(acc[dx + dq]);
             }
             if constexpr (i < R0) {
-                if constexpr (ACTIVE && READ_NEXT)
-                    read_one(s + 1, std::integral_constant<int, (PIPELINED ? 1 - SET : SET)>{}, i_c);
+                // (the last iteration reads a stale slot: valid LDS, never used)
+                if constexpr (ACTIVE)
+                    read_one(std::integral_constant<int, (PIPELINED ? 1 - SET : SET)>{}, i_c);
             } else if constexpr (i - R0 < P_::MAXU) {
-                issue_one(refill, refill_exists, std::integral_constant<int, i - R0>{});
+                constexpr int u = i - R0;
+                if (u < issue_n) issue_one(std::integral_constant<int, u>{});
             }
         });
         asm volatile("" ::: "memory");
     };
+    // the carried offsets move on between iterations (outside the lambda: plain locals)
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
+#define NIMBUS_ADVANCE()                                                      \
+    do {                                                                      \
+        src_off = bump(src_off, src_step, src_end);                           \
+        slot_off = bump(slot_off, slot_step, slot_end);                       \
+        rdA = bump(rdA, P_::A_BYTES, RA * P_::A_BYTES);                       \
+        rdB = bump(rdB, P_::B_BYTES, RB * P_::B_BYTES);                       \
+    } while (0)
     if (!active) {
-        for (int s = 0; s < KB; ++s) iteration(s, C0{}, std::false_type{}, std::false_type{});
+        for (int s = 0; s < KB; ++s) {
+            iteration(s, C0{}, std::false_type{});
+            NIMBUS_ADVANCE();
+        }
         return;
     }
     if constexpr (PIPELINED) {
-        // the last iteration also "reads stage KB": a stale ring slot, valid LDS, never used
         for (int s = 0; s < KB; s += 2) {
-            iteration(s, C0{}, std::true_type{}, std::true_type{});
-            if (s + 1 < KB) iteration(s + 1, C1{}, std::true_type{}, std::true_type{});
+            iteration(s, C0{}, std::true_type{});
+            NIMBUS_ADVANCE();
+            if (s + 1 < KB) {
+                iteration(s + 1, C1{}, std::true_type{});
+                NIMBUS_ADVANCE();
+            }
         }
     } else {
-        for (int s = 0; s < KB; ++s) iteration(s, C0{}, std::true_type{}, std::false_type{});
+        for (int s = 0; s < KB; ++s) {
+            iteration(s, C0{}, std::true_type{});
+            NIMBUS_ADVANCE();
+        }
     }
+#undef NIMBUS_ADVANCE
 
     // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
     const uint32_t col = (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
