@@ -17,10 +17,8 @@
 // Each D_d is one int32 MFMA accumulator (all byte pairs of one diagonal d
 // accumulate into the same tile).  |dx dq| <= 2^14, at most min(DX,DQ) pairs per
 // diagonal, so |D_d| <= k * min(DX,DQ) * 2^14, which the host keeps below 2^30.
-// The accumulators start at 2^30, so what comes out is D_d + 2^30 in [0, 2^31):
-// the epilogue rebuilds sum_d (D_d + 2^30) 256^d with unsigned 32-bit pieces, adds
-// one 128-bit constant (a multiple of q that makes the total non-negative, plus
-// OFFX*S, minus the 2^30 offsets), adds the mask, and reduces once.
+// The epilogue forms V = sum_d D_d 256^d + (q << sh) + OFFX*S + mask, where the
+// multiple of q makes the total non-negative, and reduces V once.
 //
 // Operand tiles are 32 x 32 bytes stored in the register order of the MFMA: the
 // 16 bytes of lane l belong to row (or column) l % 32 and to k-slots
@@ -157,31 +155,9 @@ struct MfmaArgs {
     uint32_t offx;            // OFFX
     uint64_t q[kMaxLimbs];
     double qinv[kMaxLimbs];   // 1 / q_l, rounded
-    // (q_l << sh) - 2^30 * sum_d 256^d  modulo 2^128
+    // q_l << sh
     uint64_t cst_hi[kMaxLimbs], cst_lo[kMaxLimbs];
 };
-
-// V mod q for 0 <= V = hi:lo < 2^47 * q, q < 2^62.
-// The quotient is estimated in double precision: V converted with three roundings, times
-// the rounded 1/q, has a relative error below 2^-50, so below 2^47 the estimate is off
-// by less than 1/8; taking 1/4 off before truncating gives floor(V/q) or one less,
-// never more.  The remainder is then formed modulo 2^64 and corrected once.
-__device__ __forceinline__ uint64_t reduce_fp(uint64_t hi, uint64_t lo, uint64_t q, double qinv)
-{
-    const double two32 = 4294967296.0;
-    double vd = fma((double)(uint32_t)(lo >> 32), two32, (double)(uint32_t)lo);
-    vd = fma((double)(uint32_t)hi, two32 * two32, vd);
-    vd = fma((double)(uint32_t)(hi >> 32), two32 * two32 * two32, vd);
-    const double qd = fmax(fma(vd, qinv, -0.25), 0.0);
-    const uint32_t qh = (uint32_t)(qd * (1.0 / two32));
-    const uint32_t ql = (uint32_t)fma(-(double)qh, two32, qd);
-    const uint32_t q_lo = (uint32_t)q, q_hi = (uint32_t)(q >> 32);
-    uint64_t p = (uint64_t)ql * q_lo;
-    p += (uint64_t)(ql * q_hi + qh * q_lo) << 32;
-    uint64_t r = lo - p;
-    if (r >= q) r -= q;
-    return r;
-}
 
 #define NIMBUS_AS1 __attribute__((address_space(1)))
 #define NIMBUS_AS3 __attribute__((address_space(3)))
@@ -244,47 +220,51 @@ __device__ __forceinline__ void dma_quarter(const void *src_lane, void *dst_wave
 // column tile wc, with DX+DQ-1 int32 accumulator tiles.
 //
 // A stage is one k-block (32 values of k): 4*DX operand tiles of X (12 KB for DX = 3)
-// and 2*DQ operand tiles of ciphertext planes (14 KB for DQ = 7).  X tiles come from
-// L2, ciphertext tiles from HBM, so the two have their own LDS rings and their own lead
-// (how many stages ahead of the matrix cores the loads run).  Both are filled by
-// direct-to-LDS loads of whole tiles (64 lanes x 16 B; the texture address unit spends
-// the same time on narrower loads); nothing passes through registers on the way in.  A
-// wave knows how many loads it issues per stage, so "stage s has landed" is a wait on
-// the number of its younger loads, then the barrier.
+// and 2*DQ operand tiles of ciphertext planes (14 KB for DQ = 7), each in an LDS ring of
+// its own.  Both are filled by direct-to-LDS loads of whole tiles (64 lanes x 16 B; the
+// texture address unit spends the same time on narrower loads); nothing passes through
+// registers on the way in.  The tiles of a stage are dealt round-robin to the eight
+// waves.  A wave knows how many loads it issues per stage, so "stage s has landed" is a
+// wait on the number of its younger loads, then the barrier.
 //
 // Inside a wave the loop is software pipelined: the LDS reads of stage s+1 are issued
 // between the matrix-core instructions of stage s, into the other of two operand sets.
 //
-// The loop is bound by instruction issue as much as by the matrix cores: a wave issues
-// an instruction every four or five cycles at best and all eight waves run in lockstep
-// between barriers, so every scalar instruction of the loop costs.  Hence: one stage
-// issued per iteration from the first iteration on (constant lead, no ramp), ring
-// offsets carried and wrapped instead of recomputed, and the wait for "at most n loads
-// pending" (an immediate in the instruction) done by a computed jump.
-#ifndef NIMBUS_RING_A
-#define NIMBUS_RING_A 3
-#endif
-#ifndef NIMBUS_RING_B_MAX
-#define NIMBUS_RING_B_MAX 8
-#endif
-#ifndef NIMBUS_LEAD_B
-#define NIMBUS_LEAD_B 3
+// What the loop is bound by, in this order (measured): the matrix cores (42
+// instructions per SIMD and k-block); the number of bytes a CU can have in flight to
+// HBM (about 16 KB: a load instruction that does not fit stalls its wave until earlier
+// loads return, so the ciphertext loads are spread over all waves and over the whole
+// iteration, where the other wave of the SIMD can fill the gap with its own matrix-core
+// instructions); instruction issue (a wave issues an instruction every four or five
+// cycles at best and all eight waves run in lockstep between barriers, so every scalar
+// instruction costs: one stage issued per iteration from the first iteration on,
+// ring offsets carried and wrapped instead of recomputed, and the wait for "at most n
+// loads pending", an immediate of the instruction, done by a computed jump).
+#ifndef NIMBUS_LEAD
+#define NIMBUS_LEAD 3
 #endif
 template <int DX, int DQ>
 struct Pipe {
+    static constexpr int ND = DX + DQ - 1;
     static constexpr int A_TILES = 4 * DX;
     static constexpr int B_TILES = 2 * DQ;
     static constexpr int A_BYTES = A_TILES * kTileBytes;
     static constexpr int B_BYTES = B_TILES * kTileBytes;
-    // Waves 0-3 move the X tiles of a stage (tile t to wave t % 4), waves 4-7 the
-    // ciphertext tiles, one whole-tile load each.  A wave's loads then all belong to one
-    // ring, and the in-order load counter of the wave can say "my loads of stage j have
-    // landed" without also waiting for loads of the other ring.
+    // accumulators + two operand sets + addressing must fit 256 registers (two waves per SIMD)
+    static constexpr bool PIPELINED = ND * 16 + 2 * (DX + DQ) * 4 + 12 <= 256;
+    static constexpr int AHEAD = PIPELINED ? 1 : 0;
+    // Lead: stages 0 .. LEAD-1 are issued up front, iteration s issues stage s + LEAD
+    // after its barrier, into the slot of stage s + LEAD - RING.  That slot has been read
+    // by every wave once all have passed the barrier of iteration s + LEAD - RING + 1 -
+    // AHEAD, so RING = LEAD + 1 - AHEAD slots are enough.
+    static constexpr int LEAD = NIMBUS_LEAD;
+    static constexpr int RING = LEAD + 1 - AHEAD;
+    static_assert(LEAD >= 1 + AHEAD, "the stage read next must have been issued");
+    // X tile t goes to wave t % 4 as its load t / 4, ciphertext tile t to wave 4 + t % 4
     static constexpr int MAXU = ((A_TILES > B_TILES ? A_TILES : B_TILES) + 3) / 4;
-    static constexpr int RING_A = NIMBUS_RING_A;
-    static constexpr int RING_B_FIT = (152 * 1024 - RING_A * A_BYTES) / B_BYTES;
-    static constexpr int RING_B = RING_B_FIT > NIMBUS_RING_B_MAX ? NIMBUS_RING_B_MAX : RING_B_FIT;
-    static constexpr int LDS_BYTES = RING_A * A_BYTES + RING_B * B_BYTES;
+    static_assert((LEAD - 1) * MAXU <= 63, "pending-load count must fit the wait counter");
+    static constexpr int LDS_BYTES = RING * (A_BYTES + B_BYTES);
+    static_assert(LDS_BYTES <= 160 * 1024, "rings do not fit the LDS");
 };
 
 // Wait until at most n of this wave's loads are pending, 0 <= n <= 63, n wave-uniform.
@@ -294,12 +274,12 @@ struct Pipe {
 __device__ __forceinline__ void wait_vmem_n(int n)
 {
     asm volatile(
-        "s_getpc_b64 s[98:99]\n\t"
-        "s_lshl_b32 s100, %0, 3\n\t"
-        "s_add_u32 s100, s100, 20\n\t"
-        "s_add_u32 s98, s98, s100\n\t"
-        "s_addc_u32 s99, s99, 0\n\t"
-        "s_setpc_b64 s[98:99]\n\t"
+        "s_getpc_b64 s[96:97]\n\t"
+        "s_lshl_b32 s98, %0, 3\n\t"
+        "s_add_u32 s98, s98, 20\n\t"
+        "s_add_u32 s96, s96, s98\n\t"
+        "s_addc_u32 s97, s97, 0\n\t"
+        "s_setpc_b64 s[96:97]\n\t"
         ".irp cnt,0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,"
         "32,33,34,35,36,37,38,39,40,41,42,43,44,45,46,47,48,49,50,51,52,53,54,55,56,57,58,59,60,61,62,63\n\t"
         "s_waitcnt vmcnt(\\cnt)\n\t"
@@ -307,32 +287,21 @@ __device__ __forceinline__ void wait_vmem_n(int n)
         ".endr\n"
         ".Lwait_vmem_end_%=:"
         :
-        : "s"(n)
-        : "s98", "s99", "s100", "scc", "memory");
+        : "s"(__builtin_amdgcn_readfirstlane(n))
+        : "s96", "s97", "s98", "scc", "memory");
 }
 
 template <int DX, int DQ>
 __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 {
     using P_ = Pipe<DX, DQ>;
-    constexpr int ND = DX + DQ - 1;
-    constexpr int RA = P_::RING_A, RB = P_::RING_B;
-    // accumulators + two operand sets + addressing must fit 256 registers (two waves per SIMD)
-    constexpr bool PIPELINED = ND * 16 + 2 * (DX + DQ) * 4 + 12 <= 256;
-    constexpr int AHEAD = PIPELINED ? 1 : 0;
+    constexpr int ND = P_::ND;
+    constexpr bool PIPELINED = P_::PIPELINED;
+    constexpr int AHEAD = P_::AHEAD, LEAD = P_::LEAD, RING = P_::RING;
     constexpr int SETS = PIPELINED ? 2 : 1;
-    // Lead of a ring: stages 0 .. lead-1 are issued up front, iteration s issues stage
-    // s + lead after its barrier, into the slot of stage s + lead - ring.  That slot has
-    // been read by every wave once all have passed the barrier of iteration
-    // s + lead - ring + 1 - AHEAD, so lead <= ring - 1 + AHEAD.
-    constexpr int LEAD_A = RA - 1 + AHEAD;
-    constexpr int LEAD_B = NIMBUS_LEAD_B < RB - 1 + AHEAD ? NIMBUS_LEAD_B : RB - 1 + AHEAD;
-    static_assert(LEAD_A >= 1 + AHEAD && LEAD_B >= 1 + AHEAD, "rings too shallow");
-    static_assert((LEAD_B > LEAD_A ? LEAD_B : LEAD_A) * P_::MAXU <= 63,
-                  "pending-load count must fit the wait counter");
     __shared__ __attribute__((aligned(1024))) unsigned char lds[P_::LDS_BYTES];
     unsigned char *const ldsA = lds;
-    unsigned char *const ldsB = lds + RA * P_::A_BYTES;
+    unsigned char *const ldsB = lds + RING * P_::A_BYTES;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // 0..7
@@ -373,21 +342,26 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
                                        ((size_t)(ct2 * 2u + (uint32_t)(u / DQ)) * KB * DQ +
                                         (size_t)(u % DQ)) * 64);
     };
-    // this wave's loads of a stage: load u (u < MAXU) moves tile (wave % 4) + 4 u of its ring
-    const bool loads_x = wave < 4;                  // waves 0-3: X ring, waves 4-7: ciphertext ring
-    const int lead = loads_x ? LEAD_A : LEAD_B;
+    // Waves 0-3 (the first wave of each SIMD) load the X tiles, from L2; waves 4-7 (the
+    // second of each SIMD) the ciphertext tiles, from HBM: load u (u < MAXU) of a wave
+    // moves tile wave % 4 + 4 u of its kind.
+    const bool loads_x = wave < 4;
     const unsigned char *src[P_::MAXU];             // lane's source address at k-block 0
+    unsigned char *dst[P_::MAXU];                   // the tile's place in slot 0 of its ring
     int n_loads = 0;                                // loads per stage
 #pragma unroll
     for (int u = 0; u < P_::MAXU; ++u) {
         const int t = (wave & 3) + 4 * u;
         if (loads_x ? (t < P_::A_TILES) : (t < P_::B_TILES)) {
             src[u] = (loads_x ? a_src(t) : b_src(t)) + lane * 16;
+            dst[u] = (loads_x ? ldsA : ldsB) + (uint32_t)t * kTileBytes;
             ++n_loads;
         } else {
             src[u] = nullptr;
+            dst[u] = nullptr;
         }
     }
+    n_loads = __builtin_amdgcn_readfirstlane(n_loads);
     // Stage s of this workgroup is k-block (s + k_start) mod KB: the sum over k does not
     // care about the order, and workgroups that walk their (equally spaced) ciphertext
     // regions in lockstep would otherwise ask the same memory channels for data at the
@@ -399,44 +373,51 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     const uint32_t src_step = (uint32_t)(loads_x ? DX : DQ) * kTileBytes;   // per k-block
     const uint32_t src_end = (uint32_t)KB * src_step;
     const uint32_t slot_step = loads_x ? P_::A_BYTES : P_::B_BYTES;
-    const uint32_t slot_end = loads_x ? RA * P_::A_BYTES : RB * P_::B_BYTES;
+    const uint32_t slot_end = RING * slot_step;
     uint32_t src_off = k_start * src_step;
     uint32_t slot_off = 0;
     auto bump = [](uint32_t v, uint32_t step, uint32_t end) -> uint32_t {
         v += step;
         return v == end ? 0u : v;
     };
-    // where the first tile of this wave goes inside a ring slot
-    unsigned char *const wave_dst = (loads_x ? ldsA : ldsB) + (uint32_t)(wave & 3) * kTileBytes;
-    // load u of the stage at (src_off, slot_off)
+    // load u of the stage at the carried offsets
     auto issue_one = [&](auto u_c) {
         constexpr int u = decltype(u_c)::value;
-        dma_tile(src[u] + src_off, wave_dst + slot_off + (uint32_t)(4 * u) * kTileBytes);
+        dma_tile(src[u] + src_off, dst[u] + slot_off);
     };
+#define NIMBUS_NEXT_ISSUE()                                                   \
+    do {                                                                      \
+        src_off = bump(src_off, src_step, src_end);                           \
+        slot_off = bump(slot_off, slot_step, slot_end);                       \
+    } while (0)
 
     v16i acc[ND];
 #pragma unroll
     for (int d = 0; d < ND; ++d)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[d][r] = 1 << 30;
+        for (int r = 0; r < 16; ++r) acc[d][r] = 0;
 
-    // ---- up front: stages 0 .. lead-1 ----
-    for (int st = 0; st < lead && st < KB; ++st) {
+    // ---- up front: stages 0 .. LEAD-1 ----
+    for (int st = 0; st < LEAD && st < KB; ++st) {
         static_for<0, P_::MAXU>([&](auto u_c) {
             if (decltype(u_c)::value < n_loads) issue_one(u_c);
         });
-        src_off = bump(src_off, src_step, src_end);
-        slot_off = bump(slot_off, slot_step, slot_end);
+        NIMBUS_NEXT_ISSUE();
     }
 
     // Operands come out of LDS through explicit ds_read_b128 instructions: reads the
     // compiler can see would each be made to wait for every direct-to-LDS load in flight.
     const uint32_t lds0 = (uint32_t)(uintptr_t)(NIMBUS_AS3 void *)&lds[0];
     const uint32_t laneA = lds0 + (uint32_t)(wr * DX) * kTileBytes + (uint32_t)lane * 16u;
-    const uint32_t laneB = lds0 + (uint32_t)(RA * P_::A_BYTES) +
+    const uint32_t laneB = lds0 + (uint32_t)(RING * P_::A_BYTES) +
                            (uint32_t)(wc * DQ) * kTileBytes + (uint32_t)lane * 16u;
     // ring offsets of the stage that is read next
     uint32_t rdA = 0, rdB = 0;
+#define NIMBUS_NEXT_READ()                                                    \
+    do {                                                                      \
+        rdA = bump(rdA, P_::A_BYTES, RING * P_::A_BYTES);                     \
+        rdB = bump(rdB, P_::B_BYTES, RING * P_::B_BYTES);                     \
+    } while (0)
     v4i xa[SETS][DX], xb[SETS][DQ];                 // [operand set][plane]
     // read number i (0 <= i < DX+DQ) of the stage at (rdA, rdB) into operand set SET
     auto read_one = [&](auto set_c, auto i_c) {
@@ -461,38 +442,41 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     };
 
     // Loads of this wave younger than those of stage j, before iteration s = j - AHEAD:
-    // stages j+1 .. min(KB, s + lead) - 1, that is min(lead - 1 - AHEAD, KB - 1 - j) stages.
+    // stages j+1 .. min(KB, s + LEAD) - 1, that is min(LEAD - 1 - AHEAD, KB - 1 - j) stages.
     auto younger = [&](int j) -> int {
         int st = KB - 1 - j;
-        if (st > lead - 1 - AHEAD) st = lead - 1 - AHEAD;
+        if (st > LEAD - 1 - AHEAD) st = LEAD - 1 - AHEAD;
         if (st < 0) st = 0;
         return st * n_loads;
     };
     asm volatile("" ::: "memory");
     if constexpr (PIPELINED) {
-        // stage 0 is read before the loop; its younger loads are those of stages 1 .. lead-1
-        int st = (KB < lead ? KB : lead) - 1;
+        // stage 0 is read before the loop; its younger loads are those of stages 1 .. LEAD-1
+        const int st = (KB < LEAD ? KB : LEAD) - 1;
         wait_vmem_n(st * n_loads);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if (active) read_ops(std::integral_constant<int, 0>{});
-        rdA = bump(rdA, P_::A_BYTES, RA * P_::A_BYTES);
-        rdB = bump(rdB, P_::B_BYTES, RB * P_::B_BYTES);
+        NIMBUS_NEXT_READ();
     }
 
-    // iteration s, pipelined: make stage s+1 visible, issue stage s+lead into a slot
+    // iteration s, pipelined: make stage s+1 visible, issue stage s+LEAD into a slot
     // whose stage every wave has in registers, read stage s+1 into the other operand
     // set, run the matrix cores on stage s.  Not pipelined (register budget of the
     // widest variants): make stage s visible, issue, read stage s, wait, run.
     //
-    // The matrix-core instructions of a stage are issued with one other instruction
-    // between consecutive ones: first the LDS reads of stage s+1 (pipelined variants),
-    // then the direct-to-LDS loads.  Issued in a burst those would fill the LDS and
-    // texture-address queues of the CU (all eight waves leave the barrier together)
-    // and hold back the matrix-core instructions queued behind them.  The empty volatile
-    // asm statements pin this order.
-    constexpr int R0 = PIPELINED ? DX + DQ : 0;     // MFMA positions taken by LDS reads
-    static_assert(DX * DQ >= R0 + P_::MAXU, "not enough slots between the MFMAs");
+    // Between consecutive matrix-core instructions goes at most one other instruction.
+    // The ciphertext loads come first: a load that does not fit the CU's budget of bytes
+    // in flight stalls its wave, and at the start of the iteration the other wave of the
+    // SIMD (an X-loading one) still has all its matrix-core instructions to fill the gap
+    // with.  Then the LDS reads of stage s+1 (pipelined variants), then the X loads.  The
+    // empty volatile asm statements pin this order.
+    constexpr int R0 = PIPELINED ? DX + DQ : 0;     // LDS reads placed between the MFMAs
+    constexpr int NPOS = DX * DQ;
+    static_assert(NPOS >= R0 + 1 && NPOS >= P_::MAXU, "not enough positions between the MFMAs");
+    // positions: [0, MAXU) ciphertext loads, [RP0, RP0 + R0) reads, the last MAXU X loads
+    constexpr int RP0 = P_::MAXU < NPOS - R0 ? P_::MAXU : NPOS - R0;
+    constexpr int XP0 = NPOS - P_::MAXU;
     // ACTIVE: the wave has rows.
     auto iteration = [&](int s, auto set_c, auto active_c) {
         constexpr int SET = decltype(set_c)::value;
@@ -505,8 +489,8 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
             read_ops(set_c);
             wait_ops(set_c);
         }
-        const int issue_n = s + lead < KB ? n_loads : 0;    // stage s + lead exists: its loads
-        static_for<0, DX * DQ>([&](auto i_c) {
+        const int issue_n = s + LEAD < KB ? n_loads : 0;    // stage s + LEAD exists: its loads
+        static_for<0, NPOS>([&](auto i_c) {
             constexpr int i = decltype(i_c)::value;
             constexpr int dq = i / DX, dx = i % DX;
             if constexpr (ACTIVE) {
@@ -516,13 +500,18 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
                     xa[SET][dx], xb[SET][dq], acc[dx + dq], 0, 0, 0);
                 tie_acc(acc[dx + dq]);
             }
-            if constexpr (i < R0) {
+            if constexpr (i < P_::MAXU) {
+                if (!loads_x && i < issue_n) issue_one(i_c);
+            }
+            if constexpr (i >= RP0 && i < RP0 + R0) {
                 // (the last iteration reads a stale slot: valid LDS, never used)
                 if constexpr (ACTIVE)
-                    read_one(std::integral_constant<int, (PIPELINED ? 1 - SET : SET)>{}, i_c);
-            } else if constexpr (i - R0 < P_::MAXU) {
-                constexpr int u = i - R0;
-                if (u < issue_n) issue_one(std::integral_constant<int, u>{});
+                    read_one(std::integral_constant<int, (PIPELINED ? 1 - SET : SET)>{},
+                             std::integral_constant<int, i - RP0>{});
+            }
+            if constexpr (i >= XP0) {
+                constexpr int u = i - XP0;
+                if (loads_x && u < issue_n) issue_one(std::integral_constant<int, u>{});
             }
         });
         asm volatile("" ::: "memory");
@@ -530,36 +519,33 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // the carried offsets move on between iterations (outside the lambda: plain locals)
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
-#define NIMBUS_ADVANCE()                                                      \
-    do {                                                                      \
-        src_off = bump(src_off, src_step, src_end);                           \
-        slot_off = bump(slot_off, slot_step, slot_end);                       \
-        rdA = bump(rdA, P_::A_BYTES, RA * P_::A_BYTES);                       \
-        rdB = bump(rdB, P_::B_BYTES, RB * P_::B_BYTES);                       \
-    } while (0)
     if (!active) {
         for (int s = 0; s < KB; ++s) {
             iteration(s, C0{}, std::false_type{});
-            NIMBUS_ADVANCE();
+            NIMBUS_NEXT_ISSUE();
         }
         return;
     }
     if constexpr (PIPELINED) {
         for (int s = 0; s < KB; s += 2) {
             iteration(s, C0{}, std::true_type{});
-            NIMBUS_ADVANCE();
+            NIMBUS_NEXT_ISSUE();
+            NIMBUS_NEXT_READ();
             if (s + 1 < KB) {
                 iteration(s + 1, C1{}, std::true_type{});
-                NIMBUS_ADVANCE();
+                NIMBUS_NEXT_ISSUE();
+                NIMBUS_NEXT_READ();
             }
         }
     } else {
         for (int s = 0; s < KB; ++s) {
             iteration(s, C0{}, std::true_type{});
-            NIMBUS_ADVANCE();
+            NIMBUS_NEXT_ISSUE();
+            NIMBUS_NEXT_READ();
         }
     }
-#undef NIMBUS_ADVANCE
+#undef NIMBUS_NEXT_ISSUE
+#undef NIMBUS_NEXT_READ
 
     // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
     const uint32_t col = (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
@@ -569,39 +555,64 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     const int row0 = rt * kTile + 4 * (lane >> 5);
     // every load of the epilogue first (mask words, then the column sum), so that their
     // latencies overlap
+    // element r of the lane is row row0 + roff(r); addresses are the lane's address of
+    // row0 plus a wave-uniform multiple of the row length
+    auto roff = [](int r) -> int { return 8 * (r >> 2) + (r & 3); };
+    const size_t lane_elem = (size_t)row0 * a.C + col;
+    const uint64_t *const mask0 = a.mask ? a.mask + lane_elem : nullptr;
+    uint64_t *const out0 = a.out + lane_elem;
     uint64_t mk[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = row0 + 8 * (r >> 2) + (r & 3);
-        mk[r] = (a.mask && row < a.m) ? a.mask[(size_t)row * a.C + col] : 0;
-    }
+    for (int r = 0; r < 16; ++r)
+        mk[r] = (mask0 && row0 + roff(r) < a.m) ? mask0[(size_t)roff(r) * a.C] : 0;
     uint64_t cst_hi = a.cst_hi[limb], cst_lo = a.cst_lo[limb];
     {
         const uint64_t S = a.colsum[col];
         add128(cst_hi, cst_lo, __umul64hi(S, (uint64_t)a.offx), S * (uint64_t)a.offx);
     }
+    // V = cst + mask + sum_d D_d 256^d, 0 <= V < 2^47 q.  Two things are needed of V: its
+    // low 64 bits, exactly, and V / q to within 1/2.  Low bits: diagonals 0-3 with
+    // signed 64-bit multiply-adds, diagonals 4-7 only reach the upper word, diagonals
+    // from 8 on not at all.  Quotient: V in double precision; every term is exact, the
+    // partial sums stay below 4 * 2^sh q in magnitude (signed digits: the digit
+    // magnitudes of an operand add up to at most twice its bound), and only the last
+    // few roundings are relative to such a sum, so the estimate is off by well under
+    // 1/2.  With 1/2 taken off before truncating it is floor(V/q) or one less, never
+    // more; the remainder is then formed modulo 2^64 and corrected once.
+    const double two32 = 4294967296.0;
+    double cst_d = fma((double)(uint32_t)(cst_lo >> 32), two32, (double)(uint32_t)cst_lo);
+    cst_d = fma((double)(uint32_t)cst_hi, two32 * two32, cst_d);
+    cst_d = fma((double)(uint32_t)(cst_hi >> 32), two32 * two32 * two32, cst_d);
+    const uint32_t q_lo = (uint32_t)q, q_hi = (uint32_t)(q >> 32);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        const int row = row0 + 8 * (r >> 2) + (r & 3);
-        if (row < a.m) {
-            // E_d = D_d + 2^30 < 2^31.  Z_b = E_b + 2^32 E_{b+4} is a register pair;
-            // sum_d E_d 256^d = Z_0 + 2^8 Z_1 + 2^16 Z_2 + 2^24 Z_3 + 2^64 (E_8 + ...)
-            auto E = [&](int d) -> uint64_t {
-                return d < ND ? (uint64_t)(uint32_t)acc[d][r] : 0;
-            };
-            uint64_t lo = E(0) | (E(4) << 32);
-            uint64_t hi = E(8) + (E(9) << 8) + (E(10) << 16);
+        auto D = [&](int d) -> int32_t { return acc[d][r]; };
+        // low 64 bits
+        uint64_t lo = cst_lo + mk[r];
 #pragma unroll
-            for (int b = 1; b < 4; ++b) {
-                const uint64_t Z = E(b) | (E(b + 4) << 32);
-                const uint64_t sh = Z << (8 * b);
-                lo += sh;
-                hi += (Z >> (64 - 8 * b)) + (lo < sh ? 1u : 0u);
-            }
-            add128(hi, lo, cst_hi, cst_lo);
-            add128(hi, lo, 0, mk[r]);
-            a.out[(size_t)row * a.C + col] = reduce_fp(hi, lo, q, qinv);
+        for (int d = 0; d < 4 && d < ND; ++d)
+            lo += (uint64_t)((int64_t)D(d) * (int64_t)(1ll << (8 * d)));
+        uint32_t up = 0;
+#pragma unroll
+        for (int d = 4; d < 8 && d < ND; ++d) up += (uint32_t)D(d) << (8 * (d - 4));
+        lo += (uint64_t)up << 32;
+        // quotient estimate
+        double vd = fma((double)(uint32_t)(mk[r] >> 32), two32, (double)(uint32_t)mk[r]);
+        double scale = 1.0;
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+            vd = fma((double)D(d), scale, vd);
+            scale *= 256.0;
         }
+        vd += cst_d;
+        const double qd = fmax(fma(vd, qinv, -0.5), 0.0);
+        const uint32_t qh = (uint32_t)(qd * (1.0 / two32));
+        const uint32_t ql = (uint32_t)fma(-(double)qh, two32, qd);
+        uint64_t p = (uint64_t)ql * q_lo;
+        p += (uint64_t)(ql * q_hi + qh * q_lo) << 32;
+        uint64_t res = lo - p;
+        if (res >= q) res -= q;
+        if (row0 + roff(r) < a.m) out0[(size_t)roff(r) * a.C] = res;
     }
 }
 
@@ -704,11 +715,9 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
     a.offx = 0;
     for (int d = 0; d < DX; ++d) a.offx |= 0x80u << (8 * d);
     const int sh = bias_shift(p);
-    unsigned __int128 offsets = 0;                  // 2^30 * sum_d 256^d
-    for (int d = 0; d < DX + DQ - 1; ++d) offsets += (unsigned __int128)1 << (30 + 8 * d);
     for (int l = 0; l < p.L; ++l) {
         const uint64_t q = p.limbs.limb[l].q;
-        const unsigned __int128 c = ((unsigned __int128)q << sh) - offsets;   // modulo 2^128
+        const unsigned __int128 c = (unsigned __int128)q << sh;
         a.q[l] = q;
         a.qinv[l] = 1.0 / (double)q;
         a.cst_hi[l] = (uint64_t)(c >> 64);
