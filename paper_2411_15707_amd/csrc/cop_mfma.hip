@@ -209,10 +209,12 @@ __device__ __forceinline__ void dma_tile(const void *src_lane, void *dst_wave)
     __builtin_amdgcn_global_load_lds((const NIMBUS_AS1 void *)src_lane,
                                      (NIMBUS_AS3 void *)dst_wave, 16, 0, 0);
 }
-__device__ __forceinline__ void dma_quarter(const void *src_lane, void *dst_wave)
+// the same with the streaming hint: data that is read once (the ciphertext planes) should
+// not push the X planes, which every workgroup reads again and again, out of L2
+__device__ __forceinline__ void dma_tile_stream(const void *src_lane, void *dst_wave)
 {
     __builtin_amdgcn_global_load_lds((const NIMBUS_AS1 void *)src_lane,
-                                     (NIMBUS_AS3 void *)dst_wave, 4, 0, 0);
+                                     (NIMBUS_AS3 void *)dst_wave, 16, 0, 2);
 }
 
 // The pipeline.  A workgroup of eight waves (two per SIMD) owns 128 token rows x 64
@@ -243,6 +245,7 @@ __device__ __forceinline__ void dma_quarter(const void *src_lane, void *dst_wave
 #ifndef NIMBUS_LEAD
 #define NIMBUS_LEAD 3
 #endif
+
 template <int DX, int DQ>
 struct Pipe {
     static constexpr int ND = DX + DQ - 1;
@@ -383,7 +386,8 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // load u of the stage at the carried offsets
     auto issue_one = [&](auto u_c) {
         constexpr int u = decltype(u_c)::value;
-        dma_tile(src[u] + src_off, dst[u] + slot_off);
+        if (loads_x) dma_tile(src[u] + src_off, dst[u] + slot_off);
+        else dma_tile_stream(src[u] + src_off, dst[u] + slot_off);
     };
 #define NIMBUS_NEXT_ISSUE()                                                   \
     do {                                                                      \
@@ -396,6 +400,16 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     for (int d = 0; d < ND; ++d)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[d][r] = 0;
+    // the column's ciphertext sum is needed after the loop; asked for now (older than every
+    // direct-to-LDS load, so the counted waits cover it) it costs two registers, not a
+    // round trip to memory at the end
+    // (issued by hand: it must stay ahead of the first direct-to-LDS load, and the first
+    // counted wait, which every variant reaches before the loop ends, completes it)
+    uint64_t colsum_S;
+    {
+        const uint64_t *ps = a.colsum + (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
+        asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(colsum_S) : "v"(ps) : "memory");
+    }
 
     // ---- up front: stages 0 .. LEAD-1 ----
     for (int st = 0; st < LEAD && st < KB; ++st) {
@@ -441,12 +455,14 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         for (int d = 0; d < DQ; ++d) tie(xb[SET][d]);
     };
 
-    // Loads of this wave younger than those of stage j, before iteration s = j - AHEAD:
+    // Loads of this wave younger than those of stage j = s + AHEAD, before iteration s:
     // stages j+1 .. min(KB, s + LEAD) - 1, that is min(LEAD - 1 - AHEAD, KB - 1 - j) stages.
-    auto younger = [&](int j) -> int {
+    // No stage j: nothing to wait for.
+    auto younger = [&](int s) -> int {
+        const int j = s + AHEAD;
+        if (j >= KB) return 63;
         int st = KB - 1 - j;
         if (st > LEAD - 1 - AHEAD) st = LEAD - 1 - AHEAD;
-        if (st < 0) st = 0;
         return st * n_loads;
     };
     asm volatile("" ::: "memory");
@@ -465,23 +481,22 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // set, run the matrix cores on stage s.  Not pipelined (register budget of the
     // widest variants): make stage s visible, issue, read stage s, wait, run.
     //
-    // Between consecutive matrix-core instructions goes at most one other instruction.
-    // The ciphertext loads come first: a load that does not fit the CU's budget of bytes
-    // in flight stalls its wave, and at the start of the iteration the other wave of the
-    // SIMD (an X-loading one) still has all its matrix-core instructions to fill the gap
-    // with.  Then the LDS reads of stage s+1 (pipelined variants), then the X loads.  The
-    // empty volatile asm statements pin this order.
+    // Between consecutive matrix-core instructions goes at most one other instruction
+    // (all eight waves leave the barrier together: a burst of loads or LDS reads would
+    // fill the queues of the CU and hold back the matrix-core instructions behind it):
+    // first the X loads, then the LDS reads of stage s+1 (pipelined variants), the
+    // ciphertext loads last.  The empty volatile asm statements pin this order.
     constexpr int R0 = PIPELINED ? DX + DQ : 0;     // LDS reads placed between the MFMAs
     constexpr int NPOS = DX * DQ;
     static_assert(NPOS >= R0 + 1 && NPOS >= P_::MAXU, "not enough positions between the MFMAs");
-    // positions: [0, MAXU) ciphertext loads, [RP0, RP0 + R0) reads, the last MAXU X loads
+    // positions: [0, MAXU) X loads, [RP0, RP0 + R0) reads, the last MAXU ciphertext loads
     constexpr int RP0 = P_::MAXU < NPOS - R0 ? P_::MAXU : NPOS - R0;
     constexpr int XP0 = NPOS - P_::MAXU;
     // ACTIVE: the wave has rows.
     auto iteration = [&](int s, auto set_c, auto active_c) {
         constexpr int SET = decltype(set_c)::value;
         constexpr bool ACTIVE = decltype(active_c)::value;
-        wait_vmem_n(younger(s + AHEAD));
+        wait_vmem_n(younger(s));
         if constexpr (PIPELINED && ACTIVE) wait_ops(set_c);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -501,7 +516,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
                 tie_acc(acc[dx + dq]);
             }
             if constexpr (i < P_::MAXU) {
-                if (!loads_x && i < issue_n) issue_one(i_c);
+                if (loads_x && i < issue_n) issue_one(i_c);
             }
             if constexpr (i >= RP0 && i < RP0 + R0) {
                 // (the last iteration reads a stale slot: valid LDS, never used)
@@ -511,7 +526,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
             }
             if constexpr (i >= XP0) {
                 constexpr int u = i - XP0;
-                if (loads_x && u < issue_n) issue_one(std::integral_constant<int, u>{});
+                if (!loads_x && u < issue_n) issue_one(std::integral_constant<int, u>{});
             }
         });
         asm volatile("" ::: "memory");
@@ -561,13 +576,15 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     const size_t lane_elem = (size_t)row0 * a.C + col;
     const uint64_t *const mask0 = a.mask ? a.mask + lane_elem : nullptr;
     uint64_t *const out0 = a.out + lane_elem;
-    uint64_t mk[16];
+    uint64_t mk[16];                                // read once: streaming loads
 #pragma unroll
     for (int r = 0; r < 16; ++r)
-        mk[r] = (mask0 && row0 + roff(r) < a.m) ? mask0[(size_t)roff(r) * a.C] : 0;
+        mk[r] = (mask0 && row0 + roff(r) < a.m)
+                    ? __builtin_nontemporal_load(&mask0[(size_t)roff(r) * a.C])
+                    : 0;
     uint64_t cst_hi = a.cst_hi[limb], cst_lo = a.cst_lo[limb];
     {
-        const uint64_t S = a.colsum[col];
+        const uint64_t S = colsum_S;
         add128(cst_hi, cst_lo, __umul64hi(S, (uint64_t)a.offx), S * (uint64_t)a.offx);
     }
     // V = cst + mask + sum_d D_d 256^d, 0 <= V < 2^47 q.  Two things are needed of V: its
@@ -612,7 +629,9 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         p += (uint64_t)(ql * q_hi + qh * q_lo) << 32;
         uint64_t res = lo - p;
         if (res >= q) res -= q;
-        if (row0 + roff(r) < a.m) out0[(size_t)roff(r) * a.C] = res;
+        // (streaming store: the output is not read again by this kernel, and lines that do
+        // not sit dirty in L2 need no write-back when the kernel ends)
+        if (row0 + roff(r) < a.m) __builtin_nontemporal_store(res, &out0[(size_t)roff(r) * a.C]);
     }
 }
 
