@@ -5,8 +5,11 @@
 // right operand.  Both are split into signed bytes so that the products run on
 // v_mfma_i32_32x32x32_i8:
 //
-//   x  = x' + OFFX,  x' = sum_{a<DX} dx_a 256^a,  dx_a = byte_a(x) - 128,
-//                    OFFX = sum_{a<DX} 128 * 256^a            (no carries needed)
+//   x  = x' + OFFX,  x' = sum_{a<DX} dx_a 256^a,  dx_a = byte_a(x) - 128 for the bytes that
+//                    can reach 128 (8a + 8 <= x_bits), dx_a = byte_a(x) for the others (the
+//                    top byte of a 20-bit share is a digit in [0, 15]: small operands keep
+//                    the multipliers quieter, and the kernel's speed is set by power);
+//                    OFFX = sum of 128 * 256^a over the shifted bytes   (no carries needed)
 //   c' = c or c - q  (centred, |c'| <= (q-1)/2),  c' = sum_{b<DQ} dq_b 256^b,
 //                    dq_b in [-128, 127]  (carry-propagating recode, done once
 //                    per weight matrix by nimbus_cop_prepare)
@@ -104,7 +107,7 @@ __global__ __launch_bounds__(256) void column_sums_kernel(
 // ---------------------------------------------------------------------------
 template <int DX>
 __global__ __launch_bounds__(256) void x_planes_kernel(
-    const uint64_t *__restrict__ X, int m, int k, int KB, uint32_t total,
+    const uint64_t *__restrict__ X, int m, int k, int KB, uint32_t total, uint32_t offx,
     uint32_t *__restrict__ xd)
 {
     // one thread = four consecutive k of one row: one 32-bit word in each of the DX planes
@@ -126,7 +129,8 @@ __global__ __launch_bounds__(256) void x_planes_kernel(
         for (int b = 0; b < 4; ++b) {
             const int i = kbase + b;
             if (i < k) {
-                const uint32_t x = (uint32_t)X[(size_t)row * k + i] ^ 0x80808080u;
+                // flipping bit 7 of a byte turns it into the two's complement digit byte - 128
+                const uint32_t x = (uint32_t)X[(size_t)row * k + i] ^ offx;
 #pragma unroll
                 for (int d = 0; d < DX; ++d) w[d] |= ((x >> (8 * d)) & 0xffu) << (8 * b);
             }
@@ -507,7 +511,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         const int issue_n = s + LEAD < KB ? n_loads : 0;    // stage s + LEAD exists: its loads
         static_for<0, NPOS>([&](auto i_c) {
             constexpr int i = decltype(i_c)::value;
-            constexpr int dq = i / DX, dx = i % DX;
+            constexpr int dx = i / DQ, dq = i % DQ;
             if constexpr (ACTIVE) {
                 tie(xa[SET][dx]);
                 tie(xb[SET][dq]);
@@ -645,6 +649,16 @@ static int ceil_log2(unsigned v)
     return b;
 }
 
+// OFFX: 128 in every byte of a share that can reach 128.  The same word is the XOR mask that
+// turns those bytes into signed digits.
+static uint32_t share_offset(int x_bits, int DX)
+{
+    uint32_t off = 0;
+    for (int d = 0; d < DX; ++d)
+        if (x_bits >= 8 * d + 8) off |= 0x80u << (8 * d);
+    return off;
+}
+
 // q * 2^sh is added to make the signed sum non-negative: 2^sh >= k * 2^(8 DX - 1)
 // bounds |sum_i x'_i c'_i| / q from above (|x'| < 2^(8 DX - 1) * 1.01, |c'| <= q / 2)
 static int bias_shift(const Problem &p)
@@ -697,7 +711,7 @@ static hipError_t stage_impl(const Problem &p, const uint64_t *X, void *workspac
     const int RT = (p.m + kTile - 1) / kTile;
     const uint32_t xtotal = (uint32_t)RT * KB * 256;
     hipLaunchKernelGGL(x_planes_kernel<DX>, dim3((xtotal + 255) / 256), dim3(256), 0, stream,
-                       X, p.m, p.k, KB, xtotal, (uint32_t *)workspace);
+                       X, p.m, p.k, KB, xtotal, share_offset(p.x_bits, DX), (uint32_t *)workspace);
     return hipGetLastError();
 }
 
@@ -731,8 +745,7 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
     a.L = p.L;
     a.C = (uint32_t)p.C;
     a.CT = CT;
-    a.offx = 0;
-    for (int d = 0; d < DX; ++d) a.offx |= 0x80u << (8 * d);
+    a.offx = share_offset(p.x_bits, DX);
     const int sh = bias_shift(p);
     for (int l = 0; l < p.L; ++l) {
         const uint64_t q = p.limbs.limb[l].q;
