@@ -51,6 +51,11 @@ SMALL = [
     (19, 65, 64, 64, 2, 24, 62),        # 62-bit moduli: 3 x 8 byte planes
     (20, 257, 64, 64, 2, 9, 40),        # small modulus, odd share width
     (1, 1, 32, 32, 1, 16, 50),          # k = 1, m = 1
+    (16, 160, 64, 64, 1, 12, 50),       # 12-bit shares: the upper share plane holds unshifted digits
+    (7, 33, 64, 64, 1, 7, 30),          # 7-bit shares (no shifted plane at all), 30-bit modulus
+    (9, 128, 64, 64, 2, 20, 62),        # 3 x 8 planes (operands read after the barrier), four k-blocks
+    (12, 192, 64, 64, 1, 32, 62),       # 4 x 8 planes, six k-blocks
+    (100, 1024, 64, 64, 1, 16, 50),     # 2 x 7 planes, 32 k-blocks
 ]
 
 
@@ -142,12 +147,14 @@ def test_bert_base_configs_full(oracle, cfg_id):
     _check_both(oracle, X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask, f"config {cfg_id}")
 
 
-def test_config3_real_encryption_spot_check(oracle):
-    """config 3 shape with every weight row encrypted for real; four output rows of the
-    GPU result are decrypted and compared with the brute-force X W mod t"""
+@pytest.mark.parametrize("cfg_id", [2, 3, 4])
+def test_bert_base_real_encryption_spot_check(oracle, cfg_id):
+    """configs 2-4 with every weight row encrypted for real; four output rows of the GPU
+    result are decrypted and compared with the brute-force X W mod t (Theorem 1's invariant
+    restated for the hot path: Dec(out_j) + R_j = (X W)_j mod t, zero beyond column n)"""
     import gpu_util as gu
-    cfg = ci.CONFIGS[3]
-    seed = ci.config_seed(3) + 500
+    cfg = ci.CONFIGS[cfg_id]
+    seed = ci.config_seed(cfg_id) + 500
     t = cfg.t
     rows = [0, 1, cfg.m // 2, cfg.m - 1]
     X = ci.gen_X(seed, cfg.m, cfg.k, cfg.t_bits)
@@ -155,14 +162,14 @@ def test_config3_real_encryption_spot_check(oracle):
     s = ci.gen_secret(seed, cfg.N)
     a, e = ci.gen_enc_randomness(seed, cfg.k, 1, cfg.moduli, cfg.N)
     R = ci.gen_R(seed, cfg.m, cfg.N, cfg.t_bits)
-    _say("[parity] config 3 real encryption: encrypting 768 rows on the CPU")
+    _say(f"[parity] config {cfg_id} real encryption: encrypting {cfg.k} rows on the CPU")
     ct = oracle.encrypt(oracle.encode_rows(W, cfg.N)[:, 0], s, a[:, 0], e[:, 0], cfg.moduli,
                         cfg.t_bits)
     ctW = ct.reshape(cfg.k, 1, 2, cfg.L, cfg.N)
     mask = ci.gen_mask_uniform(seed, cfg.m, 1, cfg.moduli, cfg.N)
     for j in rows:
         mask[j, 0] = oracle.share_mask(R[j], cfg.moduli, cfg.t_bits)
-    _say("[parity] config 3 real encryption: matrix-core kernel")
+    _say(f"[parity] config {cfg_id} real encryption: matrix-core kernel")
     out = gu.run_mfma(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask)
     XW = X[rows].astype(object) @ W.astype(object)
     for r, j in enumerate(rows):
