@@ -46,6 +46,11 @@ def _load():
                                    _u64p, _i64p]
     lib.oracle_share_mask.restype = ctypes.c_int
     lib.oracle_share_mask.argtypes = [_u64p, ctypes.c_int, ctypes.c_int, _u64p, ctypes.c_int, _u64p]
+    lib.oracle_rshift.restype = None
+    lib.oracle_rshift.argtypes = [_u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _u64p, _u64p]
+    lib.oracle_pack_ref.restype = ctypes.c_int
+    lib.oracle_pack_ref.argtypes = [_u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                    _u64p, _u64p, _u64p]
     _lib = lib
     return lib
 
@@ -174,3 +179,39 @@ def share_mask(R_row, moduli, t_bits):
     if rc != 0:
         raise ValueError("oracle_share_mask: L > 2 is not supported")
     return mask
+
+
+def rshift(ct, s, moduli):
+    """ct [2][L][N] -> RShift(ct, s): both polynomials times X^s, negacyclic"""
+    lib = _load()
+    ct = _u64(ct)
+    _, L, N = ct.shape
+    assert L == len(moduli) and 0 <= s < N
+    mod = np.asarray(moduli, dtype=np.uint64)
+    out = np.empty_like(ct)
+    lib.oracle_rshift(_p(ct), int(s), N, L, _p(mod), _p(out))
+    return out
+
+
+def packed_count(m, n, N):
+    """number of packed ciphertexts for m rows of n payload slots in degree N"""
+    return -(-m // (N // n))
+
+
+def pack_ref(rows, n, moduli, mask=None):
+    """rows [m][2][L][N] (one ring chunk), mask [ceil(m/P)][2][L][N] or None
+    -> packed [ceil(m/P)][2][L][N], P = N // n  (Algorithm 1 step 3, then the mask)"""
+    lib = _load()
+    rows = _u64(rows)
+    m, two, L, N = rows.shape
+    assert two == 2 and L == len(moduli) and 0 < n <= N
+    T = packed_count(m, n, N)
+    mod = np.asarray(moduli, dtype=np.uint64)
+    if mask is not None:
+        mask = _u64(mask, (T, 2, L, N))
+    out = np.empty((T, 2, L, N), dtype=np.uint64)
+    rc = lib.oracle_pack_ref(_p(rows), m, int(n), N, L, _p(mod),
+                             _p(mask) if mask is not None else None, _p(out))
+    if rc != T:
+        raise ValueError(f"oracle_pack_ref returned {rc}")
+    return out

@@ -22,7 +22,9 @@
  * cases (X = 0, X = identity, k = 1, all-ones), numpy object matmul, the
  * decryption invariant Dec(out_j) + R_j = (X W)_j mod t with a brute-force
  * right-hand side, enc/dec round trip, additive and scalar homomorphism,
- * negacyclic X^N = -1, Table 5 size accounting.
+ * negacyclic X^N = -1, Table 5 size accounting; for the right-shift packing:
+ * RShift against the dense negacyclic product by X^s, N unit shifts = negation,
+ * P = 1 is the identity, and the decryption invariant on packed ciphertexts.
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -282,4 +284,74 @@ int oracle_share_mask(const uint64_t *R, int N, int L, const uint64_t *moduli,
         }
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Right shift (Appendix B.1): RShift(ct, s) multiplies both polynomials of a
+ * ciphertext by the monomial X^s in Z_q[X]/(X^N+1), 0 <= s < N: coefficient c
+ * moves to c+s, and a coefficient that passes the end re-enters at c+s-N with
+ * its sign flipped (X^N = -1).  ct and out are [2][L][N]; out must not alias ct.
+ * ---------------------------------------------------------------------- */
+void oracle_rshift(const uint64_t *ct, int s, int N, int L, const uint64_t *moduli, uint64_t *out)
+{
+    for (int p = 0; p < 2; ++p)
+        for (int l = 0; l < L; ++l) {
+            const uint64_t q = moduli[l];
+            const uint64_t *src = ct + ((size_t)p * L + l) * N;
+            uint64_t *dst = out + ((size_t)p * L + l) * N;
+            for (int c = 0; c < N; ++c) {
+                const int to = c + s;
+                if (to < N) dst[to] = src[c];
+                else        dst[to - N] = src[c] == 0 ? 0 : q - src[c];
+            }
+        }
+}
+
+/* ------------------------------------------------------------------------
+ * Output packing, Algorithm 1 step 3 (n <= N, one ring chunk): with
+ * P = floor(N/n) rows per packed ciphertext,
+ *   packed[theta] = (+)_{u in [P]}  RShift(rows[theta*P + u], u*n)   (+) mask[theta]
+ * for theta in [ceil(m/P)]; rows past m count as zero ciphertexts.  The shift
+ * amounts are multiples of n (the printed algorithm writes another letter; the
+ * figure shifts the second ciphertext by the width of the first one's payload).
+ * rows is [m][2][L][N], mask is [ceil(m/P)][2][L][N] or NULL, packed likewise.
+ * Returns the number of packed ciphertexts, or -1 if n > N.
+ * ---------------------------------------------------------------------- */
+int oracle_pack_ref(const uint64_t *rows, int m, int n, int N, int L, const uint64_t *moduli,
+                    const uint64_t *mask, uint64_t *packed)
+{
+    if (n > N || n <= 0) return -1;
+    const int P = N / n;
+    const int T = (m + P - 1) / P;
+    const size_t ct_words = (size_t)2 * L * N;
+    uint64_t *tmp = (uint64_t *)malloc(ct_words * sizeof(uint64_t));
+    if (!tmp) return -1;
+    for (int th = 0; th < T; ++th) {
+        uint64_t *dst = packed + (size_t)th * ct_words;
+        memset(dst, 0, ct_words * sizeof(uint64_t));
+        for (int u = 0; u < P; ++u) {
+            const int j = th * P + u;
+            if (j >= m) break;
+            oracle_rshift(rows + (size_t)j * ct_words, u * n, N, L, moduli, tmp);
+            for (int p = 0; p < 2; ++p)
+                for (int l = 0; l < L; ++l) {
+                    const uint64_t q = moduli[l];
+                    for (int c = 0; c < N; ++c) {
+                        const size_t at = ((size_t)p * L + l) * N + c;
+                        dst[at] = (uint64_t)(((u128)dst[at] + tmp[at]) % q);
+                    }
+                }
+        }
+        if (mask)
+            for (int p = 0; p < 2; ++p)
+                for (int l = 0; l < L; ++l) {
+                    const uint64_t q = moduli[l];
+                    for (int c = 0; c < N; ++c) {
+                        const size_t at = ((size_t)p * L + l) * N + c;
+                        dst[at] = (uint64_t)(((u128)dst[at] + mask[(size_t)th * ct_words + at]) % q);
+                    }
+                }
+    }
+    free(tmp);
+    return T;
 }

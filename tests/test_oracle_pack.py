@@ -1,0 +1,126 @@
+"""Pins for the oracle's right-shift packing (Algorithm 1 step 3; Appendix B.1 "Right Shift").
+
+What fixes it besides itself: RShift must equal the dense negacyclic product by the monomial
+X^s (Python big ints); N unit shifts negate (X^N = -1); shifts compose additively; P = 1 packs
+nothing; a packed ciphertext decrypts to the payloads of its P rows laid side by side, which
+the brute-force X W mod t supplies; and per limb the phase of the packed ciphertext is the
+sum of the monomial-shifted phases of its rows.
+"""
+import numpy as np
+import pytest
+
+import cop_inputs as ci
+from test_oracle_rlwe import dense_negacyclic
+
+
+def _ct(seed, rows, moduli, N):
+    return ci.gen_mask_uniform(seed, rows, 1, moduli, N)[:, 0]          # [rows][2][L][N] uniform residues
+
+
+@pytest.mark.parametrize("s", [0, 1, 5, 15])
+def test_rshift_is_the_product_with_a_monomial(oracle, s):
+    N, moduli = 16, ci.limb_primes(54, 20, 2)
+    ct = _ct(1, 1, moduli, N)[0]
+    got = oracle.rshift(ct, s, moduli)
+    mono = np.zeros(N, np.int64)
+    mono[s] = 1
+    for p in range(2):
+        for l, q in enumerate(moduli):
+            assert np.array_equal(got[p, l], dense_negacyclic(ct[p, l], mono, q))
+
+
+def test_n_unit_shifts_negate_and_shifts_compose(oracle):
+    N, moduli = 32, ci.limb_primes(50, 16, 1)
+    ct = _ct(2, 1, moduli, N)[0]
+    cur = ct.copy()
+    for _ in range(N):
+        cur = oracle.rshift(cur, 1, moduli)
+    q = np.uint64(moduli[0])
+    assert np.array_equal(cur, (q - ct) % q)
+    assert np.array_equal(oracle.rshift(oracle.rshift(ct, 7, moduli), 9, moduli),
+                          oracle.rshift(ct, 16, moduli))
+
+
+def test_pack_with_one_row_per_ciphertext_only_adds_the_mask(oracle):
+    N, n, m, moduli = 64, 40, 5, ci.limb_primes(54, 20, 2)        # P = floor(64/40) = 1
+    rows = _ct(3, m, moduli, N)
+    assert np.array_equal(oracle.pack_ref(rows, n, moduli), rows)
+    mask = _ct(4, m, moduli, N)
+    want = np.empty_like(rows)
+    for l, q in enumerate(moduli):
+        want[:, :, l] = ((rows[:, :, l].astype(object) + mask[:, :, l].astype(object)) % q).astype(np.uint64)
+    assert np.array_equal(oracle.pack_ref(rows, n, moduli, mask), want)
+
+
+def test_pack_against_big_int_definition(oracle):
+    """ragged: m = 7 rows, P = 3 per ciphertext, the last one holds a single row"""
+    N, n, m, moduli = 32, 10, 7, ci.limb_primes(54, 20, 2)
+    P, T = N // n, -(-m // (N // n))
+    assert (P, T) == (3, 3) and oracle.packed_count(m, n, N) == T
+    rows = _ct(5, m, moduli, N)
+    mask = _ct(6, T, moduli, N)
+    got = oracle.pack_ref(rows, n, moduli, mask)
+    for th in range(T):
+        for p in range(2):
+            for l, q in enumerate(moduli):
+                acc = [int(v) for v in mask[th, p, l]]
+                for u in range(P):
+                    j = th * P + u
+                    if j >= m:
+                        continue
+                    for c in range(N):
+                        to = c + u * n
+                        if to < N:
+                            acc[to] += int(rows[j, p, l, c])
+                        else:
+                            acc[to - N] -= int(rows[j, p, l, c])
+                assert [v % q for v in acc] == [int(v) for v in got[th, p, l]]
+
+
+@pytest.mark.parametrize("L,t_bits,q_bits,N,n,m,k", [(1, 16, 50, 64, 16, 9, 12), (2, 20, 54, 128, 40, 7, 20)])
+def test_packed_ciphertexts_decrypt_to_side_by_side_payloads(oracle, L, t_bits, q_bits, N, n, m, k):
+    """COP on really encrypted weights, then packing with a share mask per packed ciphertext:
+    Dec(packed[theta])[u n + c] + R[theta][u n + c] = (X W)[theta P + u][c] mod t  (Theorem 1's
+    invariant after step 3), and slots that hold no payload decrypt to -R, i.e. sum to zero"""
+    moduli = ci.limb_primes(q_bits, t_bits, L)
+    t = 1 << t_bits
+    P, T = N // n, -(-m // (N // n))
+    seed = 77 + N
+    X = ci.gen_X(seed, m, k, t_bits)
+    W = ci.gen_W(seed, k, n, t_bits)
+    s = ci.gen_secret(seed, N)
+    a, e = ci.gen_enc_randomness(seed, k, 1, moduli, N)
+    ct = oracle.encrypt(oracle.encode_rows(W, N)[:, 0], s, a[:, 0], e[:, 0], moduli, t_bits)
+    rows, _ = oracle.cop_ref(X, ct.reshape(k, 1, 2, L, N), moduli, n, N, None)
+    R = ci.gen_R(seed, T, N, t_bits)
+    mask = np.stack([oracle.share_mask(R[th], moduli, t_bits) for th in range(T)])
+    packed = oracle.pack_ref(rows[:, 0], n, moduli, mask)
+    XW = X.astype(object) @ W.astype(object)
+    for th in range(T):
+        got = (oracle.decrypt(packed[th], s, moduli, t_bits) + R[th]) % np.uint64(t)
+        want = np.zeros(N, dtype=object)
+        for u in range(P):
+            if th * P + u < m:
+                want[u * n:(u + 1) * n] = XW[th * P + u] % t
+        assert np.array_equal(got, want.astype(np.uint64))
+
+
+def test_phase_of_a_packed_ciphertext_is_the_sum_of_shifted_phases(oracle):
+    """linearity per limb, for arbitrary (uniform) ciphertexts: no encryption needed"""
+    N, n, m, moduli = 64, 20, 6, ci.limb_primes(54, 20, 2)
+    P = N // n
+    rows = _ct(8, m, moduli, N)
+    s = ci.gen_secret(9, N)
+    packed = oracle.pack_ref(rows, n, moduli)
+    for th in range(-(-m // P)):
+        phi = oracle.phase(packed[th], s, moduli)                 # [L][N]
+        for l, q in enumerate(moduli):
+            acc = np.zeros(N, dtype=object)
+            for u in range(P):
+                j = th * P + u
+                if j >= m:
+                    continue
+                mono = np.zeros(N, np.int64)
+                mono[u * n] = 1
+                acc = acc + dense_negacyclic(oracle.phase(rows[j], s, moduli)[l], mono, q).astype(object)
+            assert np.array_equal((acc % q).astype(np.uint64), phi[l])
