@@ -126,6 +126,34 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
                                void *stream);
 
 /* static, NUL-terminated description of a status code */
+/*
+ * Output packing (Algorithm 1 step 3; Appendix B.1 "Right Shift"; Section 3.2 "Output
+ * Communication"): when n <= N/2 the payload of an output ciphertext fills only its
+ * first n slots, so P = floor(N/n) of them are merged into one by negacyclic right
+ * shifts, and the mask of step 4 goes onto the packed ciphertexts:
+ *
+ *   packed[theta] = (+)_{u in [P]} RShift(rows[theta*P + u], u*n)  (+)  mask[theta]
+ *
+ * RShift(ct, s) multiplies both polynomials by X^s in Z_q[X]/(X^N+1): coefficient c
+ * moves to c+s, and one that passes the end re-enters at c+s-N negated.  Rows past m
+ * count as zero.  (The printed algorithm garbles the shift amounts; they are the
+ * multiples of the payload width n, as in the paper's figure.)
+ *
+ *   rows    device [m][2][L][N]: the output of a matmul entry point called with
+ *           mask = NULL and the same n <= N (one ring chunk)
+ *   mask    device [T][2][L][N], T = nimbus_cop_packed_count(m, n, N), residues
+ *           < q_l, or NULL for no mask
+ *   packed  device [T][2][L][N], canonical residues; must not alias rows
+ *   nimbus_cop_packed_count  T = ceil(m / floor(N/n)); 0 for invalid arguments or n > N
+ * Errors: NIMBUS_COP_ERR_INVALID_ARG as for the other entry points;
+ * NIMBUS_COP_ERR_UNSUPPORTED for n > N (several chunks: there is nothing to pack) and
+ * for more than 65535 packed ciphertexts.  On error nothing is enqueued.
+ */
+int nimbus_cop_packed_count(int m, int n, int N);
+int nimbus_cop_pack(const uint64_t *rows, int m, int n, int N, int L,
+                    const uint64_t *moduli,
+                    const uint64_t *mask, uint64_t *packed, void *stream);
+
 const char *nimbus_cop_strerror(int status);
 
 /* library version, major*10000 + minor*100 + patch */

@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     nimbus_cop_matmul,
     nimbus_cop_matmul_prepared,
     nimbus_cop_matmul_staged,
+    nimbus_cop_pack,
+    nimbus_cop_packed_count,
     nimbus_cop_stage_shares,
     nimbus_cop_prepare,
     nimbus_cop_prepared_bytes,

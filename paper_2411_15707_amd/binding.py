@@ -21,6 +21,8 @@ EXPORTED_SYMBOLS = (
     "nimbus_cop_stage_shares",
     "nimbus_cop_matmul_staged",
     "nimbus_cop_matmul_prepared",
+    "nimbus_cop_packed_count",
+    "nimbus_cop_pack",
     "nimbus_cop_strerror",
     "nimbus_cop_version",
 )
@@ -62,6 +64,10 @@ def load_library():
     lib.nimbus_cop_matmul_staged.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.nimbus_cop_matmul_prepared.restype = ci
     lib.nimbus_cop_matmul_prepared.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    lib.nimbus_cop_packed_count.restype = ci
+    lib.nimbus_cop_packed_count.argtypes = [ci, ci, ci]
+    lib.nimbus_cop_pack.restype = ci
+    lib.nimbus_cop_pack.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
     lib.nimbus_cop_strerror.restype = ctypes.c_char_p
     lib.nimbus_cop_strerror.argtypes = [ci]
     lib.nimbus_cop_version.restype = ci
@@ -189,3 +195,22 @@ def nimbus_cop_matmul_prepared(X, m, k, x_bits, prepared, n, N, L, moduli, mask,
         _dev_ptr(workspace, "workspace"), ws_bytes, _stream(stream))
     if rc != 0:
         raise NimbusCopError(rc, "nimbus_cop_matmul_prepared")
+
+
+def nimbus_cop_packed_count(m, n, N) -> int:
+    return int(load_library().nimbus_cop_packed_count(m, n, N))
+
+
+def nimbus_cop_pack(rows, m, n, N, L, moduli, mask, packed, stream=None):
+    lib = load_library()
+    T = nimbus_cop_packed_count(m, n, N)
+    _words(rows, "rows", m * 2 * L * N)
+    if T > 0:
+        _words(packed, "packed", T * 2 * L * N)
+        if mask is not None:
+            _words(mask, "mask", T * 2 * L * N)
+    rc = lib.nimbus_cop_pack(_dev_ptr(rows, "rows"), m, n, N, L, _moduli(moduli),
+                             _dev_ptr(mask, "mask", True), _dev_ptr(packed, "packed"),
+                             _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_pack")

@@ -173,6 +173,29 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 
+int nimbus_cop_packed_count(int m, int n, int N)
+{
+    if (m < 1 || n < 1 || N < 32 || N > 65536 || (N & (N - 1)) != 0 || n > N) return 0;
+    const int P = N / n;
+    return (m + P - 1) / P;
+}
+
+int nimbus_cop_pack(const uint64_t *rows, int m, int n, int N, int L,
+                    const uint64_t *moduli,
+                    const uint64_t *mask, uint64_t *packed, void *stream)
+{
+    if (!rows || !packed || rows == packed) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (m < 1) return NIMBUS_COP_ERR_INVALID_ARG;
+    Problem p;
+    const int rc = make_problem(0, 1, 0, n, N, L, moduli, false, &p);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if (n > N) return NIMBUS_COP_ERR_UNSUPPORTED;          // several ring chunks: nothing to pack
+    if (nimbus_cop_packed_count(m, n, N) > 65535) return NIMBUS_COP_ERR_UNSUPPORTED;   // grid limit
+    p.m = m;
+    const hipError_t e = launch_cop_pack(p, rows, mask, packed, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
 const char *nimbus_cop_strerror(int status)
 {
     switch (status) {
@@ -185,6 +208,6 @@ const char *nimbus_cop_strerror(int status)
     }
 }
 
-int nimbus_cop_version(void) { return 100; }
+int nimbus_cop_version(void) { return 101; }
 
 }  // extern "C"

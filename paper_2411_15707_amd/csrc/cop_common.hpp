@@ -65,5 +65,7 @@ hipError_t launch_stage_shares(const Problem &p, const uint64_t *X, void *worksp
 hipError_t launch_cop_mfma(const Problem &p, const void *staged, const void *prepared,
                            const uint64_t *mask, uint64_t *out, hipStream_t stream);
 bool mfma_supported(const Problem &p);
+hipError_t launch_cop_pack(const Problem &p, const uint64_t *rows, const uint64_t *mask,
+                           uint64_t *packed, hipStream_t stream);
 
 }  // namespace nimbus

@@ -1,0 +1,72 @@
+// Output packing by right shifts (Algorithm 1 step 3; Appendix B.1 "Right Shift"), with the
+// mask of step 4 applied to the packed ciphertexts.
+//
+// RShift(ct, s) multiplies both polynomials of a ciphertext by X^s in Z_q[X]/(X^N+1):
+// coefficient c moves to c+s, a coefficient that passes the end re-enters at c+s-N negated.
+// With P = floor(N/n) rows per packed ciphertext,
+//   packed[theta] = sum_{u<P} RShift(rows[theta P + u], u n) + mask[theta]   (mod q_l),
+// rows past m counting as zero.  Seen from the output: coefficient c of packed[theta] is
+//   sum_u  sign * rows[theta P + u][(c - u n) mod N],   sign = -1 where c < u n,
+// a gather of P words, so one thread owns one output coefficient of one polynomial and limb
+// and no two threads write the same word.  Bound by HBM: every input word is read once
+// (consecutive threads read consecutive words), every output word written once.
+#include "cop_common.hpp"
+
+namespace nimbus {
+
+struct PackArgs {
+    const uint64_t *rows;     // [m][2][L][N]
+    const uint64_t *mask;     // [T][2][L][N] or nullptr
+    uint64_t *packed;         // [T][2][L][N]
+    int m, n, N, L, P, T;
+    uint64_t q[kMaxLimbs];
+};
+
+__global__ __launch_bounds__(256) void cop_pack_kernel(const PackArgs a)
+{
+    // grid: x covers the 2 L N words of one packed ciphertext, y = theta
+    const uint32_t w = blockIdx.x * 256u + threadIdx.x;       // word inside the ciphertext
+    const uint32_t words = 2u * (uint32_t)a.L * (uint32_t)a.N;
+    if (w >= words) return;
+    const int theta = (int)blockIdx.y;
+    const uint32_t c = w & (uint32_t)(a.N - 1);               // N is a power of two
+    const uint32_t block = w - c;                              // (poly, limb) offset
+    const uint64_t q = a.q[(w / (uint32_t)a.N) % (uint32_t)a.L];
+
+    uint64_t acc = a.mask ? a.mask[(size_t)theta * words + w] : 0;
+    if (acc >= q) acc -= q;                                    // tolerate an unreduced mask word
+    for (int u = 0; u < a.P; ++u) {
+        const int j = theta * a.P + u;
+        if (j >= a.m) break;
+        const uint32_t shift = (uint32_t)u * (uint32_t)a.n;   // < N
+        const bool wrapped = c < shift;
+        const uint32_t src = wrapped ? c + (uint32_t)a.N - shift : c - shift;
+        uint64_t v = a.rows[(size_t)j * words + block + src];
+        if (wrapped && v != 0) v = q - v;
+        acc += v;                                              // both below q < 2^62
+        if (acc >= q) acc -= q;
+    }
+    a.packed[(size_t)theta * words + w] = acc;
+}
+
+hipError_t launch_cop_pack(const Problem &p, const uint64_t *rows, const uint64_t *mask,
+                           uint64_t *packed, hipStream_t stream)
+{
+    PackArgs a{};
+    a.rows = rows;
+    a.mask = mask;
+    a.packed = packed;
+    a.m = p.m;
+    a.n = p.n;
+    a.N = p.N;
+    a.L = p.L;
+    a.P = p.N / p.n;
+    a.T = (p.m + a.P - 1) / a.P;
+    for (int l = 0; l < p.L; ++l) a.q[l] = p.limbs.limb[l].q;
+    const uint32_t words = 2u * (uint32_t)p.L * (uint32_t)p.N;
+    hipLaunchKernelGGL(cop_pack_kernel, dim3((words + 255) / 256, (uint32_t)a.T), dim3(256), 0,
+                       stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace nimbus

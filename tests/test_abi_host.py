@@ -103,3 +103,23 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))
     with pytest.raises(FileNotFoundError):
         binding.load_library()
+
+
+def test_packed_count_and_pack_argument_checks():
+    lib = _raw()
+    assert nc.nimbus_cop_packed_count(128, 768, 4096) == 26        # P = 5
+    assert nc.nimbus_cop_packed_count(8, 64, 1024) == 1            # P = 16
+    assert nc.nimbus_cop_packed_count(512, 4096, 8192) == 256      # P = 2
+    assert nc.nimbus_cop_packed_count(7, 40, 64) == 7              # P = 1
+    assert nc.nimbus_cop_packed_count(7, 65, 64) == 0              # n > N
+    assert nc.nimbus_cop_packed_count(0, 8, 64) == 0
+    mod = (ctypes.c_uint64 * 1)(*ci.limb_primes(50, 16, 1))
+    ok = dict(rows=0x1000, m=4, n=16, N=64, L=1, mask=None, packed=0x2000)
+    for kw, want in [(dict(rows=None), -1), (dict(packed=None), -1), (dict(packed=0x1000), -1),
+                     (dict(m=0), -1), (dict(n=0), -1), (dict(N=48), -1), (dict(L=0), -1),
+                     (dict(n=65), -2)]:
+        a = dict(ok)
+        a.update(kw)
+        rc = lib.nimbus_cop_pack(a["rows"], a["m"], a["n"], a["N"], a["L"], mod, a["mask"],
+                                 a["packed"], None)
+        assert rc == want, (kw, rc)

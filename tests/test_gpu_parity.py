@@ -262,3 +262,67 @@ def test_two_step_entry_points_match_the_fused_call(oracle):
     torch.cuda.synchronize()
     assert np.array_equal(gu.host(out), want)
     assert np.array_equal(gu.run_mfma(X, ctW, moduli, n, N, t_bits, mask, prepared), want)
+
+
+# m, n, N, L, t_bits, q_bits
+PACK_SHAPES = [
+    (8, 64, 1024, 1, 16, 50),       # config 1: 16 rows per ciphertext, half-filled
+    (7, 10, 32, 2, 20, 54),         # ragged: three per ciphertext, the last holds one row
+    (5, 40, 64, 2, 20, 54),         # one row per ciphertext: only the mask is added
+    (33, 64, 64, 3, 24, 55),        # n = N
+    (128, 768, 4096, 2, 20, 54),    # config 4: five per ciphertext, 26 ciphertexts
+    (512, 4096, 8192, 3, 24, 55),   # config 5: two per ciphertext
+]
+
+
+@pytest.mark.parametrize("m,n,N,L,t_bits,q_bits", PACK_SHAPES)
+def test_pack_matches_the_oracle(oracle, m, n, N, L, t_bits, q_bits):
+    import gpu_util as gu
+    import paper_2411_15707_amd as nc
+    moduli = ci.limb_primes(q_bits, t_bits, L)
+    T = oracle.packed_count(m, n, N)
+    rows = ci.gen_mask_uniform(4000 + m, m, 1, moduli, N)[:, 0]
+    mask = ci.gen_mask_uniform(5000 + m, T, 1, moduli, N)[:, 0]
+    for l, q in enumerate(moduli):                      # extremes: largest residues, zeros
+        rows[0, :, l, :3] = q - 1
+        rows[-1, :, l, -3:] = q - 1
+        rows[0, :, l, 3:5] = 0
+        mask[0, :, l, :3] = q - 1
+    _say(f"[parity] pack m={m} n={n} N={N} L={L}")
+    for msk in (mask, None):
+        d_rows, d_out = gu.dev(rows), gu.dev(np.zeros((T, 2, L, N), dtype=np.uint64))
+        nc.nimbus_cop_pack(d_rows, m, n, N, L, moduli, gu.dev(msk) if msk is not None else None, d_out)
+        got = gu.host(d_out)
+        want = oracle.pack_ref(rows, n, moduli, msk)
+        assert np.array_equal(got, want), gu.first_mismatch(got, want)
+
+
+def test_config1_matmul_then_pack_decrypts_to_side_by_side_payloads(oracle):
+    """whole client step on the GPU: COP on really encrypted weights without mask, packing
+    with a share mask, then Dec(packed)[u n + c] + R[u n + c] = (X W)[u][c] mod t"""
+    import gpu_util as gu
+    import paper_2411_15707_amd as nc
+    cfg = ci.CONFIGS[1]
+    seed = ci.config_seed(1) + 900
+    t, n, N, L, m = cfg.t, cfg.n, cfg.N, cfg.L, cfg.m
+    P, T = N // n, oracle.packed_count(m, n, N)
+    X = ci.gen_X(seed, m, cfg.k, cfg.t_bits)
+    W = ci.gen_W(seed, cfg.k, n, cfg.t_bits)
+    s = ci.gen_secret(seed, N)
+    a, e = ci.gen_enc_randomness(seed, cfg.k, 1, cfg.moduli, N)
+    ct = oracle.encrypt(oracle.encode_rows(W, N)[:, 0], s, a[:, 0], e[:, 0], cfg.moduli, cfg.t_bits)
+    rows = gu.run_mfma(X, ct.reshape(cfg.k, 1, 2, L, N), cfg.moduli, n, N, cfg.t_bits, None)
+    R = ci.gen_R(seed, T, N, cfg.t_bits)
+    mask = np.stack([oracle.share_mask(R[th], cfg.moduli, cfg.t_bits) for th in range(T)])
+    d_out = gu.dev(np.zeros((T, 2, L, N), dtype=np.uint64))
+    nc.nimbus_cop_pack(gu.dev(rows[:, 0]), m, n, N, L, cfg.moduli, gu.dev(mask), d_out)
+    packed = gu.host(d_out)
+    assert np.array_equal(packed, oracle.pack_ref(rows[:, 0], n, cfg.moduli, mask))
+    XW = X.astype(object) @ W.astype(object)
+    for th in range(T):
+        got = (oracle.decrypt(packed[th], s, cfg.moduli, cfg.t_bits) + R[th]) % np.uint64(t)
+        want = np.zeros(N, dtype=object)
+        for u in range(P):
+            if th * P + u < m:
+                want[u * n:(u + 1) * n] = XW[th * P + u] % t
+        assert np.array_equal(got, want.astype(np.uint64))
