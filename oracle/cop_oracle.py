@@ -70,10 +70,11 @@ def max_threads() -> int:
     return int(_load().oracle_max_threads())
 
 
-def cop_ref(X, ctW, moduli, n, N, mask=None, threads=None):
+def cop_ref(X, ctW, moduli, n, N, mask=None, threads=None, wide=False):
     """out[m][Ch][2][L][N] = (X @ ctW + mask) mod q_l, the definition.
 
-    X [m][k]; ctW [k][Ch][2][L][N]; mask like out or None.
+    X [m][k]; ctW [k][Ch][2][L][N]; mask like out or None.  wide=True: shares of up to 64
+    bits (every product reduced before it is added); otherwise shares of at most 32 bits.
     Returns (out, threads_used).
     """
     lib = _load()
@@ -90,7 +91,8 @@ def cop_ref(X, ctW, moduli, n, N, mask=None, threads=None):
         mp = _p(mask)
     if threads is None:
         threads = max_threads()
-    used = lib.oracle_cop_ref(_p(X), m, k, _p(ctW), n, N, L, _p(mod), mp, _p(out), int(threads))
+    fn = lib.oracle_cop_ref_wide if wide else lib.oracle_cop_ref
+    used = fn(_p(X), m, k, _p(ctW), n, N, L, _p(mod), mp, _p(out), int(threads))
     return out, int(used)
 
 

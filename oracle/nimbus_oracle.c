@@ -22,7 +22,9 @@
  * cases (X = 0, X = identity, k = 1, all-ones), numpy object matmul, the
  * decryption invariant Dec(out_j) + R_j = (X W)_j mod t with a brute-force
  * right-hand side, enc/dec round trip, additive and scalar homomorphism,
- * negacyclic X^N = -1, Table 5 size accounting; for the right-shift packing:
+ * negacyclic X^N = -1, Table 5 size accounting; for shares of up to 64 bits:
+ * big-int recomputation, agreement with the narrow version, the high/low half
+ * identity, phase linearity; for the right-shift packing:
  * RShift against the dense negacyclic product by X^s, N unit shifts = negation,
  * P = 1 is the identity, and the decryption invariant on packed ciphertexts.
  */
@@ -87,6 +89,52 @@ int oracle_cop_ref(const uint64_t *X, int m, int k,
             }
             for (size_t col = 0; col < C; ++col) {
                 const int l = (int)((col / N) % L);      /* [Ch][2][L][N] -> limb */
+                u128 v = acc[col];
+                if (mask) v += mask[(size_t)j * C + col];
+                out[(size_t)j * C + col] = (uint64_t)(v % moduli[l]);
+            }
+        }
+        free(acc);
+    }
+    return used;
+}
+
+/* ------------------------------------------------------------------------
+ * The same for shares of up to 64 bits (the paper's own parameter set uses
+ * l = 64, Section 5.1 "Experimental setup"): a product of a 64-bit share and
+ * a < 2^62 residue still fits 128 bits, a sum of them does not, so every
+ * product is reduced before it is added:
+ *   acc = (acc + (x * c mod q_l)) , acc < k * q_l  < 2^86
+ * ---------------------------------------------------------------------- */
+int oracle_cop_ref_wide(const uint64_t *X, int m, int k,
+                        const uint64_t *ctW, int n, int N, int L,
+                        const uint64_t *moduli,
+                        const uint64_t *mask, uint64_t *out, int threads)
+{
+    const int Ch = (n + N - 1) / N;
+    const size_t C = (size_t)Ch * 2 * L * N;
+    int used = 1;
+    if (threads < 1) threads = 1;
+#pragma omp parallel num_threads(threads)
+    {
+#ifdef _OPENMP
+#pragma omp single
+        used = omp_get_num_threads();
+#endif
+        u128 *acc = (u128 *)malloc(sizeof(u128) * C);
+#pragma omp for schedule(static)
+        for (int j = 0; j < m; ++j) {
+            for (size_t col = 0; col < C; ++col) acc[col] = 0;
+            for (int i = 0; i < k; ++i) {
+                const uint64_t x = X[(size_t)j * k + i];
+                const uint64_t *ct = ctW + (size_t)i * C;
+                for (size_t col = 0; col < C; ++col) {
+                    const uint64_t q = moduli[(col / N) % L];
+                    acc[col] += ((u128)x * ct[col]) % q;
+                }
+            }
+            for (size_t col = 0; col < C; ++col) {
+                const int l = (int)((col / N) % L);
                 u128 v = acc[col];
                 if (mask) v += mask[(size_t)j * C + col];
                 out[(size_t)j * C + col] = (uint64_t)(v % moduli[l]);

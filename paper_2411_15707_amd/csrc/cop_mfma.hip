@@ -142,11 +142,7 @@ __global__ __launch_bounds__(256) void x_planes_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// main kernel
-// workgroup = 4 waves = 128 token rows x one 32-column tile; wave w owns the
-// 32 x 32 output tile of rows rb*128 + w*32 .. +31 with DX+DQ-1 accumulators.
-// B (ciphertext planes) streams global -> LDS in stages of KS k-blocks, double
-// buffered; A (X planes, L2 resident) is read straight into registers.
+// main kernel: arguments (the pipeline is described further down)
 // ---------------------------------------------------------------------------
 struct MfmaArgs {
     const uint4 *xd;          // [RT][KB][DX][64] uint4
