@@ -43,8 +43,13 @@
  * exception crosses this boundary.
  *
  * Accepted parameters: m, k, n >= 1; N a power of two in [32, 65536];
- * L in [1, 4]; x_bits in [1, 32]; every q_l odd with 2^x_bits < q_l < 2^62;
+ * L in [1, 4]; x_bits in [1, 32] with every q_l odd and 2^x_bits < q_l < 2^62;
  * k < 2^24; Ch*2*L*N < 2^31.
+ * Shares of 33 to 64 bits (the paper's own setting is l = 64, Section 5.1
+ * "Experimental setup") are accepted by the prepared-weights entry points only
+ * (nimbus_cop_workspace_bytes, nimbus_cop_stage_shares, nimbus_cop_matmul_staged,
+ * nimbus_cop_matmul_prepared); there q_l only has to be odd and below 2^62.
+ * nimbus_cop_matmul answers NIMBUS_COP_ERR_UNSUPPORTED for them.
  */
 #ifndef NIMBUS_COP_H
 #define NIMBUS_COP_H
@@ -110,6 +115,10 @@ int nimbus_cop_prepare(const uint64_t *ctW, int k, int n, int N, int L,
  *              (0 is returned for invalid parameters.)
  * Additional limit (NIMBUS_COP_ERR_UNSUPPORTED beyond it): k <= 16383, so that
  * the int32 accumulators of the byte products cannot overflow.
+ * Shares of more than 32 bits take two passes over the prepared weights,
+ * x = x_lo + 2^32 x_hi: the pass over the upper halves leaves its reduced result
+ * in `out`, the pass over the lower halves adds 2^32 times it and the mask and
+ * overwrites it; the workspace holds the byte planes of both halves.
  */
 size_t nimbus_cop_workspace_bytes(int m, int k, int x_bits);
 int nimbus_cop_stage_shares(const uint64_t *X, int m, int k, int x_bits,

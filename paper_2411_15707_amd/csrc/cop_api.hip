@@ -12,8 +12,10 @@ static int bit_length(uint64_t v)
     return b;
 }
 
-// Shape / modulus checks shared by every entry point.  x_bits <= 0 means "the
+// Shape / modulus checks shared by every entry point.  with_x = false means "the
 // call has no X" (prepare, size queries) and skips the checks that involve it.
+// Shares wider than 32 bits (up to 64) are accepted here; the entry points that
+// cannot handle them answer NIMBUS_COP_ERR_UNSUPPORTED.
 static int make_problem(int m, int k, int x_bits, int n, int N, int L,
                         const uint64_t *moduli, bool with_x, Problem *out)
 {
@@ -21,7 +23,7 @@ static int make_problem(int m, int k, int x_bits, int n, int N, int L,
     if (k < 1 || n < 1 || k >= (1 << 24)) return NIMBUS_COP_ERR_INVALID_ARG;
     if (N < 32 || N > 65536 || (N & (N - 1)) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
     if (L < 1 || L > kMaxLimbs) return NIMBUS_COP_ERR_INVALID_ARG;
-    if (with_x && (m < 1 || x_bits < 1 || x_bits > 32)) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (with_x && (m < 1 || x_bits < 1 || x_bits > 64)) return NIMBUS_COP_ERR_INVALID_ARG;
     Problem p{};
     p.m = with_x ? m : 0;
     p.k = k;
@@ -37,7 +39,8 @@ static int make_problem(int m, int k, int x_bits, int n, int N, int L,
     for (int l = 0; l < L; ++l) {
         const uint64_t q = moduli[l];
         if ((q & 1) == 0 || q >= (1ull << 62) || q < 3) return NIMBUS_COP_ERR_INVALID_ARG;
-        if (with_x && q <= (1ull << x_bits)) return NIMBUS_COP_ERR_INVALID_ARG;
+        // t < q_l for shares of up to 32 bits (wider shares exceed any single limb)
+        if (with_x && x_bits <= 32 && q <= (1ull << x_bits)) return NIMBUS_COP_ERR_INVALID_ARG;
         const int b = bit_length(q);
         Limb &P = p.limbs.limb[l];
         P.q = q;
@@ -66,11 +69,55 @@ static bool staging_fits(int m, int k)
     return RT * KB <= (1ull << 23);
 }
 
-static size_t workspace_bytes_of(int m, int k, int x_bits)
+// Shares of more than 32 bits are staged as two halves: the lower 32 bits first (4 byte
+// planes), then the upper x_bits - 32 bits.
+static size_t half_bytes(int m, int k, int half_bits)
 {
     const size_t RT = (size_t)(m + kTile - 1) / kTile;
     const size_t KB = (size_t)kblocks(k);
-    return RT * KB * (size_t)planes_x(x_bits) * kTileBytes;
+    return RT * KB * (size_t)planes_x(half_bits) * kTileBytes;
+}
+
+static size_t workspace_bytes_of(int m, int k, int x_bits)
+{
+    if (x_bits <= 32) return half_bytes(m, k, x_bits);
+    return half_bytes(m, k, 32) + half_bytes(m, k, x_bits - 32);
+}
+
+// the two passes of a wide share: same problem with the width of one half
+static Problem half_problem(const Problem &p, int half_bits)
+{
+    Problem h = p;
+    h.x_bits = half_bits;
+    return h;
+}
+
+static bool prepared_path_supported(const Problem &p)
+{
+    if (p.x_bits <= 32) return mfma_supported(p);
+    return mfma_supported(half_problem(p, 32)) && mfma_supported(half_problem(p, p.x_bits - 32));
+}
+
+static hipError_t stage_all(const Problem &p, const uint64_t *X, void *workspace, hipStream_t stream)
+{
+    if (p.x_bits <= 32) return launch_stage_shares(p, X, 0, workspace, stream);
+    hipError_t e = launch_stage_shares(half_problem(p, 32), X, 0, workspace, stream);
+    if (e != hipSuccess) return e;
+    return launch_stage_shares(half_problem(p, p.x_bits - 32), X, 32,
+                               (char *)workspace + half_bytes(p.m, p.k, 32), stream);
+}
+
+// x = x_lo + 2^32 x_hi: the pass over the upper halves writes its reduced result to out,
+// the pass over the lower halves adds 2^32 times it (and the mask) and overwrites it
+static hipError_t matmul_all(const Problem &p, const void *staged, const void *prepared,
+                             const uint64_t *mask, uint64_t *out, hipStream_t stream)
+{
+    if (p.x_bits <= 32) return launch_cop_mfma(p, staged, prepared, mask, nullptr, out, stream);
+    const void *staged_hi = (const char *)staged + half_bytes(p.m, p.k, 32);
+    hipError_t e = launch_cop_mfma(half_problem(p, p.x_bits - 32), staged_hi, prepared, nullptr,
+                                   nullptr, out, stream);
+    if (e != hipSuccess) return e;
+    return launch_cop_mfma(half_problem(p, 32), staged, prepared, mask, out, out, stream);
 }
 
 }  // namespace nimbus
@@ -88,6 +135,7 @@ int nimbus_cop_matmul(const uint64_t *X, int m, int k, int x_bits,
     Problem p;
     const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
     if (rc != NIMBUS_COP_OK) return rc;
+    if (x_bits > 32) return NIMBUS_COP_ERR_UNSUPPORTED;    // wide shares: prepared path only
     const hipError_t e = launch_cop_valu(p, X, ctW, mask, out, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
@@ -115,7 +163,7 @@ int nimbus_cop_prepare(const uint64_t *ctW, int k, int n, int N, int L,
 
 size_t nimbus_cop_workspace_bytes(int m, int k, int x_bits)
 {
-    if (m < 1 || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 32) return 0;
+    if (m < 1 || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 64) return 0;
     return workspace_bytes_of(m, k, x_bits);
 }
 
@@ -123,7 +171,7 @@ int nimbus_cop_stage_shares(const uint64_t *X, int m, int k, int x_bits,
                             void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!X || !workspace || ((uintptr_t)workspace & 15u) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
-    if (m < 1 || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 32)
+    if (m < 1 || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 64)
         return NIMBUS_COP_ERR_INVALID_ARG;
     if (!staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
@@ -131,7 +179,7 @@ int nimbus_cop_stage_shares(const uint64_t *X, int m, int k, int x_bits,
     p.m = m;
     p.k = k;
     p.x_bits = x_bits;
-    const hipError_t e = launch_stage_shares(p, X, workspace, (hipStream_t)stream);
+    const hipError_t e = stage_all(p, X, workspace, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 
@@ -146,9 +194,8 @@ int nimbus_cop_matmul_staged(const void *staged_shares, int m, int k, int x_bits
     Problem p;
     const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
     if (rc != NIMBUS_COP_OK) return rc;
-    if (!mfma_supported(p)) return NIMBUS_COP_ERR_UNSUPPORTED;
-    const hipError_t e = launch_cop_mfma(p, staged_shares, prepared, mask, out,
-                                         (hipStream_t)stream);
+    if (!prepared_path_supported(p)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    const hipError_t e = matmul_all(p, staged_shares, prepared, mask, out, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 
@@ -165,11 +212,11 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
     Problem p;
     const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
     if (rc != NIMBUS_COP_OK) return rc;
-    if (!mfma_supported(p) || !staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    if (!prepared_path_supported(p) || !staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
-    hipError_t e = launch_stage_shares(p, X, workspace, (hipStream_t)stream);
+    hipError_t e = stage_all(p, X, workspace, (hipStream_t)stream);
     if (e != hipSuccess) return NIMBUS_COP_ERR_LAUNCH;
-    e = launch_cop_mfma(p, workspace, prepared, mask, out, (hipStream_t)stream);
+    e = matmul_all(p, workspace, prepared, mask, out, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 
@@ -208,6 +255,6 @@ const char *nimbus_cop_strerror(int status)
     }
 }
 
-int nimbus_cop_version(void) { return 101; }
+int nimbus_cop_version(void) { return 102; }
 
 }  // extern "C"

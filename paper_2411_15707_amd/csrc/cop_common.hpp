@@ -60,10 +60,11 @@ hipError_t launch_cop_valu(const Problem &p, const uint64_t *X, const uint64_t *
                            const uint64_t *mask, uint64_t *out, hipStream_t stream);
 hipError_t launch_prepare(const Problem &p, const uint64_t *ctW, void *prepared,
                           hipStream_t stream);
-hipError_t launch_stage_shares(const Problem &p, const uint64_t *X, void *workspace,
-                               hipStream_t stream);
+hipError_t launch_stage_shares(const Problem &p, const uint64_t *X, int half_shift,
+                               void *workspace, hipStream_t stream);
 hipError_t launch_cop_mfma(const Problem &p, const void *staged, const void *prepared,
-                           const uint64_t *mask, uint64_t *out, hipStream_t stream);
+                           const uint64_t *mask, const uint64_t *prev, uint64_t *out,
+                           hipStream_t stream);
 bool mfma_supported(const Problem &p);
 hipError_t launch_cop_pack(const Problem &p, const uint64_t *rows, const uint64_t *mask,
                            uint64_t *packed, hipStream_t stream);

@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void column_sums_kernel(
 template <int DX>
 __global__ __launch_bounds__(256) void x_planes_kernel(
     const uint64_t *__restrict__ X, int m, int k, int KB, uint32_t total, uint32_t offx,
-    uint32_t *__restrict__ xd)
+    int half_shift, uint32_t *__restrict__ xd)
 {
     // one thread = four consecutive k of one row: one 32-bit word in each of the DX planes
     const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
@@ -130,7 +130,8 @@ __global__ __launch_bounds__(256) void x_planes_kernel(
             const int i = kbase + b;
             if (i < k) {
                 // flipping bit 7 of a byte turns it into the two's complement digit byte - 128
-                const uint32_t x = (uint32_t)X[(size_t)row * k + i] ^ offx;
+                // (half_shift = 32 selects the upper half of a share wider than 32 bits)
+                const uint32_t x = (uint32_t)(X[(size_t)row * k + i] >> half_shift) ^ offx;
 #pragma unroll
                 for (int d = 0; d < DX; ++d) w[d] |= ((x >> (8 * d)) & 0xffu) << (8 * b);
             }
@@ -149,6 +150,7 @@ struct MfmaArgs {
     const uint4 *planes;      // [CT][KB][DQ][64] uint4
     const uint64_t *colsum;   // [C]
     const uint64_t *mask;     // [m][C] or null
+    const uint64_t *prev;     // [m][C] or null: result of the pass over the upper share halves
     uint64_t *out;            // [m][C]
     int m, KB, RB, N, L;
     uint32_t C, CT;
@@ -564,7 +566,8 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 
     // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
     const uint32_t col = (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
-    const uint32_t limb = (ct2 * 2u * kTile / (uint32_t)a.N) % (uint32_t)a.L;   // uniform
+    // the wave's 32 columns lie in one (polynomial, limb) block of N >= 32 columns
+    const uint32_t limb = ((ct2 * 2u + (uint32_t)wc) * kTile / (uint32_t)a.N) % (uint32_t)a.L;
     const uint64_t q = a.q[limb];
     const double qinv = a.qinv[limb];
     const int row0 = rt * kTile + 4 * (lane >> 5);
@@ -575,6 +578,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     auto roff = [](int r) -> int { return 8 * (r >> 2) + (r & 3); };
     const size_t lane_elem = (size_t)row0 * a.C + col;
     const uint64_t *const mask0 = a.mask ? a.mask + lane_elem : nullptr;
+    const uint64_t *const prev0 = a.prev ? a.prev + lane_elem : nullptr;
     uint64_t *const out0 = a.out + lane_elem;
     uint64_t mk[16];                                // read once: streaming loads
 #pragma unroll
@@ -604,8 +608,14 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         auto D = [&](int d) -> int32_t { return acc[d][r]; };
+        // Shares wider than 32 bits take two passes, x = x_lo + 2^32 x_hi: this one then adds
+        // 2^32 times the (reduced) result of the pass over the upper halves, read from where
+        // this pass writes its own result (prev may be out: the element is read before it is
+        // written, by the same lane).  2^32 prev < 2^32 q keeps V below 2^47 q.
+        uint64_t pv = 0;
+        if (prev0 && row0 + roff(r) < a.m) pv = prev0[(size_t)roff(r) * a.C];
         // low 64 bits
-        uint64_t lo = cst_lo + mk[r];
+        uint64_t lo = cst_lo + mk[r] + (pv << 32);
 #pragma unroll
         for (int d = 0; d < 4 && d < ND; ++d)
             lo += (uint64_t)((int64_t)D(d) * (int64_t)(1ll << (8 * d)));
@@ -615,6 +625,8 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         lo += (uint64_t)up << 32;
         // quotient estimate
         double vd = fma((double)(uint32_t)(mk[r] >> 32), two32, (double)(uint32_t)mk[r]);
+        if (prev0)   // exact below 2^53; above, off by < 2^-53 of a term that is < 2^32 q
+            vd = fma(fma((double)(uint32_t)(pv >> 32), two32, (double)(uint32_t)pv), two32, vd);
         double scale = 1.0;
 #pragma unroll
         for (int d = 0; d < ND; ++d) {
@@ -669,8 +681,9 @@ bool mfma_supported(const Problem &p)
     const long long pairs = DX < DQ ? DX : DQ;
     // |D_d| < 2^30 (zero padding of k adds nothing)
     if ((long long)p.k * pairs * 16384ll >= (1ll << 30)) return false;
-    // the value reduced in the epilogue is below (2^(sh+1) + 2^32 + 1) * q; the
-    // floating-point quotient needs it below 2^47 * q
+    // the value reduced in the epilogue is below (2^(sh+1) + 2^33 + 1) * q (the second
+    // 2^32 q: the previous pass of a wide share); the floating-point quotient needs it
+    // below 2^47 * q
     return bias_shift(p) + 2 <= 47;
 }
 
@@ -700,30 +713,33 @@ hipError_t launch_prepare(const Problem &p, const uint64_t *ctW, void *prepared,
 }
 
 template <int DX>
-static hipError_t stage_impl(const Problem &p, const uint64_t *X, void *workspace,
+static hipError_t stage_impl(const Problem &p, const uint64_t *X, int half_shift, void *workspace,
                              hipStream_t stream)
 {
     const int KB = kblocks(p.k);
     const int RT = (p.m + kTile - 1) / kTile;
     const uint32_t xtotal = (uint32_t)RT * KB * 256;
     hipLaunchKernelGGL(x_planes_kernel<DX>, dim3((xtotal + 255) / 256), dim3(256), 0, stream,
-                       X, p.m, p.k, KB, xtotal, share_offset(p.x_bits, DX), (uint32_t *)workspace);
+                       X, p.m, p.k, KB, xtotal, share_offset(p.x_bits, DX), half_shift,
+                       (uint32_t *)workspace);
     return hipGetLastError();
 }
 
-hipError_t launch_stage_shares(const Problem &p, const uint64_t *X, void *workspace,
-                               hipStream_t stream)
+// p.x_bits (<= 32) is the width of the half that is staged; half_shift is 0 or 32
+hipError_t launch_stage_shares(const Problem &p, const uint64_t *X, int half_shift,
+                               void *workspace, hipStream_t stream)
 {
     switch (planes_x(p.x_bits)) {
-    case 2: return stage_impl<2>(p, X, workspace, stream);
-    case 3: return stage_impl<3>(p, X, workspace, stream);
-    default: return stage_impl<4>(p, X, workspace, stream);
+    case 2: return stage_impl<2>(p, X, half_shift, workspace, stream);
+    case 3: return stage_impl<3>(p, X, half_shift, workspace, stream);
+    default: return stage_impl<4>(p, X, half_shift, workspace, stream);
     }
 }
 
 template <int DX, int DQ>
 static hipError_t mfma_impl(const Problem &p, const void *staged, const void *prepared,
-                            const uint64_t *mask, uint64_t *out, hipStream_t stream)
+                            const uint64_t *mask, const uint64_t *prev, uint64_t *out,
+                            hipStream_t stream)
 {
     const int KB = kblocks(p.k);
     const uint32_t CT = (uint32_t)(p.C / kTile);
@@ -733,6 +749,7 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
     a.planes = (const uint4 *)prepared;
     a.colsum = (const uint64_t *)((const char *)prepared + (size_t)CT * KB * DQ * kTileBytes);
     a.mask = mask;
+    a.prev = prev;
     a.out = out;
     a.m = p.m;
     a.KB = KB;
@@ -756,11 +773,12 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
 }
 
 hipError_t launch_cop_mfma(const Problem &p, const void *staged, const void *prepared,
-                           const uint64_t *mask, uint64_t *out, hipStream_t stream)
+                           const uint64_t *mask, const uint64_t *prev, uint64_t *out,
+                           hipStream_t stream)
 {
     const int DX = planes_x(p.x_bits), DQ = planes_q(p.q_bits_max);
 #define NIMBUS_CASE(dx, dq) \
-    if (DX == dx && DQ == dq) return mfma_impl<dx, dq>(p, staged, prepared, mask, out, stream);
+    if (DX == dx && DQ == dq) return mfma_impl<dx, dq>(p, staged, prepared, mask, prev, out, stream);
     NIMBUS_CASE(2, 7)
     NIMBUS_CASE(3, 7)
     NIMBUS_CASE(4, 7)

@@ -54,7 +54,7 @@ def _raw():
 
 @pytest.mark.parametrize("kw", [
     dict(m=0), dict(k=0), dict(n=0), dict(N=48), dict(N=16), dict(N=1 << 17), dict(L=0), dict(L=5),
-    dict(x_bits=0), dict(x_bits=33), dict(moduli=(1 << 54,)), dict(moduli=((1 << 62) + 1,)),
+    dict(x_bits=0), dict(x_bits=65), dict(moduli=(1 << 54,)), dict(moduli=((1 << 62) + 1,)),
     dict(moduli=(65537,), x_bits=20), dict(X=None), dict(ctW=None), dict(out=None),
     dict(moduli=None),
 ])
@@ -123,3 +123,16 @@ def test_packed_count_and_pack_argument_checks():
         rc = lib.nimbus_cop_pack(a["rows"], a["m"], a["n"], a["N"], a["L"], mod, a["mask"],
                                  a["packed"], None)
         assert rc == want, (kw, rc)
+
+
+def test_wide_shares_only_on_the_prepared_path():
+    """33..64-bit shares: the canonical-layout entry point answers UNSUPPORTED; the size
+    query counts the byte planes of both halves"""
+    lib = _raw()
+    mod = (ctypes.c_uint64 * 1)(*ci.limb_primes(59, 14, 1))
+    rc = lib.nimbus_cop_matmul(0x1000, 4, 8, 64, 0x2000, 32, 32, 1, mod, None, 0x3000, None)
+    assert rc == -2
+    # 33 rows x 65 k -> 2 x 3 tiles; 4 planes for the lower half + 4 (64 bits) or 2 (40 bits)
+    assert nc.nimbus_cop_workspace_bytes(33, 65, 64) == 2 * 3 * (4 + 4) * 1024
+    assert nc.nimbus_cop_workspace_bytes(33, 65, 40) == 2 * 3 * (4 + 2) * 1024
+    assert nc.nimbus_cop_workspace_bytes(33, 65, 65) == 0

@@ -56,6 +56,7 @@ SMALL = [
     (9, 128, 64, 64, 2, 20, 62),        # 3 x 8 planes (operands read after the barrier), four k-blocks
     (12, 192, 64, 64, 1, 32, 62),       # 4 x 8 planes, six k-blocks
     (100, 1024, 64, 64, 1, 16, 50),     # 2 x 7 planes, 32 k-blocks
+    (6, 50, 32, 32, 3, 20, 54),         # smallest ring with several limbs: a 64-column tile spans two limbs
 ]
 
 
@@ -326,3 +327,36 @@ def test_config1_matmul_then_pack_decrypts_to_side_by_side_payloads(oracle):
             if th * P + u < m:
                 want[u * n:(u + 1) * n] = XW[th * P + u] % t
         assert np.array_equal(got, want.astype(np.uint64))
+
+
+# m, k, n, N, L, x_bits, q_bits (per limb)
+WIDE = [
+    (5, 40, 32, 32, 2, 64, (59, 55)),        # the paper's limb sizes, full 64-bit shares
+    (33, 100, 64, 64, 1, 64, (54,)),         # 4 + 4 share planes x 7 ciphertext planes
+    (17, 70, 64, 64, 2, 48, (62, 55)),       # 48-bit shares: upper half has two planes
+    (9, 33, 32, 32, 1, 33, (50,)),           # one bit above 32
+    (32, 128, 8192, 8192, 2, 64, (59, 55)),  # the paper's ring degree and moduli, one chunk
+]
+
+
+@pytest.mark.parametrize("m,k,n,N,L,x_bits,q_bits", WIDE)
+def test_wide_shares_two_pass_path(oracle, m, k, n, N, L, x_bits, q_bits):
+    """shares of more than 32 bits (Section 5.1: l = 64) through the prepared path against the
+    per-term-reduced oracle, with and without mask, extremes included"""
+    import gpu_util as gu
+    moduli = tuple(ci.limb_primes(b, 14, 1)[0] for b in q_bits)
+    X = ci.gen_X(7000 + m, m, k, x_bits)
+    X[0, 0] = (1 << x_bits) - 1
+    X[-1, :] = (1 << x_bits) - 1
+    X[0, 1] = 0
+    ctW = ci.gen_ctW_uniform(7000 + m, k, 1, moduli, N)
+    mask = ci.gen_mask_uniform(7000 + m, m, 1, moduli, N)
+    for l, q in enumerate(moduli):
+        ctW[:, 0, :, l, :4] = q - 1
+        mask[0, 0, :, l, :4] = q - 1
+    _say(f"[parity] wide shares m={m} k={k} N={N} L={L} x_bits={x_bits}")
+    prepared = gu.prepare(ctW, moduli, n, N)
+    for msk in (mask, None):
+        want, _ = oracle.cop_ref(X, ctW, moduli, n, N, msk, wide=True)
+        got = gu.run_mfma(X, ctW, moduli, n, N, x_bits, msk, prepared=prepared)
+        assert np.array_equal(got, want), gu.first_mismatch(got, want)
