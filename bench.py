@@ -198,6 +198,35 @@ def main():
             "frac_of_hbm_peak": round(pack_bytes / (pack_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         }
 
+    # ---- calibration: what this chip sustains on the two resources that bound the kernel ----
+    # (register-only int8 matrix-core loop with zero and with random operand bytes; streaming
+    # read of one prepared weight buffer per launch, rotating over all of them)
+    def timed(launch, reps):
+        launch(0)
+        a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a_.record(stream)
+        work = 0
+        for i in range(reps):
+            work += launch(i)
+        b_.record(stream)
+        torch.cuda.synchronize()
+        return work / (a_.elapsed_time(b_) * 1e-3)
+    sink = torch.empty(512 * 256, dtype=torch.int32, device="cuda")
+    mfma_zero = timed(lambda i: nc.nimbus_calib_mfma_i8(512, 2000, 0, sink), 4) / 1e12
+    mfma_rand = timed(lambda i: nc.nimbus_calib_mfma_i8(512, 2000, 1, sink), 4) / 1e12
+    read_gbps = timed(lambda i: nc.nimbus_calib_stream_read(preps[i % R], sink), 3 * R) / 1e9
+    t_hbm_us = alg_bytes / (read_gbps * 1e9) * 1e6
+    t_mfma_us = i8_ops / (mfma_rand * 1e12) * 1e6
+    calibration = {
+        "int8_mfma_tops_zero_operands": round(mfma_zero, 1),
+        "int8_mfma_tops_random_operands": round(mfma_rand, 1),
+        "hbm_stream_read_gbps": round(read_gbps, 1),
+        "t_hbm_us_at_measured_rate": round(t_hbm_us, 2),
+        "t_mfma_us_at_measured_rate": round(t_mfma_us, 2),
+        "kernel_frac_of_measured_bound": round(max(t_hbm_us, t_mfma_us) / (kernel_ms_avg * 1e3), 4),
+    }
+
     # ---- a plain device-to-device copy of known size: reference point for HBM byte counters ----
     # (an elementwise add kernel: reads 256 MiB, writes 256 MiB)
     ca = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
@@ -260,6 +289,7 @@ def main():
         "canonical_layout_valu_kernel_ms": round(valu_ms, 4),
         "roofline": roofline,
         "pack": pack,
+        "calibration": calibration,
         "cpu_baseline": cpu_baseline,
         "output_matches_oracle": verified,
     }

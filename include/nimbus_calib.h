@@ -1,0 +1,40 @@
+/*
+ * nimbus_calib.h: calibration launches used by the benchmark, exported by the same shared
+ * library as nimbus_cop.h.  They measure what the chip sustains on the two resources the
+ * COP kernel is bounded by, so that its time can be set against measured ceilings as well
+ * as against the published peaks.  Not part of the COP path; for callers that benchmark.
+ *
+ * Both only enqueue one kernel on `stream` (a hipStream_t, NULL = default) and return at
+ * once; the caller times them.  Pointers are DEVICE pointers owned by the caller.
+ * Return value: the amount of work enqueued, or -1 for invalid arguments / a refused launch.
+ */
+#ifndef NIMBUS_CALIB_H
+#define NIMBUS_CALIB_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Register-only loop of the int8 matrix-core instruction the COP kernel uses (3 share
+ * planes x 7 ciphertext planes into 9 accumulators per wave, Section 3.2's scalar-times-
+ * polynomial products after the byte split), `workgroups` workgroups of four waves, `iters`
+ * rounds of 21 instructions per wave; operand bytes all zero (random_operands = 0) or
+ * pseudo-random (1).  sink: at least workgroups * 1024 bytes, written once.
+ * Returns the number of int8 operations (2 per multiply-accumulate) enqueued.
+ */
+long long nimbus_calib_mfma_i8(int workgroups, int iters, int random_operands, void *sink,
+                               size_t sink_bytes, void *stream);
+
+/*
+ * Streaming read of `bytes` bytes at `src` (16-byte aligned) with 16-byte loads.
+ * sink: at least 4 bytes.  Returns the number of bytes read.
+ */
+long long nimbus_calib_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NIMBUS_CALIB_H */

@@ -19,4 +19,7 @@ from .binding import (  # noqa: F401
     nimbus_cop_version,
     nimbus_cop_workspace_bytes,
     EXPORTED_SYMBOLS,
+    CALIBRATION_SYMBOLS,
+    nimbus_calib_mfma_i8,
+    nimbus_calib_stream_read,
 )

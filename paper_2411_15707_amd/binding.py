@@ -12,6 +12,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libnimbus_cop.so"
 _lib = None
+NIMBUS_INVALID = -1
 
 EXPORTED_SYMBOLS = (
     "nimbus_cop_matmul",
@@ -26,6 +27,9 @@ EXPORTED_SYMBOLS = (
     "nimbus_cop_strerror",
     "nimbus_cop_version",
 )
+
+
+CALIBRATION_SYMBOLS = ("nimbus_calib_mfma_i8", "nimbus_calib_stream_read")
 
 
 class NimbusCopError(RuntimeError):
@@ -68,6 +72,10 @@ def load_library():
     lib.nimbus_cop_packed_count.argtypes = [ci, ci, ci]
     lib.nimbus_cop_pack.restype = ci
     lib.nimbus_cop_pack.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
+    lib.nimbus_calib_mfma_i8.restype = ctypes.c_longlong
+    lib.nimbus_calib_mfma_i8.argtypes = [ci, ci, ci, vp, sz, vp]
+    lib.nimbus_calib_stream_read.restype = ctypes.c_longlong
+    lib.nimbus_calib_stream_read.argtypes = [vp, sz, vp, vp]
     lib.nimbus_cop_strerror.restype = ctypes.c_char_p
     lib.nimbus_cop_strerror.argtypes = [ci]
     lib.nimbus_cop_version.restype = ci
@@ -214,3 +222,23 @@ def nimbus_cop_pack(rows, m, n, N, L, moduli, mask, packed, stream=None):
                              _stream(stream))
     if rc != 0:
         raise NimbusCopError(rc, "nimbus_cop_pack")
+
+
+def nimbus_calib_mfma_i8(workgroups, iters, random_operands, sink, stream=None) -> int:
+    """enqueue the register-only int8 matrix-core loop; returns the int8 operations enqueued"""
+    ops = load_library().nimbus_calib_mfma_i8(workgroups, iters, int(bool(random_operands)),
+                                              _dev_ptr(sink, "sink"),
+                                              sink.numel() * sink.element_size(), _stream(stream))
+    if ops < 0:
+        raise NimbusCopError(NIMBUS_INVALID, "nimbus_calib_mfma_i8")
+    return int(ops)
+
+
+def nimbus_calib_stream_read(src, sink, stream=None) -> int:
+    """enqueue a streaming read of the whole tensor `src`; returns the bytes read"""
+    n = load_library().nimbus_calib_stream_read(_dev_ptr(src, "src"),
+                                                src.numel() * src.element_size(),
+                                                _dev_ptr(sink, "sink"), _stream(stream))
+    if n < 0:
+        raise NimbusCopError(NIMBUS_INVALID, "nimbus_calib_stream_read")
+    return int(n)

@@ -1,0 +1,89 @@
+// Calibration kernels for the benchmark: what this chip sustains on the two resources the
+// COP kernel leans on, measured the same way the kernel uses them.  Not part of the COP
+// path; declared in include/nimbus_calib.h.
+//
+//  * int8 matrix-core rate: a register-only loop of v_mfma_i32_32x32x32_i8 with three A
+//    operands, seven B operands and nine accumulators per wave (the COP kernel's 3 x 7
+//    digit products), with zero or with random operand bytes.  The sustained rate depends
+//    on the operand values (the chip lowers its clock under load), so both are measured.
+//  * HBM read rate: a grid-stride read of a buffer with 16-byte loads.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/nimbus_calib.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+__device__ inline uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+    return x;
+}
+
+__global__ __launch_bounds__(256) void calib_mfma_kernel(int iters, int random_operands, int *sink)
+{
+    v4i a[3], b[7];
+    const uint32_t seed = blockIdx.x * 256u + threadIdx.x;
+    for (int i = 0; i < 3; ++i)
+        for (int r = 0; r < 4; ++r)
+            a[i][r] = random_operands ? (int)mix32(seed * 31u + (uint32_t)(i * 4 + r) + 1u) : 0;
+    for (int i = 0; i < 7; ++i)
+        for (int r = 0; r < 4; ++r)
+            b[i][r] = random_operands ? (int)mix32(seed * 77u + (uint32_t)(i * 4 + r) + 1000u) : 0;
+    v16i c[9];
+    for (int i = 0; i < 9; ++i)
+        for (int r = 0; r < 16; ++r) c[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 21; ++i)
+            c[i / 7 + i % 7] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i / 7], b[i % 7],
+                                                                    c[i / 7 + i % 7], 0, 0, 0);
+    }
+    int s = 0;
+    for (int i = 0; i < 9; ++i) s += c[i][0];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void calib_read_kernel(const u32x4 *__restrict__ src, size_t n16,
+                                                         uint32_t *sink)
+{
+    uint32_t acc = 0;
+    const size_t stride = (size_t)gridDim.x * 256u;
+    for (size_t i = (size_t)blockIdx.x * 256u + threadIdx.x; i < n16; i += stride) {
+        const u32x4 v = __builtin_nontemporal_load(src + i);
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;      // keeps the loads alive, (almost) never taken
+}
+
+}  // namespace
+
+extern "C" {
+
+long long nimbus_calib_mfma_i8(int workgroups, int iters, int random_operands, void *sink,
+                               size_t sink_bytes, void *stream)
+{
+    if (workgroups < 1 || workgroups > 65535 || iters < 1 || !sink) return -1;
+    if (sink_bytes < (size_t)workgroups * 256u * sizeof(int)) return -1;
+    hipLaunchKernelGGL(calib_mfma_kernel, dim3((uint32_t)workgroups), dim3(256), 0,
+                       (hipStream_t)stream, iters, random_operands, (int *)sink);
+    if (hipGetLastError() != hipSuccess) return -1;
+    // int8 operations issued: 4 waves x iters x 21 instructions x 2 * 32*32*32 each
+    return (long long)workgroups * 4ll * iters * 21ll * 65536ll;
+}
+
+long long nimbus_calib_stream_read(const void *src, size_t bytes, void *sink, void *stream)
+{
+    if (!src || !sink || bytes < 16 || ((uintptr_t)src & 15u) != 0) return -1;
+    const size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(calib_read_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream,
+                       (const u32x4 *)src, n16, (uint32_t *)sink);
+    if (hipGetLastError() != hipSuccess) return -1;
+    return (long long)(n16 * 16);
+}
+
+}  // extern "C"

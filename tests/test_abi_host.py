@@ -26,6 +26,13 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(nc.lib_path())
     for name in declared_functions():
         assert hasattr(lib, name), name
+    # the calibration header of the benchmark
+    text = open(os.path.join(ROOT, "include", "nimbus_calib.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    calib = sorted(set(re.findall(r"\b(nimbus_calib_\w+)\s*\(", text)))
+    assert calib == sorted(nc.CALIBRATION_SYMBOLS)
+    for name in calib:
+        assert hasattr(lib, name), name
 
 
 def test_version_and_strerror():

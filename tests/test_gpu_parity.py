@@ -360,3 +360,19 @@ def test_wide_shares_two_pass_path(oracle, m, k, n, N, L, x_bits, q_bits):
         want, _ = oracle.cop_ref(X, ctW, moduli, n, N, msk, wide=True)
         got = gu.run_mfma(X, ctW, moduli, n, N, x_bits, msk, prepared=prepared)
         assert np.array_equal(got, want), gu.first_mismatch(got, want)
+
+
+def test_calibration_launches_run():
+    """the benchmark's calibration kernels enqueue and report the work they were asked for"""
+    import torch
+    import paper_2411_15707_amd as nc
+    sink = torch.zeros(8 * 256, dtype=torch.int32, device="cuda")
+    assert nc.nimbus_calib_mfma_i8(8, 3, 1, sink) == 8 * 4 * 3 * 21 * 65536
+    assert nc.nimbus_calib_mfma_i8(8, 3, 0, sink) == 8 * 4 * 3 * 21 * 65536
+    torch.cuda.synchronize()
+    assert int(sink.abs().max()) == 0                      # zero operands leave zero accumulators
+    src = torch.ones(1 << 20, dtype=torch.int32, device="cuda")
+    assert nc.nimbus_calib_stream_read(src, sink) == 4 << 20
+    torch.cuda.synchronize()
+    with pytest.raises(nc.NimbusCopError):
+        nc.nimbus_calib_mfma_i8(8, 3, 1, sink[:16])        # sink too small: refused on the host
