@@ -563,6 +563,9 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     }
 #undef NIMBUS_NEXT_ISSUE
 #undef NIMBUS_NEXT_READ
+    // the last pipelined iteration has read a stage that does not exist into the other
+    // operand set; nothing may reuse those registers before the reads are back
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
     // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
     const uint32_t col = (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
@@ -605,34 +608,55 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     cst_d = fma((double)(uint32_t)cst_hi, two32 * two32, cst_d);
     cst_d = fma((double)(uint32_t)(cst_hi >> 32), two32 * two32 * two32, cst_d);
     const uint32_t q_lo = (uint32_t)q, q_hi = (uint32_t)(q >> 32);
+    // First everything that does not need the mask words (their loads are in flight): per
+    // element the low 64 bits and the double of sum_d D_d 256^d; then, per element, mask and
+    // constant, quotient, remainder, store.
+    uint64_t lo_part[16];
+    double vd_part[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         auto D = [&](int d) -> int32_t { return acc[d][r]; };
-        // Shares wider than 32 bits take two passes, x = x_lo + 2^32 x_hi: this one then adds
-        // 2^32 times the (reduced) result of the pass over the upper halves, read from where
-        // this pass writes its own result (prev may be out: the element is read before it is
-        // written, by the same lane).  2^32 prev < 2^32 q keeps V below 2^47 q.
-        uint64_t pv = 0;
-        if (prev0 && row0 + roff(r) < a.m) pv = prev0[(size_t)roff(r) * a.C];
-        // low 64 bits
-        uint64_t lo = cst_lo + mk[r] + (pv << 32);
+        uint64_t lo = cst_lo;
 #pragma unroll
         for (int d = 0; d < 4 && d < ND; ++d)
             lo += (uint64_t)((int64_t)D(d) * (int64_t)(1ll << (8 * d)));
         uint32_t up = 0;
 #pragma unroll
         for (int d = 4; d < 8 && d < ND; ++d) up += (uint32_t)D(d) << (8 * (d - 4));
-        lo += (uint64_t)up << 32;
-        // quotient estimate
-        double vd = fma((double)(uint32_t)(mk[r] >> 32), two32, (double)(uint32_t)mk[r]);
-        if (prev0)   // exact below 2^53; above, off by < 2^-53 of a term that is < 2^32 q
-            vd = fma(fma((double)(uint32_t)(pv >> 32), two32, (double)(uint32_t)pv), two32, vd);
-        double scale = 1.0;
+        lo_part[r] = lo + ((uint64_t)up << 32);
+        double vd = 0.0, scale = 1.0;
 #pragma unroll
         for (int d = 0; d < ND; ++d) {
             vd = fma((double)D(d), scale, vd);
             scale *= 256.0;
         }
+        vd_part[r] = vd;
+    }
+    // the second half stays behind the first: volatile statements keep their order, and
+    // these make the first half's results and the loaded words pass through them
+#pragma unroll
+    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(lo_part[r]), "+v"(vd_part[r]));
+    // Shares wider than 32 bits take two passes, x = x_lo + 2^32 x_hi: the second one adds
+    // 2^32 times the (reduced) result of the pass over the upper halves, read from where
+    // this pass writes its own result (prev may be out: an element is read and written by
+    // the same lane, and every read comes before the first write).  2^32 prev < 2^32 q keeps
+    // V below 2^47 q.
+    // (asked for here, where the accumulators' registers are free)
+    uint64_t pv[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        pv[r] = (prev0 && row0 + roff(r) < a.m)
+                    ? __builtin_nontemporal_load(&prev0[(size_t)roff(r) * a.C])
+                    : 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(mk[r]), "+v"(pv[r]));
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const uint64_t lo = lo_part[r] + mk[r] + (pv[r] << 32);
+        // quotient estimate
+        double vd = vd_part[r] + fma((double)(uint32_t)(mk[r] >> 32), two32, (double)(uint32_t)mk[r]);
+        if (prev0)   // exact below 2^53; above, off by < 2^-53 of a term that is < 2^32 q
+            vd = fma(fma((double)(uint32_t)(pv[r] >> 32), two32, (double)(uint32_t)pv[r]), two32, vd);
         vd += cst_d;
         const double qd = fmax(fma(vd, qinv, -0.5), 0.0);
         const uint32_t qh = (uint32_t)(qd * (1.0 / two32));
