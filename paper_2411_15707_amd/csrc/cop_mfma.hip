@@ -154,6 +154,7 @@ struct MfmaArgs {
     uint64_t *out;            // [m][C]
     int m, KB, RB, N, L;
     uint32_t C, CT;
+    uint32_t kb_magic;        // floor(2^32 / KB): x / KB = umulhi(x, kb_magic) or one more
     uint32_t offx;            // OFFX
     uint64_t q[kMaxLimbs];
     double qinv[kMaxLimbs];   // 1 / q_l, rounded
@@ -319,7 +320,10 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     {
         const uint32_t id = blockIdx.x;
         const uint32_t CT2 = a.CT >> 1;
-        if ((CT2 & 7u) == 0) {
+        if (a.RB == 1) {                            // one row block: no division
+            rb = 0;
+            ct2 = id;
+        } else if ((CT2 & 7u) == 0) {
             const uint32_t xcd = id & 7u, slot = id >> 3;
             rb = slot % (uint32_t)a.RB;
             ct2 = (slot / (uint32_t)a.RB) * 8u + xcd;
@@ -337,15 +341,23 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // X tile t of a stage, t in [0, 4 DX): row tile t / DX (clamped to an existing one;
     // rows past m are never used), plane t % DX.  Ciphertext tile u in [0, 2 DQ):
     // column tile u / DQ, plane u % DQ.
+    // (one 64-bit base per operand, 32-bit offsets from it: a row tile or column tile of
+    // planes spans KB * D KiB < 2^23 bytes, and the setup before the first load is all
+    // scalar instructions on the critical path of the launch)
+    const uint32_t a_tile_bytes = (uint32_t)KB * DX * kTileBytes;     // one row tile, all k-blocks
+    const uint32_t b_tile_bytes = (uint32_t)KB * DQ * kTileBytes;     // one column tile
+    const unsigned char *const a_base =
+        (const unsigned char *)a.xd + (size_t)rb * 4u * a_tile_bytes;
+    const unsigned char *const b_base =
+        (const unsigned char *)a.planes + (size_t)ct2 * 2u * b_tile_bytes;
     auto a_src = [&](int t) -> const unsigned char * {
-        int r = (int)rb * 4 + t / DX;
-        if (r > RT - 1) r = RT - 1;
-        return (const unsigned char *)(a.xd + ((size_t)r * KB * DX + (size_t)(t % DX)) * 64);
+        int r = t / DX;                                 // row tile inside the row block
+        const int last = RT - 1 - (int)rb * 4;          // last one that exists (>= 0)
+        if (r > last) r = last;
+        return a_base + ((uint32_t)r * a_tile_bytes + (uint32_t)(t % DX) * kTileBytes);
     };
     auto b_src = [&](int u) -> const unsigned char * {
-        return (const unsigned char *)(a.planes +
-                                       ((size_t)(ct2 * 2u + (uint32_t)(u / DQ)) * KB * DQ +
-                                        (size_t)(u % DQ)) * 64);
+        return b_base + ((uint32_t)(u / DQ) * b_tile_bytes + (uint32_t)(u % DQ) * kTileBytes);
     };
     // Waves 0-3 (the first wave of each SIMD) load the X tiles, from L2; waves 4-7 (the
     // second of each SIMD) the ciphertext tiles, from HBM: load u (u < MAXU) of a wave
@@ -371,7 +383,8 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // care about the order, and workgroups that walk their (equally spaced) ciphertext
     // regions in lockstep would otherwise ask the same memory channels for data at the
     // same moment.
-    const uint32_t k_start = blockIdx.x % (uint32_t)KB;
+    uint32_t k_start = blockIdx.x - __umulhi(blockIdx.x, a.kb_magic) * (uint32_t)KB;   // id mod KB
+    if (k_start >= (uint32_t)KB) k_start -= (uint32_t)KB;
     // Wave-uniform state of the issue side, for the next stage to issue: byte offset of
     // its k-block in the source, byte offset of its slot in the ring.  Carried and
     // wrapped, never recomputed.
@@ -397,11 +410,6 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         slot_off = bump(slot_off, slot_step, slot_end);                       \
     } while (0)
 
-    v16i acc[ND];
-#pragma unroll
-    for (int d = 0; d < ND; ++d)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[d][r] = 0;
     // the column's ciphertext sum is needed after the loop; asked for now (older than every
     // direct-to-LDS load, so the counted waits cover it) it costs two registers, not a
     // round trip to memory at the end
@@ -420,6 +428,15 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         });
         NIMBUS_NEXT_ISSUE();
     }
+
+    // (cleared after the loads are on their way, not before)
+    v16i acc[ND];
+#pragma unroll
+    for (int d = 0; d < ND; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[d][r] = 0;
+#pragma unroll
+    for (int d = 0; d < ND; ++d) tie_acc(acc[d]);
 
     // Operands come out of LDS through explicit ds_read_b128 instructions: reads the
     // compiler can see would each be made to wait for every direct-to-LDS load in flight.
@@ -783,6 +800,8 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
     a.C = (uint32_t)p.C;
     a.CT = CT;
     a.offx = share_offset(p.x_bits, DX);
+    a.kb_magic = (uint32_t)((1ull << 32) / (uint64_t)KB);   // KB = 1: 2^32 does not fit, see below
+    if (KB == 1) a.kb_magic = 0xffffffffu;
     const int sh = bias_shift(p);
     for (int l = 0; l < p.L; ++l) {
         const uint64_t q = p.limbs.limb[l].q;
