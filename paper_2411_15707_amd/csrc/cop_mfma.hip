@@ -583,6 +583,8 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // the last pipelined iteration has read a stage that does not exist into the other
     // operand set; nothing may reuse those registers before the reads are back
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    // (the column sum was loaded by hand: its uses must stay behind the loop's waits)
+    asm volatile("" : "+v"(colsum_S));
 
     // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
     const uint32_t col = (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
