@@ -376,3 +376,28 @@ def test_calibration_launches_run():
     torch.cuda.synchronize()
     with pytest.raises(nc.NimbusCopError):
         nc.nimbus_calib_mfma_i8(8, 3, 1, sink[:16])        # sink too small: refused on the host
+
+
+@pytest.mark.parametrize("t_bits,q_bits", [(32, 62), (20, 54), (16, 50)])
+def test_longest_inner_dimension_with_extreme_digits(oracle, t_bits, q_bits):
+    """k = 16383, the largest the matrix-core path accepts: 512 k-blocks, int32 accumulators
+    closest to their bound.  Shares 0 and t-1 give share digits -128 and 127 in every shifted
+    plane; residues around q/2 give ciphertext digits of the largest magnitude the centred
+    recoding can produce."""
+    import gpu_util as gu
+    m, k, n, N, L = 3, 16383, 32, 32, 1
+    moduli = ci.limb_primes(q_bits, t_bits, L)
+    q = moduli[0]
+    X = ci.gen_X(31, m, k, t_bits)
+    X[0, :] = 0
+    X[1, :] = (1 << t_bits) - 1
+    ctW = ci.gen_ctW_uniform(31, k, 1, moduli, N)
+    ctW[:, 0, :, 0, 0] = (q - 1) // 2          # centred: the most positive value
+    ctW[:, 0, :, 0, 1] = (q - 1) // 2 + 1      # the most negative
+    ctW[:, 0, :, 0, 2] = q - 1
+    ctW[:, 0, :, 0, 3] = 0
+    mask = ci.gen_mask_uniform(31, m, 1, moduli, N)
+    _say(f"[parity] k=16383 t_bits={t_bits} q_bits={q_bits}")
+    want, _ = oracle.cop_ref(X, ctW, moduli, n, N, mask)
+    got = gu.run_mfma(X, ctW, moduli, n, N, t_bits, mask)
+    assert np.array_equal(got, want), gu.first_mismatch(got, want)
