@@ -401,3 +401,37 @@ def test_longest_inner_dimension_with_extreme_digits(oracle, t_bits, q_bits):
     want, _ = oracle.cop_ref(X, ctW, moduli, n, N, mask)
     got = gu.run_mfma(X, ctW, moduli, n, N, t_bits, mask)
     assert np.array_equal(got, want), gu.first_mismatch(got, want)
+
+
+def test_random_parameter_sweep(oracle):
+    """forty seeded random parameter sets (ring degree, limbs of different sizes, share widths
+    1..64 bits, ragged m and k, one to three ring chunks), both kernels where they apply"""
+    import gpu_util as gu
+    rng = np.random.default_rng(20241115707)
+    for case in range(40):
+        N = int(rng.choice([32, 64, 128]))
+        L = int(rng.integers(1, 4))
+        n = int(rng.integers(1, 3 * N + 1))
+        m = int(rng.integers(1, 141))
+        k = int(rng.integers(1, 401))
+        x_bits = int(rng.integers(1, 65)) if case % 4 == 3 else int(rng.integers(1, 33))
+        lo = max(min(x_bits, 32) + 2, 20)
+        moduli = []
+        while len(moduli) < L:                       # limbs of different sizes, all distinct
+            b = int(rng.integers(lo, 63))
+            q = ci.limb_primes(b, 5, 1)[0]
+            if q not in moduli:
+                moduli.append(q)
+        moduli = tuple(moduli)
+        Ch = -(-n // N)
+        X = ci.gen_X(9000 + case, m, k, x_bits)
+        ctW = ci.gen_ctW_uniform(9000 + case, k, Ch, moduli, N)
+        mask = ci.gen_mask_uniform(9000 + case, m, Ch, moduli, N) if case % 3 else None
+        label = f"sweep {case}: m={m} k={k} n={n} N={N} L={L} x_bits={x_bits} q_bits={[q.bit_length() for q in moduli]}"
+        _say("[parity] " + label)
+        want, _ = oracle.cop_ref(X, ctW, moduli, n, N, mask, wide=x_bits > 32)
+        got = gu.run_mfma(X, ctW, moduli, n, N, x_bits, mask)
+        assert np.array_equal(got, want), label + " mfma: " + gu.first_mismatch(got, want)
+        if x_bits <= 32:
+            got = gu.run_valu(X, ctW, moduli, n, N, x_bits, mask)
+            assert np.array_equal(got, want), label + " valu: " + gu.first_mismatch(got, want)
