@@ -630,6 +630,11 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // First everything that does not need the mask words (their loads are in flight): per
     // element the low 64 bits and the double of sum_d D_d 256^d; then, per element, mask and
     // constant, quotient, remainder, store.
+    // (the powers of 256 are kept opaque so that each term is one 32 x 32 + 64-bit
+    // multiply-add instead of a sign extension, a 64-bit shift and a 64-bit add)
+    int32_t pow256[4] = {1, 1 << 8, 1 << 16, 1 << 24};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) asm volatile("" : "+s"(pow256[d]));
     uint64_t lo_part[16];
     double vd_part[16];
 #pragma unroll
@@ -638,7 +643,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         uint64_t lo = cst_lo;
 #pragma unroll
         for (int d = 0; d < 4 && d < ND; ++d)
-            lo += (uint64_t)((int64_t)D(d) * (int64_t)(1ll << (8 * d)));
+            lo += (uint64_t)((int64_t)D(d) * (int64_t)pow256[d]);
         uint32_t up = 0;
 #pragma unroll
         for (int d = 4; d < 8 && d < ND; ++d) up += (uint32_t)D(d) << (8 * (d - 4));
