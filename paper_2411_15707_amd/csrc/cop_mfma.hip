@@ -664,31 +664,39 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // 2^32 times the (reduced) result of the pass over the upper halves, read from where
     // this pass writes its own result (prev may be out: an element is read and written by
     // the same lane, and every read comes before the first write).  2^32 prev < 2^32 q keeps
-    // V below 2^47 q.
-    // (asked for here, where the accumulators' registers are free)
-    uint64_t pv[16];
+    // V below 2^47 q.  (A block of its own behind one wave-uniform branch: the narrow path
+    // does not execute any of it.)
+    if (prev0) {
+        uint64_t pv[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-        pv[r] = (prev0 && row0 + roff(r) < a.m)
-                    ? __builtin_nontemporal_load(&prev0[(size_t)roff(r) * a.C])
-                    : 0;
+        for (int r = 0; r < 16; ++r)
+            pv[r] = row0 + roff(r) < a.m ? __builtin_nontemporal_load(&prev0[(size_t)roff(r) * a.C]) : 0;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(mk[r]), "+v"(pv[r]));
+        for (int r = 0; r < 16; ++r) {
+            lo_part[r] += pv[r] << 32;
+            // exact below 2^53; above, off by < 2^-53 of a term that is < 2^32 q
+            vd_part[r] = fma(fma((double)(uint32_t)(pv[r] >> 32), two32, (double)(uint32_t)pv[r]),
+                             two32, vd_part[r]);
+        }
+        asm volatile("" ::: "memory");
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(mk[r]));
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        const uint64_t lo = lo_part[r] + mk[r] + (pv[r] << 32);
+        const uint64_t lo = lo_part[r] + mk[r];
         // quotient estimate
         double vd = vd_part[r] + fma((double)(uint32_t)(mk[r] >> 32), two32, (double)(uint32_t)mk[r]);
-        if (prev0)   // exact below 2^53; above, off by < 2^-53 of a term that is < 2^32 q
-            vd = fma(fma((double)(uint32_t)(pv[r] >> 32), two32, (double)(uint32_t)pv[r]), two32, vd);
         vd += cst_d;
         const double qd = fmax(fma(vd, qinv, -0.5), 0.0);
         const uint32_t qh = (uint32_t)(qd * (1.0 / two32));
         const uint32_t ql = (uint32_t)fma(-(double)qh, two32, qd);
-        uint64_t p = (uint64_t)ql * q_lo;
-        p += (uint64_t)(ql * q_hi + qh * q_lo) << 32;
-        uint64_t res = lo - p;
-        if (res >= q) res -= q;
+        // remainder modulo 2^64: lo - (qh 2^32 + ql) q, then one correction
+        const uint64_t t = lo - (uint64_t)ql * q_lo;
+        const uint32_t t_hi = (uint32_t)(t >> 32) - (ql * q_hi + qh * q_lo);   // upper word only
+        uint64_t res = ((uint64_t)t_hi << 32) | (uint32_t)t;
+        const uint64_t res_q = res - q;
+        res = res < q ? res : res_q;
         // (streaming store: the output is not read again by this kernel, and lines that do
         // not sit dirty in L2 need no write-back when the kernel ends)
         if (row0 + roff(r) < a.m) __builtin_nontemporal_store(res, &out0[(size_t)roff(r) * a.C]);
