@@ -614,52 +614,59 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         add128(cst_hi, cst_lo, __umul64hi(S, (uint64_t)a.offx), S * (uint64_t)a.offx);
     }
     // V = cst + mask + sum_d D_d 256^d, 0 <= V < 2^47 q.  Two things are needed of V: its
-    // low 64 bits, exactly, and V / q to within 1/2.  Low bits: diagonals 0-3 with
-    // signed 64-bit multiply-adds, diagonals 4-7 only reach the upper word, diagonals
-    // from 8 on not at all.  Quotient: V in double precision; every term is exact, the
-    // partial sums stay below 4 * 2^sh q in magnitude (signed digits: the digit
-    // magnitudes of an operand add up to at most twice its bound), and only the last
-    // few roundings are relative to such a sum, so the estimate is off by well under
-    // 1/2.  With 1/2 taken off before truncating it is floor(V/q) or one less, never
-    // more; the remainder is then formed modulo 2^64 and corrected once.
+    // low 64 bits, exactly, and V / q to within 1/2.  The diagonals are first gathered four
+    // at a time into exact 64-bit integers with signed 32 x 32 + 64-bit multiply-adds,
+    //     g0 = c0 + sum_{d<4} D_d 256^d,   g1 = c1 + sum_{4<=d<8} D_d 256^(d-4),
+    // (c0, c1: the two low 32-bit words of cst; |g| < 2^56), so that
+    //     V = (g0 + mask) + 2^32 g1 + 2^64 (cst_hi + sum_{d>=8} D_d 256^(d-8)).
+    // Low bits: those of g0 + mask, with the low word of g1 added to the upper word.
+    // Quotient: the three terms in double precision.  The third is exact (below 2^53);
+    // g1 and g0 + mask each round once when they are converted; every partial sum is a
+    // prefix of the signed-digit expansion and stays below 4 * 2^sh q in magnitude (the
+    // digit magnitudes of an operand add up to at most twice its bound), so the handful of
+    // roundings, each relative to such a sum, leave the estimate off by well under 1/2.
+    // With 1/2 taken off before truncating it is floor(V/q) or one less, never more; the
+    // remainder is then formed modulo 2^64 and corrected once.
     const double two32 = 4294967296.0;
-    double cst_d = fma((double)(uint32_t)(cst_lo >> 32), two32, (double)(uint32_t)cst_lo);
-    cst_d = fma((double)(uint32_t)cst_hi, two32 * two32, cst_d);
-    cst_d = fma((double)(uint32_t)(cst_hi >> 32), two32 * two32 * two32, cst_d);
+    const int64_t c0 = (int64_t)(cst_lo & 0xffffffffu), c1 = (int64_t)(cst_lo >> 32);
+    // cst < 2^108 (q << sh < 2^107, OFFX * S < 2^94): its upper word converts exactly
+    const double k2 = fma((double)(uint32_t)(cst_hi >> 32), two32, (double)(uint32_t)cst_hi) *
+                      (two32 * two32);
     const uint32_t q_lo = (uint32_t)q, q_hi = (uint32_t)(q >> 32);
-    // First everything that does not need the mask words (their loads are in flight): per
-    // element the low 64 bits and the double of sum_d D_d 256^d; then, per element, mask and
-    // constant, quotient, remainder, store.
-    // (the powers of 256 are kept opaque so that each term is one 32 x 32 + 64-bit
-    // multiply-add instead of a sign extension, a 64-bit shift and a 64-bit add)
+    // First everything that does not need the mask words (their loads are in flight), then,
+    // per element, mask, quotient, remainder, store.
+    // (the powers of 256 are kept opaque so that each term is one multiply-add instead of a
+    // sign extension, a 64-bit shift and a 64-bit add)
     int32_t pow256[4] = {1, 1 << 8, 1 << 16, 1 << 24};
 #pragma unroll
     for (int d = 0; d < 4; ++d) asm volatile("" : "+s"(pow256[d]));
-    uint64_t lo_part[16];
-    double vd_part[16];
+    static_assert(ND >= 8, "two full groups of diagonals");
+    int64_t g0[16];
+    uint32_t g1_lo[16];
+    double v_hi[16];                                // 2^32 g1 + 2^64 (...), in double
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         auto D = [&](int d) -> int32_t { return acc[d][r]; };
-        uint64_t lo = cst_lo;
+        int64_t s0 = c0, s1 = c1;
 #pragma unroll
-        for (int d = 0; d < 4 && d < ND; ++d)
-            lo += (uint64_t)((int64_t)D(d) * (int64_t)pow256[d]);
-        uint32_t up = 0;
+        for (int d = 0; d < 4; ++d) s0 += (int64_t)D(d) * (int64_t)pow256[d];
 #pragma unroll
-        for (int d = 4; d < 8 && d < ND; ++d) up += (uint32_t)D(d) << (8 * (d - 4));
-        lo_part[r] = lo + ((uint64_t)up << 32);
-        double vd = 0.0, scale = 1.0;
+        for (int d = 4; d < 8; ++d) s1 += (int64_t)D(d) * (int64_t)pow256[d - 4];
+        double top = k2, scale = two32 * two32;
 #pragma unroll
-        for (int d = 0; d < ND; ++d) {
-            vd = fma((double)D(d), scale, vd);
+        for (int d = 8; d < ND; ++d) {
+            top = fma((double)D(d), scale, top);
             scale *= 256.0;
         }
-        vd_part[r] = vd;
+        g0[r] = s0;
+        g1_lo[r] = (uint32_t)s1;
+        const double s1_d = fma((double)(int32_t)(s1 >> 32), two32, (double)(uint32_t)s1);
+        v_hi[r] = fma(s1_d, two32, top);
     }
     // the second half stays behind the first: volatile statements keep their order, and
     // these make the first half's results and the loaded words pass through them
 #pragma unroll
-    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(lo_part[r]), "+v"(vd_part[r]));
+    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(g0[r]), "+v"(g1_lo[r]), "+v"(v_hi[r]));
     // Shares wider than 32 bits take two passes, x = x_lo + 2^32 x_hi: the second one adds
     // 2^32 times the (reduced) result of the pass over the upper halves, read from where
     // this pass writes its own result (prev may be out: an element is read and written by
@@ -673,10 +680,10 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
             pv[r] = row0 + roff(r) < a.m ? __builtin_nontemporal_load(&prev0[(size_t)roff(r) * a.C]) : 0;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            lo_part[r] += pv[r] << 32;
+            g1_lo[r] += (uint32_t)pv[r];
             // exact below 2^53; above, off by < 2^-53 of a term that is < 2^32 q
-            vd_part[r] = fma(fma((double)(uint32_t)(pv[r] >> 32), two32, (double)(uint32_t)pv[r]),
-                             two32, vd_part[r]);
+            v_hi[r] = fma(fma((double)(uint32_t)(pv[r] >> 32), two32, (double)(uint32_t)pv[r]),
+                          two32, v_hi[r]);
         }
         asm volatile("" ::: "memory");
     }
@@ -684,15 +691,16 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(mk[r]));
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        const uint64_t lo = lo_part[r] + mk[r];
+        const int64_t t0 = g0[r] + (int64_t)mk[r];          // |g0| < 2^56, mask < 2^62
+        const uint32_t lo_lo = (uint32_t)t0;
+        const uint32_t lo_hi = (uint32_t)(t0 >> 32) + g1_lo[r];
         // quotient estimate
-        double vd = vd_part[r] + fma((double)(uint32_t)(mk[r] >> 32), two32, (double)(uint32_t)mk[r]);
-        vd += cst_d;
+        const double vd = v_hi[r] + fma((double)(int32_t)(t0 >> 32), two32, (double)lo_lo);
         const double qd = fmax(fma(vd, qinv, -0.5), 0.0);
         const uint32_t qh = (uint32_t)(qd * (1.0 / two32));
         const uint32_t ql = (uint32_t)fma(-(double)qh, two32, qd);
         // remainder modulo 2^64: lo - (qh 2^32 + ql) q, then one correction
-        const uint64_t t = lo - (uint64_t)ql * q_lo;
+        const uint64_t t = (((uint64_t)lo_hi << 32) | lo_lo) - (uint64_t)ql * q_lo;
         const uint32_t t_hi = (uint32_t)(t >> 32) - (ql * q_hi + qh * q_lo);   // upper word only
         uint64_t res = ((uint64_t)t_hi << 32) | (uint32_t)t;
         const uint64_t res_q = res - q;
