@@ -1,6 +1,7 @@
 """MI355X (gfx950) library for the client side of the Nimbus COP linear layer.
 
-Thin ctypes binding over libnimbus_cop.so (C ABI in include/nimbus_cop.h): argument
+Thin ctypes binding over libnimbus_cop.so (C ABI in include/nimbus_cop.h, and
+include/nimbus_rlwe.h for the server side: encryption of the weights, decryption): argument
 marshalling only, every step of the computation runs in the HIP kernels.
 """
 from .binding import (  # noqa: F401
@@ -22,4 +23,11 @@ from .binding import (  # noqa: F401
     CALIBRATION_SYMBOLS,
     nimbus_calib_mfma_i8,
     nimbus_calib_stream_read,
+    RLWE_SYMBOLS,
+    nimbus_rlwe_tables_bytes,
+    nimbus_rlwe_setup,
+    nimbus_rlwe_phase,
+    nimbus_rlwe_decode,
+    nimbus_rlwe_decrypt,
+    nimbus_rlwe_encrypt,
 )

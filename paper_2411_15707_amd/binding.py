@@ -31,6 +31,15 @@ EXPORTED_SYMBOLS = (
 
 CALIBRATION_SYMBOLS = ("nimbus_calib_mfma_i8", "nimbus_calib_stream_read")
 
+RLWE_SYMBOLS = (
+    "nimbus_rlwe_tables_bytes",
+    "nimbus_rlwe_setup",
+    "nimbus_rlwe_phase",
+    "nimbus_rlwe_decode",
+    "nimbus_rlwe_decrypt",
+    "nimbus_rlwe_encrypt",
+)
+
 
 class NimbusCopError(RuntimeError):
     def __init__(self, status: int, where: str):
@@ -76,6 +85,18 @@ def load_library():
     lib.nimbus_calib_mfma_i8.argtypes = [ci, ci, ci, vp, sz, vp]
     lib.nimbus_calib_stream_read.restype = ctypes.c_longlong
     lib.nimbus_calib_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.nimbus_rlwe_tables_bytes.restype = sz
+    lib.nimbus_rlwe_tables_bytes.argtypes = [ci, ci]
+    lib.nimbus_rlwe_setup.restype = ci
+    lib.nimbus_rlwe_setup.argtypes = [ci, ci, vp, vp, vp, sz, vp]
+    lib.nimbus_rlwe_phase.restype = ci
+    lib.nimbus_rlwe_phase.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+    lib.nimbus_rlwe_decode.restype = ci
+    lib.nimbus_rlwe_decode.argtypes = [vp, ci, ci, ci, vp, ci, vp, vp]
+    lib.nimbus_rlwe_decrypt.restype = ci
+    lib.nimbus_rlwe_decrypt.argtypes = [vp, ci, ci, ci, vp, ci, vp, vp, vp, vp]
+    lib.nimbus_rlwe_encrypt.restype = ci
+    lib.nimbus_rlwe_encrypt.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.nimbus_cop_strerror.restype = ctypes.c_char_p
     lib.nimbus_cop_strerror.argtypes = [ci]
     lib.nimbus_cop_version.restype = ci
@@ -242,3 +263,72 @@ def nimbus_calib_stream_read(src, sink, stream=None) -> int:
     if n < 0:
         raise NimbusCopError(NIMBUS_INVALID, "nimbus_calib_stream_read")
     return int(n)
+
+
+# ---------------------------------------------------------------------------
+# server side: key tables, encryption of the weight rows, decryption
+# ---------------------------------------------------------------------------
+def _bytes_of(t, name, count):
+    if t.element_size() != 1:
+        raise ValueError(f"{name} must hold bytes")
+    if t.numel() != count:
+        raise ValueError(f"{name} has {t.numel()} bytes, expected {count}")
+
+
+def nimbus_rlwe_tables_bytes(N, L) -> int:
+    return int(load_library().nimbus_rlwe_tables_bytes(N, L))
+
+
+def nimbus_rlwe_setup(N, L, moduli, s, tables, stream=None):
+    lib = load_library()
+    _bytes_of(s, "s", N)
+    rc = lib.nimbus_rlwe_setup(N, L, _moduli(moduli), _dev_ptr(s, "s"), _dev_ptr(tables, "tables"),
+                               tables.numel() * tables.element_size(), _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_rlwe_setup")
+
+
+def nimbus_rlwe_phase(ct, T, N, L, moduli, tables, phi, stream=None):
+    lib = load_library()
+    _words(ct, "ct", T * 2 * L * N)
+    _words(phi, "phi", T * L * N)
+    rc = lib.nimbus_rlwe_phase(_dev_ptr(ct, "ct"), T, N, L, _moduli(moduli),
+                               _dev_ptr(tables, "tables"), _dev_ptr(phi, "phi"), _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_rlwe_phase")
+
+
+def nimbus_rlwe_decode(phi, T, N, L, moduli, t_bits, m_hat, stream=None):
+    lib = load_library()
+    _words(phi, "phi", T * L * N)
+    _words(m_hat, "m_hat", T * N)
+    rc = lib.nimbus_rlwe_decode(_dev_ptr(phi, "phi"), T, N, L, _moduli(moduli), t_bits,
+                                _dev_ptr(m_hat, "m_hat"), _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_rlwe_decode")
+
+
+def nimbus_rlwe_decrypt(ct, T, N, L, moduli, t_bits, tables, phi, m_hat, stream=None):
+    lib = load_library()
+    _words(ct, "ct", T * 2 * L * N)
+    _words(phi, "phi", T * L * N)
+    _words(m_hat, "m_hat", T * N)
+    rc = lib.nimbus_rlwe_decrypt(_dev_ptr(ct, "ct"), T, N, L, _moduli(moduli), t_bits,
+                                 _dev_ptr(tables, "tables"), _dev_ptr(phi, "phi"),
+                                 _dev_ptr(m_hat, "m_hat"), _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_rlwe_decrypt")
+
+
+def nimbus_rlwe_encrypt(W, k, n, t_bits, N, L, moduli, tables, a, e, ctW, stream=None):
+    lib = load_library()
+    Ch = -(-n // N)
+    _words(W, "W", k * n)
+    _words(a, "a", k * Ch * L * N)
+    _bytes_of(e, "e", k * Ch * N)
+    _words(ctW, "ctW", k * Ch * 2 * L * N)
+    rc = lib.nimbus_rlwe_encrypt(_dev_ptr(W, "W"), k, n, t_bits, N, L, _moduli(moduli),
+                                 _dev_ptr(tables, "tables"), _dev_ptr(a, "a"), _dev_ptr(e, "e"),
+                                 _dev_ptr(ctW, "ctW"), _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_rlwe_encrypt")

@@ -1,0 +1,632 @@
+// Server side of the Nimbus linear layer on gfx950: negacyclic number-theoretic transform
+// per RNS limb, and on top of it the setup-phase encryption of the weight rows (Algorithm 1
+// step 1 with the row-wise encoding of Section 3.2, Eq. (2)) and the decryption + decoding
+// of returned ciphertexts (Algorithm 1 step 5; Enc / Dec of Appendix B.1).
+// Declarations and the contract of every entry point: include/nimbus_rlwe.h.
+//
+// One workgroup transforms one polynomial of one limb entirely inside the LDS:
+//   load -> forward rounds -> pointwise product with the transformed secret -> inverse
+//   rounds -> (add c0 | assemble c0) -> store,
+// so a product c1 * s costs one read of c1 and one write of the result in HBM.
+//
+// Transform (the usual in-place pair for X^N + 1, psi a primitive 2N-th root of unity):
+//   forward:  stages m = 1, 2, 4, ..., N/2 blocks; in block i of a stage every pair
+//             (j, j + t), t = N / 2m, becomes (u + w v, u - w v) with w = psi^brv(m + i);
+//             natural order in, bit-reversed order out;
+//   inverse:  the same stages backwards, (u, v) -> (u + v, (u - v) w^-1); the factor 1/N
+//             is folded into the table of the transformed secret.
+// A round keeps 2^S coefficients of a thread in registers for S <= 4 consecutive stages;
+// between rounds the coefficients go through the LDS.  The last forward round, the
+// pointwise product and the first inverse round work on the same coefficients of the same
+// thread and are one round.
+//
+// Arithmetic: moduli below 2^62, values kept lazily in [0, 4q) (forward) and [0, 2q)
+// (inverse); a product by a table constant w uses its companion floor(w 2^64 / q):
+//   x w - floor(x w' / 2^64) q  lies in [0, 2q) for every 64-bit x.
+#include "cop_common.hpp"
+#include "../../include/nimbus_cop.h"
+#include "../../include/nimbus_rlwe.h"
+
+namespace nimbus {
+
+typedef unsigned __int128 u128;
+
+constexpr int kRlweMinLogN = 5;
+constexpr int kRlweMaxLogN = 14;        // 2^14 coefficients of 8 bytes = 128 KiB of the 160 KiB LDS
+
+struct Twiddle {
+    uint64_t w;     // < q
+    uint64_t ws;    // floor(w * 2^64 / q)
+};
+
+// per limb: forward powers | inverse powers | transformed secret (times 1/N), N entries each
+__host__ __device__ inline size_t limb_table_entries(int N) { return (size_t)3 * (size_t)N; }
+
+struct RlweLimb {
+    Limb red;           // constants of the one-shot reduction of a 128-bit value
+    uint64_t psi;       // primitive 2N-th root of unity mod q (setup only)
+    uint64_t psi_inv;   // its inverse (setup only)
+    uint64_t n_inv;     // N^-1 mod q (setup only)
+    uint64_t delta;     // floor(Q / t) mod q (encryption only)
+};
+
+struct RlweArgs {
+    RlweLimb limb[kMaxLimbs];
+};
+
+__device__ __forceinline__ uint64_t mul_lazy(uint64_t x, const Twiddle &t, uint64_t q)
+{
+    return x * t.w - __umul64hi(x, t.ws) * q;
+}
+
+// a, b < q  ->  a b mod q
+__device__ __forceinline__ uint64_t mulmod(uint64_t a, uint64_t b, const Limb &P)
+{
+    return barrett128(__umul64hi(a, b), a * b, P);
+}
+
+__device__ uint64_t powmod(uint64_t base, uint32_t e, const Limb &P)
+{
+    uint64_t r = 1;
+    while (e) {
+        if (e & 1u) r = mulmod(r, base, P);
+        base = mulmod(base, base, P);
+        e >>= 1;
+    }
+    return r;
+}
+
+// floor(w * 2^64 / q) for w < q < 2^62: schoolbook binary division
+__device__ uint64_t companion(uint64_t w, uint64_t q)
+{
+    uint64_t r = w, quo = 0;
+    for (int i = 0; i < 64; ++i) {
+        r <<= 1;
+        quo <<= 1;
+        if (r >= q) {
+            r -= q;
+            quo |= 1u;
+        }
+    }
+    return quo;
+}
+
+// ---------------------------------------------------------------------------
+// setup: powers of psi in bit-reversed order, forward and inverse, with companions
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rlwe_powers_kernel(RlweArgs a, int logN, int L,
+                                                          Twiddle *__restrict__ tables)
+{
+    const uint32_t N = 1u << logN;
+    const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
+    if (gid >= N * (uint32_t)L) return;
+    const uint32_t l = gid >> logN, i = gid & (N - 1u);
+    const RlweLimb &P = a.limb[l];
+    const uint32_t e = __brev(i) >> (32 - logN);
+    Twiddle *const t = tables + (size_t)l * limb_table_entries((int)N);
+    const uint64_t f = powmod(P.psi, e, P.red), g = powmod(P.psi_inv, e, P.red);
+    t[i] = Twiddle{f, companion(f, P.red.q)};
+    t[N + i] = Twiddle{g, companion(g, P.red.q)};
+}
+
+// ---------------------------------------------------------------------------
+// the transform rounds
+// ---------------------------------------------------------------------------
+constexpr int rounds_for(int stages) { return (stages + 3) / 4; }
+// stages of the next round when `stages` are left: as even a split as possible
+constexpr int round_stages(int stages) { return (stages + rounds_for(stages) - 1) / rounds_for(stages); }
+constexpr int threads_for(int logN)
+{
+    const int t = (1 << logN) / 16;
+    return t < 64 ? 64 : (t > 1024 ? 1024 : t);
+}
+
+enum RoundKind { kForward, kInverse, kMiddle };
+
+// One round over the stages P0 .. P0+S-1.  A group is the 2^S coefficients
+//   base + r * 2^LT,  r < 2^S,  base = i0 * 2^(LOGN-P0) + o,  o < 2^LT,  LT = LOGN - P0 - S:
+// block i0 of stage P0 (2^P0 blocks), offset o inside the smallest stride of the round.
+// In stage P0+st coefficient r of the group sits in block i0 * 2^st + (r >> (S - st)).
+template <int LOGN, int P0, int S, RoundKind KIND, int NT>
+__device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restrict__ fwd,
+                                          const Twiddle *__restrict__ inv,
+                                          const Twiddle *__restrict__ shat, uint64_t q, int tid)
+{
+    constexpr int N = 1 << LOGN, R = 1 << S, LT = LOGN - P0 - S, G = N / R;
+    const uint64_t two_q = 2 * q;
+    for (int g = tid; g < G; g += NT) {
+        const int i0 = g >> LT, o = g & ((1 << LT) - 1);
+        const int base = (i0 << (LOGN - P0)) + o;
+        uint64_t x[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) x[r] = lds[base + (r << LT)];
+        if constexpr (KIND != kInverse) {
+#pragma unroll
+            for (int st = 0; st < S; ++st) {
+                const int half = R >> (st + 1);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (r & half) continue;
+                    const Twiddle t = fwd[(1 << (P0 + st)) + (i0 << st) + (r >> (S - st))];
+                    uint64_t u = x[r];
+                    u = u >= two_q ? u - two_q : u;
+                    const uint64_t v = mul_lazy(x[r + half], t, q);
+                    x[r] = u + v;
+                    x[r + half] = u - v + two_q;
+                }
+            }
+        }
+        if constexpr (KIND == kMiddle) {
+            // bit-reversed position = LDS index: the transformed secret uses the same order
+#pragma unroll
+            for (int r = 0; r < R; ++r) x[r] = mul_lazy(x[r], shat[base + (r << LT)], q);
+        }
+        if constexpr (KIND != kForward) {
+#pragma unroll
+            for (int st = S - 1; st >= 0; --st) {
+                const int half = R >> (st + 1);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (r & half) continue;
+                    const Twiddle t = inv[(1 << (P0 + st)) + (i0 << st) + (r >> (S - st))];
+                    const uint64_t u = x[r], v = x[r + half];
+                    const uint64_t sum = u + v;
+                    x[r] = sum >= two_q ? sum - two_q : sum;
+                    x[r + half] = mul_lazy(u - v + two_q, t, q);
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) lds[base + (r << LT)] = x[r];
+    }
+}
+
+// forward rounds from stage P0 on, the pointwise product, and the inverse rounds back to P0
+template <int LOGN, int P0, int NT>
+__device__ __forceinline__ void multiply_by_secret(uint64_t *lds, const Twiddle *fwd,
+                                                   const Twiddle *inv, const Twiddle *shat,
+                                                   uint64_t q, int tid)
+{
+    constexpr int S = round_stages(LOGN - P0);
+    if constexpr (P0 + S == LOGN) {
+        ntt_round<LOGN, P0, S, kMiddle, NT>(lds, fwd, inv, shat, q, tid);
+        __syncthreads();
+    } else {
+        ntt_round<LOGN, P0, S, kForward, NT>(lds, fwd, inv, shat, q, tid);
+        __syncthreads();
+        multiply_by_secret<LOGN, P0 + S, NT>(lds, fwd, inv, shat, q, tid);
+        ntt_round<LOGN, P0, S, kInverse, NT>(lds, fwd, inv, shat, q, tid);
+        __syncthreads();
+    }
+}
+
+template <int LOGN, int P0, int NT>
+__device__ __forceinline__ void forward_only(uint64_t *lds, const Twiddle *fwd, uint64_t q, int tid)
+{
+    if constexpr (P0 < LOGN) {
+        constexpr int S = round_stages(LOGN - P0);
+        ntt_round<LOGN, P0, S, kForward, NT>(lds, fwd, nullptr, nullptr, q, tid);
+        __syncthreads();
+        forward_only<LOGN, P0 + S, NT>(lds, fwd, q, tid);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// setup: transform of the secret, times 1/N, with companions
+// one workgroup per limb
+// ---------------------------------------------------------------------------
+template <int LOGN>
+__global__ __launch_bounds__(threads_for(LOGN)) void rlwe_secret_kernel(
+    RlweArgs a, const int8_t *__restrict__ s, Twiddle *__restrict__ tables)
+{
+    constexpr int N = 1 << LOGN, NT = threads_for(LOGN);
+    __shared__ uint64_t lds[N];
+    const int tid = threadIdx.x, l = blockIdx.x;
+    const RlweLimb &P = a.limb[l];
+    const uint64_t q = P.red.q;
+    Twiddle *const t = tables + (size_t)l * limb_table_entries(N);
+    for (int c = tid; c < N; c += NT) {
+        const int v = s[c];
+        lds[c] = v < 0 ? q - (uint64_t)(-v) : (uint64_t)v;
+    }
+    __syncthreads();
+    forward_only<LOGN, 0, NT>(lds, t, q, tid);
+    for (int c = tid; c < N; c += NT) {
+        uint64_t v = lds[c];                    // [0, 4q)
+        v = v >= 2 * q ? v - 2 * q : v;
+        v = v >= q ? v - q : v;
+        v = mulmod(v, P.n_inv, P.red);
+        t[2 * N + c] = Twiddle{v, companion(v, q)};
+    }
+}
+
+// ---------------------------------------------------------------------------
+// c1 * s per (ciphertext, limb), then either the phase or the assembly of c0
+// ---------------------------------------------------------------------------
+struct PolyArgs {
+    const Twiddle *tables;
+    int L;
+    // phase: src = ct [T][2][L][N], dst = phi [T][L][N]
+    // encrypt: src = a [rows][L][N], dst = ctW [rows][2][L][N]
+    const uint64_t *src;
+    uint64_t *dst;
+    // encrypt only
+    const uint64_t *W;      // [k][n]
+    const int8_t *e;        // [rows][N]
+    int n, Ch;
+    RlweArgs limbs;
+};
+
+template <int LOGN, bool ENCRYPT>
+__global__ __launch_bounds__(threads_for(LOGN)) void rlwe_poly_kernel(PolyArgs a)
+{
+    constexpr int N = 1 << LOGN, NT = threads_for(LOGN);
+    __shared__ uint64_t lds[N];
+    const int tid = threadIdx.x;
+    const uint32_t row = blockIdx.x / (uint32_t)a.L, l = blockIdx.x % (uint32_t)a.L;
+    const RlweLimb &P = a.limbs.limb[l];
+    const uint64_t q = P.red.q;
+    const Twiddle *const t = a.tables + (size_t)l * limb_table_entries(N);
+    // the polynomial that is multiplied by s
+    const uint64_t *const mul_in =
+        ENCRYPT ? a.src + ((size_t)row * a.L + l) * N
+                : a.src + (((size_t)row * 2 + 1) * a.L + l) * N;
+    for (int c = tid; c < N; c += NT) lds[c] = mul_in[c];
+    __syncthreads();
+    multiply_by_secret<LOGN, 0, NT>(lds, t, t + N, t + 2 * N, q, tid);
+    if constexpr (!ENCRYPT) {
+        const uint64_t *const c0 = a.src + (((size_t)row * 2 + 0) * a.L + l) * N;
+        uint64_t *const phi = a.dst + ((size_t)row * a.L + l) * N;
+        for (int c = tid; c < N; c += NT) {
+            uint64_t v = lds[c];                // [0, 2q)
+            v = v >= q ? v - q : v;
+            v += c0[c];
+            phi[c] = v >= q ? v - q : v;
+        }
+    } else {
+        uint64_t *const c0 = a.dst + (((size_t)row * 2 + 0) * a.L + l) * N;
+        uint64_t *const c1 = a.dst + (((size_t)row * 2 + 1) * a.L + l) * N;
+        const uint32_t i = row / (uint32_t)a.Ch, ch = row % (uint32_t)a.Ch;
+        const uint64_t *const Wrow = a.W + (size_t)i * a.n;
+        const int8_t *const e = a.e + (size_t)row * N;
+        for (int c = tid; c < N; c += NT) {
+            uint64_t as = lds[c];               // [0, 2q)
+            as = as >= q ? as - q : as;
+            // Eq. (2) with chunking: coefficient c of chunk ch is column ch N + c, zero past n
+            const uint32_t col = ch * (uint32_t)N + (uint32_t)c;
+            const uint64_t w = col < (uint32_t)a.n ? Wrow[col] : 0;
+            uint64_t v = barrett128(__umul64hi(P.delta, w), P.delta * w, P.red);   // w < t < q
+            const int ev = e[c];
+            v += ev < 0 ? q - (uint64_t)(-ev) : (uint64_t)ev;
+            v += q - as;                        // < 3q
+            v = v >= q ? v - q : v;
+            v = v >= q ? v - q : v;
+            c0[c] = v;
+            c1[c] = mul_in[c];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// decoding: CRT of the limb phases, then rounding division by Delta
+// ---------------------------------------------------------------------------
+struct DecodeArgs {
+    const uint64_t *phi;    // [T][L][N]
+    uint64_t *m_hat;        // [T][N]
+    int L, logN;
+    uint64_t total;         // T * N
+    uint64_t q0;
+    Limb red1;              // limb 1 (L == 2)
+    uint64_t q0_inv;        // q0^-1 mod q1
+    uint64_t delta_hi, delta_lo, half_hi, half_lo;   // Delta and floor(Delta / 2)
+    double delta_inv;       // 1 / Delta, rounded
+    uint64_t t_mask;
+};
+
+__global__ __launch_bounds__(256) void rlwe_decode_kernel(DecodeArgs a)
+{
+    const uint64_t gid = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (gid >= a.total) return;
+    const uint64_t N = 1ull << a.logN;
+    const uint64_t row = gid >> a.logN, c = gid & (N - 1);
+    const uint64_t *const ph = a.phi + row * (uint64_t)a.L * N;
+    const uint64_t p0 = ph[c];
+    u128 v = p0;
+    if (a.L == 2) {
+        // Garner: phi = p0 + q0 * ((p1 - p0) * q0^-1 mod q1)
+        const uint64_t q1 = a.red1.q;
+        const uint64_t p1 = ph[N + c];
+        const uint64_t p0r = barrett128(0, p0, a.red1);
+        uint64_t diff = p1 + q1 - p0r;
+        diff = diff >= q1 ? diff - q1 : diff;
+        const uint64_t h = mulmod(diff, a.q0_inv, a.red1);
+        v += (u128)a.q0 * h;
+    }
+    const u128 delta = ((u128)a.delta_hi << 64) | a.delta_lo;
+    const u128 num = v + (((u128)a.half_hi << 64) | a.half_lo);
+    // quotient <= 2^32 + 1: a double-precision estimate is within one of it
+    const double nd = fma((double)(uint64_t)(num >> 64), 18446744073709551616.0,
+                          (double)(uint64_t)num);
+    uint64_t est = (uint64_t)(nd * a.delta_inv);
+    u128 prod = delta * est;                    // about num: no overflow
+    if (prod > num) {                           // one too many
+        est -= 1;
+        prod -= delta;
+    }
+    if (num - prod >= delta) est += 1;          // one too few
+    a.m_hat[gid] = est & a.t_mask;
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+static uint64_t h_mulmod(uint64_t a, uint64_t b, uint64_t q) { return (uint64_t)((u128)a * b % q); }
+
+static uint64_t h_powmod(uint64_t base, uint64_t e, uint64_t q)
+{
+    uint64_t r = 1 % q;
+    base %= q;
+    while (e) {
+        if (e & 1) r = h_mulmod(r, base, q);
+        base = h_mulmod(base, base, q);
+        e >>= 1;
+    }
+    return r;
+}
+
+// inverse of a modulo mod (coprime), by the extended Euclidean algorithm
+static uint64_t h_invmod(uint64_t a, uint64_t mod)
+{
+    __int128 old_r = (__int128)(a % mod), r = (__int128)mod, old_c = 1, c = 0;
+    while (r != 0) {
+        const __int128 quo = old_r / r;
+        const __int128 nr = old_r - quo * r;
+        old_r = r;
+        r = nr;
+        const __int128 ncoef = old_c - quo * c;
+        old_c = c;
+        c = ncoef;
+    }
+    if (old_r != 1) return 0;                   // not coprime
+    __int128 res = old_c % (__int128)mod;
+    if (res < 0) res += mod;
+    return (uint64_t)res;
+}
+
+static int log2_exact(int N)
+{
+    int b = 0;
+    while ((1 << b) < N) ++b;
+    return b;
+}
+
+static int bit_length64(uint64_t v)
+{
+    int b = 0;
+    while (v) { ++b; v >>= 1; }
+    return b;
+}
+
+// shape and modulus checks shared by every entry point; fills the reduction constants
+static int rlwe_check(int N, int L, const uint64_t *moduli, RlweArgs *out)
+{
+    if (!moduli) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (N < 32 || N > 65536 || (N & (N - 1)) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (L < 1 || L > kMaxLimbs) return NIMBUS_COP_ERR_INVALID_ARG;
+    RlweArgs a{};
+    for (int l = 0; l < L; ++l) {
+        const uint64_t q = moduli[l];
+        if ((q & 1) == 0 || q >= (1ull << 62) || q < 3) return NIMBUS_COP_ERR_INVALID_ARG;
+        if ((q - 1) % (2ull * (uint64_t)N) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
+        for (int j = 0; j < l; ++j)
+            if (moduli[j] == q) return NIMBUS_COP_ERR_INVALID_ARG;
+        const int b = bit_length64(q);
+        Limb &P = a.limb[l].red;
+        P.q = q;
+        P.s1 = (uint32_t)(b - 1);
+        P.mu = (uint64_t)((((u128)1) << (b + 63)) / q);
+        P.pad = 0;
+    }
+    if (N > (1 << kRlweMaxLogN)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    *out = a;
+    return NIMBUS_COP_OK;
+}
+
+// a primitive 2N-th root of unity: psi^N = -1.  Any of them gives the same products.
+static bool find_psi(uint64_t q, int N, uint64_t *psi)
+{
+    const uint64_t e = (q - 1) / (2ull * (uint64_t)N);
+    for (uint64_t g = 2; g < 2000 && g < q; ++g) {
+        const uint64_t cand = h_powmod(g, e, q);
+        if (h_powmod(cand, (uint64_t)N, q) == q - 1) {
+            *psi = cand;
+            return true;
+        }
+    }
+    return false;
+}
+
+// Delta = floor(Q / 2^t_bits) for L <= 2
+static int scaling(int L, const uint64_t *moduli, int t_bits, u128 *Q, u128 *delta)
+{
+    if (t_bits < 1 || t_bits > 32) return NIMBUS_COP_ERR_INVALID_ARG;
+    for (int l = 0; l < L; ++l)
+        if (moduli[l] <= (1ull << t_bits)) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (L > 2) return NIMBUS_COP_ERR_UNSUPPORTED;
+    *Q = L == 1 ? (u128)moduli[0] : (u128)moduli[0] * moduli[1];
+    *delta = *Q >> t_bits;
+    return NIMBUS_COP_OK;
+}
+
+#define NIMBUS_RLWE_DISPATCH(logN, CALL)                                          \
+    switch (logN) {                                                               \
+    case 5: { constexpr int LOGN = 5; CALL; break; }                              \
+    case 6: { constexpr int LOGN = 6; CALL; break; }                              \
+    case 7: { constexpr int LOGN = 7; CALL; break; }                              \
+    case 8: { constexpr int LOGN = 8; CALL; break; }                              \
+    case 9: { constexpr int LOGN = 9; CALL; break; }                              \
+    case 10: { constexpr int LOGN = 10; CALL; break; }                            \
+    case 11: { constexpr int LOGN = 11; CALL; break; }                            \
+    case 12: { constexpr int LOGN = 12; CALL; break; }                            \
+    case 13: { constexpr int LOGN = 13; CALL; break; }                            \
+    case 14: { constexpr int LOGN = 14; CALL; break; }                            \
+    default: return hipErrorInvalidValue;                                         \
+    }
+
+static hipError_t launch_secret(const RlweArgs &a, int logN, int L, const int8_t *s,
+                                Twiddle *tables, hipStream_t stream)
+{
+    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL(rlwe_secret_kernel<LOGN>, dim3((unsigned)L),
+                                                  dim3(threads_for(LOGN)), 0, stream, a, s, tables));
+    return hipGetLastError();
+}
+
+template <bool ENCRYPT>
+static hipError_t launch_poly(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
+{
+    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL((rlwe_poly_kernel<LOGN, ENCRYPT>),
+                                                  dim3((unsigned)polys), dim3(threads_for(LOGN)),
+                                                  0, stream, a));
+    return hipGetLastError();
+}
+
+}  // namespace nimbus
+
+using namespace nimbus;
+
+extern "C" {
+
+size_t nimbus_rlwe_tables_bytes(int N, int L)
+{
+    if (N < 32 || N > (1 << kRlweMaxLogN) || (N & (N - 1)) != 0) return 0;
+    if (L < 1 || L > kMaxLimbs) return 0;
+    return (size_t)L * limb_table_entries(N) * sizeof(Twiddle);
+}
+
+int nimbus_rlwe_setup(int N, int L, const uint64_t *moduli, const int8_t *s,
+                      void *tables, size_t tables_bytes, void *stream)
+{
+    if (!s || !tables) return NIMBUS_COP_ERR_INVALID_ARG;
+    RlweArgs a;
+    const int rc = rlwe_check(N, L, moduli, &a);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if (((uintptr_t)tables & 15u) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (tables_bytes < nimbus_rlwe_tables_bytes(N, L)) return NIMBUS_COP_ERR_BUFFER_SIZE;
+    for (int l = 0; l < L; ++l) {
+        const uint64_t q = moduli[l];
+        uint64_t psi;
+        if (!find_psi(q, N, &psi)) return NIMBUS_COP_ERR_INVALID_ARG;
+        a.limb[l].psi = psi;
+        a.limb[l].psi_inv = h_powmod(psi, 2ull * (uint64_t)N - 1, q);     // psi^(2N) = 1
+        a.limb[l].n_inv = q - (q - 1) / (uint64_t)N;                      // N (q - (q-1)/N) = 1 mod q
+    }
+    const int logN = log2_exact(N);
+    const unsigned total = (unsigned)N * (unsigned)L;
+    hipLaunchKernelGGL(rlwe_powers_kernel, dim3((total + 255u) / 256u), dim3(256), 0,
+                       (hipStream_t)stream, a, logN, L, (Twiddle *)tables);
+    if (hipGetLastError() != hipSuccess) return NIMBUS_COP_ERR_LAUNCH;
+    const hipError_t e = launch_secret(a, logN, L, s, (Twiddle *)tables, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+int nimbus_rlwe_phase(const uint64_t *ct, int T, int N, int L, const uint64_t *moduli,
+                      const void *tables, uint64_t *phi, void *stream)
+{
+    if (!ct || !tables || !phi || T < 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    PolyArgs a{};
+    const int rc = rlwe_check(N, L, moduli, &a.limbs);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if ((unsigned long long)T * (unsigned)L >= (1ull << 31)) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (T == 0) return NIMBUS_COP_OK;
+    a.tables = (const Twiddle *)tables;
+    a.L = L;
+    a.src = ct;
+    a.dst = phi;
+    const hipError_t e = launch_poly<false>(a, log2_exact(N), (size_t)T * L, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+int nimbus_rlwe_decode(const uint64_t *phi, int T, int N, int L, const uint64_t *moduli,
+                       int t_bits, uint64_t *m_hat, void *stream)
+{
+    if (!phi || !m_hat || T < 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    RlweArgs limbs;
+    int rc = rlwe_check(N, L, moduli, &limbs);
+    if (rc != NIMBUS_COP_OK) return rc;
+    u128 Q, delta;
+    rc = scaling(L, moduli, t_bits, &Q, &delta);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if (T == 0) return NIMBUS_COP_OK;
+    DecodeArgs a{};
+    a.phi = phi;
+    a.m_hat = m_hat;
+    a.L = L;
+    a.logN = log2_exact(N);
+    a.total = (uint64_t)T * (uint64_t)N;
+    if (a.total >= (1ull << 39)) return NIMBUS_COP_ERR_INVALID_ARG;
+    a.q0 = moduli[0];
+    if (L == 2) {
+        a.red1 = limbs.limb[1].red;
+        a.q0_inv = h_invmod(moduli[0] % moduli[1], moduli[1]);
+        if (a.q0_inv == 0) return NIMBUS_COP_ERR_INVALID_ARG;       // moduli not coprime
+    }
+    const u128 half = delta >> 1;
+    a.delta_hi = (uint64_t)(delta >> 64);
+    a.delta_lo = (uint64_t)delta;
+    a.half_hi = (uint64_t)(half >> 64);
+    a.half_lo = (uint64_t)half;
+    a.delta_inv = 1.0 / ((double)a.delta_hi * 18446744073709551616.0 + (double)a.delta_lo);
+    a.t_mask = (1ull << t_bits) - 1;
+    hipLaunchKernelGGL(rlwe_decode_kernel, dim3((unsigned)((a.total + 255u) / 256u)), dim3(256), 0,
+                       (hipStream_t)stream, a);
+    return hipGetLastError() == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+int nimbus_rlwe_decrypt(const uint64_t *ct, int T, int N, int L, const uint64_t *moduli,
+                        int t_bits, const void *tables, uint64_t *phi, uint64_t *m_hat,
+                        void *stream)
+{
+    if (!ct || !tables || !phi || !m_hat || T < 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    // every check of the second step before the first one is enqueued
+    RlweArgs limbs;
+    int rc = rlwe_check(N, L, moduli, &limbs);
+    if (rc != NIMBUS_COP_OK) return rc;
+    u128 Q, delta;
+    rc = scaling(L, moduli, t_bits, &Q, &delta);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if ((uint64_t)T * (uint64_t)N >= (1ull << 39)) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (L == 2 && h_invmod(moduli[0] % moduli[1], moduli[1]) == 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    rc = nimbus_rlwe_phase(ct, T, N, L, moduli, tables, phi, stream);
+    if (rc != NIMBUS_COP_OK) return rc;
+    return nimbus_rlwe_decode(phi, T, N, L, moduli, t_bits, m_hat, stream);
+}
+
+int nimbus_rlwe_encrypt(const uint64_t *W, int k, int n, int t_bits, int N, int L,
+                        const uint64_t *moduli, const void *tables, const uint64_t *a_poly,
+                        const int8_t *e, uint64_t *ctW, void *stream)
+{
+    if (!W || !tables || !a_poly || !e || !ctW) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (k < 1 || n < 1) return NIMBUS_COP_ERR_INVALID_ARG;
+    PolyArgs a{};
+    int rc = rlwe_check(N, L, moduli, &a.limbs);
+    if (rc != NIMBUS_COP_OK) return rc;
+    u128 Q, delta;
+    rc = scaling(L, moduli, t_bits, &Q, &delta);
+    if (rc != NIMBUS_COP_OK) return rc;
+    const unsigned long long Ch = ((unsigned long long)n + (unsigned)N - 1) / (unsigned)N;
+    const unsigned long long polys = (unsigned long long)k * Ch * (unsigned)L;
+    if (polys >= (1ull << 31) || Ch * (unsigned)N >= (1ull << 31)) return NIMBUS_COP_ERR_INVALID_ARG;
+    for (int l = 0; l < L; ++l) a.limbs.limb[l].delta = (uint64_t)(delta % moduli[l]);
+    a.tables = (const Twiddle *)tables;
+    a.L = L;
+    a.src = a_poly;
+    a.dst = ctW;
+    a.W = W;
+    a.e = e;
+    a.n = n;
+    a.Ch = (int)Ch;
+    const hipError_t err = launch_poly<true>(a, log2_exact(N), (size_t)polys, (hipStream_t)stream);
+    return err == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -143,3 +143,65 @@ def test_wide_shares_only_on_the_prepared_path():
     assert nc.nimbus_cop_workspace_bytes(33, 65, 64) == 2 * 3 * (4 + 4) * 1024
     assert nc.nimbus_cop_workspace_bytes(33, 65, 40) == 2 * 3 * (4 + 2) * 1024
     assert nc.nimbus_cop_workspace_bytes(33, 65, 65) == 0
+
+
+def test_rlwe_header_binding_and_exports_agree():
+    text = open(os.path.join(ROOT, "include", "nimbus_rlwe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(nimbus_rlwe_\w+)\s*\(", text)))
+    assert declared == sorted(nc.RLWE_SYMBOLS)
+    lib = ctypes.CDLL(nc.lib_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_rlwe_argument_checks_on_the_host():
+    """bad calls of the server-side entry points return before anything is enqueued; the
+    pointers are dummies that are never dereferenced"""
+    lib = _raw()
+    N, L = 64, 2
+    good = ci.limb_primes(54, 20, L)                      # = 1 mod 2^20, so also mod 2N
+    mod = (ctypes.c_uint64 * L)(*good)
+    assert nc.nimbus_rlwe_tables_bytes(N, L) == L * 3 * N * 16
+    assert nc.nimbus_rlwe_tables_bytes(48, 1) == 0
+    assert nc.nimbus_rlwe_tables_bytes(16, 1) == 0
+    assert nc.nimbus_rlwe_tables_bytes(32768, 1) == 0      # does not fit the local memory
+    assert nc.nimbus_rlwe_tables_bytes(64, 5) == 0
+    big = nc.nimbus_rlwe_tables_bytes(N, L)
+    # setup
+    assert lib.nimbus_rlwe_setup(N, L, mod, None, 0x1000, big, None) == -1
+    assert lib.nimbus_rlwe_setup(N, L, mod, 0x2000, None, big, None) == -1
+    assert lib.nimbus_rlwe_setup(N, L, None, 0x2000, 0x1000, big, None) == -1
+    assert lib.nimbus_rlwe_setup(48, L, mod, 0x2000, 0x1000, big, None) == -1
+    assert lib.nimbus_rlwe_setup(N, L, mod, 0x2000, 0x1008, big, None) == -1       # alignment
+    assert lib.nimbus_rlwe_setup(N, L, mod, 0x2000, 0x1000, big - 1, None) == -4
+    assert lib.nimbus_rlwe_setup(32768, L, mod, 0x2000, 0x1000, 1 << 30, None) == -2
+    # a modulus that is not 1 modulo 2N has no 2N-th root of unity
+    bad = (ctypes.c_uint64 * 1)(97)                         # 96 is not a multiple of 128
+    assert lib.nimbus_rlwe_setup(N, 1, bad, 0x2000, 0x1000, big, None) == -1
+    even = (ctypes.c_uint64 * 1)(1 << 20)
+    assert lib.nimbus_rlwe_setup(N, 1, even, 0x2000, 0x1000, big, None) == -1
+    twice = (ctypes.c_uint64 * 2)(good[0], good[0])         # limbs must be distinct
+    assert lib.nimbus_rlwe_setup(N, 2, twice, 0x2000, 0x1000, big, None) == -1
+    # phase
+    assert lib.nimbus_rlwe_phase(None, 1, N, L, mod, 0x1000, 0x3000, None) == -1
+    assert lib.nimbus_rlwe_phase(0x4000, -1, N, L, mod, 0x1000, 0x3000, None) == -1
+    assert lib.nimbus_rlwe_phase(0x4000, 0, N, L, mod, 0x1000, 0x3000, None) == 0   # nothing to do
+    assert lib.nimbus_rlwe_phase(0x4000, 1, N, L, bad, 0x1000, 0x3000, None) == -1
+    # decode / decrypt / encrypt: at most two limbs, 1 <= t_bits <= 32, t < q
+    three = ci.limb_primes(54, 20, 3)
+    mod3 = (ctypes.c_uint64 * 3)(*three)
+    assert lib.nimbus_rlwe_decode(0x3000, 1, N, 3, mod3, 20, 0x5000, None) == -2
+    assert lib.nimbus_rlwe_decode(0x3000, 1, N, L, mod, 0, 0x5000, None) == -1
+    assert lib.nimbus_rlwe_decode(0x3000, 1, N, L, mod, 33, 0x5000, None) == -1
+    assert lib.nimbus_rlwe_decode(0x3000, 0, N, L, mod, 20, 0x5000, None) == 0
+    small = (ctypes.c_uint64 * 1)(ci.limb_primes(20, 7, 1)[0])
+    assert lib.nimbus_rlwe_decode(0x3000, 1, N, 1, small, 20, 0x5000, None) == -1   # t >= q
+    assert lib.nimbus_rlwe_decrypt(0x4000, 1, N, 3, mod3, 20, 0x1000, 0x3000, 0x5000, None) == -2
+    assert lib.nimbus_rlwe_decrypt(0x4000, 1, N, L, mod, 20, 0x1000, None, 0x5000, None) == -1
+    assert lib.nimbus_rlwe_encrypt(0x6000, 0, 8, 20, N, L, mod, 0x1000, 0x7000, 0x8000, 0x9000,
+                                   None) == -1
+    assert lib.nimbus_rlwe_encrypt(0x6000, 4, 8, 20, N, 3, mod3, 0x1000, 0x7000, 0x8000, 0x9000,
+                                   None) == -2
+    assert lib.nimbus_rlwe_encrypt(0x6000, 4, 8, 20, N, L, mod, 0x1000, None, 0x8000, 0x9000,
+                                   None) == -1
