@@ -25,6 +25,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 INT8_PEAK_TOPS = 5000.0         # MI355X dense int8 MFMA, tera-ops/s (2 ops per MAC)
+# 32-bit integer vector operations: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz
+INT32_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 METRIC = "modular MACs/sec (Z_q) + HBM GB/s, COP ct×share matmul, BERT-base FFN shape"
 
 
@@ -198,6 +200,65 @@ def main():
             "frac_of_hbm_peak": round(pack_bytes / (pack_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         }
 
+    # ---- server side of this layer (Algorithm 1 steps 1 and 5): encryption of the k weight
+    # rows and decryption of the m returned rows, plus the rate of the transform kernel on a
+    # batch large enough to fill the chip several times ----
+    server = None
+    if L <= 2 and N <= 16384:
+        logN = N.bit_length() - 1
+        seed = ci.config_seed(args.config, call=100)
+        s_dev = torch.from_numpy(ci.gen_secret(seed, N)).cuda()
+        tables = torch.empty(nc.nimbus_rlwe_tables_bytes(N, L), dtype=torch.uint8, device="cuda")
+        nc.nimbus_rlwe_setup(N, L, moduli, s_dev, tables)
+        Wp = dev(ci.gen_W(seed, k, n, xb))
+        a_np, e_np = ci.gen_enc_randomness(seed, k, cfg.Ch, moduli, N)
+        a_dev, e_dev = dev(a_np), torch.from_numpy(e_np).cuda()
+        ct_enc = torch.empty((k, cfg.Ch, 2, L, N), dtype=torch.int64, device="cuda")
+        rows = m * cfg.Ch
+        phi = torch.empty((rows, L, N), dtype=torch.int64, device="cuda")
+        m_hat = torch.empty((rows, N), dtype=torch.int64, device="cuda")
+        Tb = max(rows, (256 << 20) // (2 * L * N * 8))          # about 256 MiB of ciphertexts
+        ct_big = torch.empty((Tb, 2, L, N), dtype=torch.int64, device="cuda")
+        for l, q in enumerate(moduli):
+            ct_big[:, :, l].random_(0, q)
+        phi_big = torch.empty((Tb, L, N), dtype=torch.int64, device="cuda")
+
+        def timed_ms(launch, reps):
+            launch()
+            a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a_.record(stream)
+            for _ in range(reps):
+                launch()
+            b_.record(stream)
+            torch.cuda.synchronize()
+            return a_.elapsed_time(b_) / reps
+        enc_ms = timed_ms(lambda: nc.nimbus_rlwe_encrypt(Wp, k, n, xb, N, L, moduli, tables, a_dev,
+                                                         e_dev, ct_enc), 20)
+        dec_ms = timed_ms(lambda: nc.nimbus_rlwe_decrypt(outs[0].view(rows, 2, L, N), rows, N, L,
+                                                         moduli, xb, tables, phi, m_hat), 50)
+        big_ms = timed_ms(lambda: nc.nimbus_rlwe_phase(ct_big, Tb, N, L, moduli, tables, phi_big), 10)
+        # algorithmic 32-bit integer operations of one product by the secret: two transforms
+        # of (N/2) log N butterflies at 24 operations, N pointwise products at 16
+        int_ops = (N * logN * 24 + N * 16) * Tb * L
+        server = {
+            "kernel": f"rlwe_poly_kernel<{logN}>",
+            "encrypt_weight_rows_ms": round(enc_ms, 4),
+            "encrypt_polynomials": k * cfg.Ch * L,
+            "decrypt_output_rows_ms": round(dec_ms, 4),
+            "decrypt_ciphertexts": rows,
+            "batch_ciphertexts": Tb,
+            "batch_phase_ms": round(big_ms, 4),
+            "products_by_secret_per_s": round(Tb * L / (big_ms * 1e-3), 1),
+            "bound": "alu",
+            "achieved": round(int_ops / (big_ms * 1e-3) / 1e12, 2),
+            "peak": INT32_PEAK_TOPS,
+            "unit": "Tint32op/s",
+            "frac": round(int_ops / (big_ms * 1e-3) / 1e12 / INT32_PEAK_TOPS, 4),
+            "hbm_gbps": round(Tb * L * N * 8 * 3 / (big_ms * 1e-3) / 1e9, 1),
+        }
+        del ct_big, phi_big, ct_enc, a_dev, e_dev
+
     # ---- calibration: what this chip sustains on the two resources that bound the kernel ----
     # (register-only int8 matrix-core loop with zero and with random operand bytes; streaming
     # read of one prepared weight buffer per launch, rotating over all of them)
@@ -289,6 +350,7 @@ def main():
         "canonical_layout_valu_kernel_ms": round(valu_ms, 4),
         "roofline": roofline,
         "pack": pack,
+        "server": server,
         "calibration": calibration,
         "cpu_baseline": cpu_baseline,
         "output_matches_oracle": verified,
