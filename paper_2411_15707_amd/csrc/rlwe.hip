@@ -112,14 +112,25 @@ __global__ __launch_bounds__(256) void rlwe_powers_kernel(RlweArgs a, int logN, 
 // ---------------------------------------------------------------------------
 // the transform rounds
 // ---------------------------------------------------------------------------
-constexpr int rounds_for(int stages) { return (stages + 3) / 4; }
+// MAXS: most stages a round may take (2^MAXS coefficients per thread and round).  Large
+// batches use 4: fewest trips through the LDS.  A batch that cannot fill the chip takes
+// fewer stages per round and more threads per polynomial instead: shorter dependent chains
+// per thread, more waves to hide the latencies of one polynomial.
+constexpr int rounds_for(int stages, int MAXS) { return (stages + MAXS - 1) / MAXS; }
 // stages of the next round when `stages` are left: as even a split as possible
-constexpr int round_stages(int stages) { return (stages + rounds_for(stages) - 1) / rounds_for(stages); }
-constexpr int threads_for(int logN)
+constexpr int round_stages(int stages, int MAXS)
 {
-    const int t = (1 << logN) / 16;
+    return (stages + rounds_for(stages, MAXS) - 1) / rounds_for(stages, MAXS);
+}
+constexpr int threads_for(int logN, int MAXS)
+{
+    const int t = (1 << logN) >> MAXS;
     return t < 64 ? 64 : (t > 1024 ? 1024 : t);
 }
+// LDS index of coefficient i: one word of padding after every 16, so that the strides of
+// 16 and 256 words of the later rounds spread over the banks
+__device__ __forceinline__ int pad(int i) { return i + (i >> 4); }
+constexpr int padded_size(int N) { return N + (N >> 4); }
 
 enum RoundKind { kForward, kInverse, kMiddle };
 
@@ -139,7 +150,7 @@ __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restri
         const int base = (i0 << (LOGN - P0)) + o;
         uint64_t x[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) x[r] = lds[base + (r << LT)];
+        for (int r = 0; r < R; ++r) x[r] = lds[pad(base + (r << LT))];
         if constexpr (KIND != kInverse) {
 #pragma unroll
             for (int st = 0; st < S; ++st) {
@@ -177,37 +188,37 @@ __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restri
             }
         }
 #pragma unroll
-        for (int r = 0; r < R; ++r) lds[base + (r << LT)] = x[r];
+        for (int r = 0; r < R; ++r) lds[pad(base + (r << LT))] = x[r];
     }
 }
 
 // forward rounds from stage P0 on, the pointwise product, and the inverse rounds back to P0
-template <int LOGN, int P0, int NT>
+template <int LOGN, int MAXS, int P0, int NT>
 __device__ __forceinline__ void multiply_by_secret(uint64_t *lds, const Twiddle *fwd,
                                                    const Twiddle *inv, const Twiddle *shat,
                                                    uint64_t q, int tid)
 {
-    constexpr int S = round_stages(LOGN - P0);
+    constexpr int S = round_stages(LOGN - P0, MAXS);
     if constexpr (P0 + S == LOGN) {
         ntt_round<LOGN, P0, S, kMiddle, NT>(lds, fwd, inv, shat, q, tid);
         __syncthreads();
     } else {
         ntt_round<LOGN, P0, S, kForward, NT>(lds, fwd, inv, shat, q, tid);
         __syncthreads();
-        multiply_by_secret<LOGN, P0 + S, NT>(lds, fwd, inv, shat, q, tid);
+        multiply_by_secret<LOGN, MAXS, P0 + S, NT>(lds, fwd, inv, shat, q, tid);
         ntt_round<LOGN, P0, S, kInverse, NT>(lds, fwd, inv, shat, q, tid);
         __syncthreads();
     }
 }
 
-template <int LOGN, int P0, int NT>
+template <int LOGN, int MAXS, int P0, int NT>
 __device__ __forceinline__ void forward_only(uint64_t *lds, const Twiddle *fwd, uint64_t q, int tid)
 {
     if constexpr (P0 < LOGN) {
-        constexpr int S = round_stages(LOGN - P0);
+        constexpr int S = round_stages(LOGN - P0, MAXS);
         ntt_round<LOGN, P0, S, kForward, NT>(lds, fwd, nullptr, nullptr, q, tid);
         __syncthreads();
-        forward_only<LOGN, P0 + S, NT>(lds, fwd, q, tid);
+        forward_only<LOGN, MAXS, P0 + S, NT>(lds, fwd, q, tid);
     }
 }
 
@@ -216,23 +227,23 @@ __device__ __forceinline__ void forward_only(uint64_t *lds, const Twiddle *fwd, 
 // one workgroup per limb
 // ---------------------------------------------------------------------------
 template <int LOGN>
-__global__ __launch_bounds__(threads_for(LOGN)) void rlwe_secret_kernel(
+__global__ __launch_bounds__(threads_for(LOGN, 4)) void rlwe_secret_kernel(
     RlweArgs a, const int8_t *__restrict__ s, Twiddle *__restrict__ tables)
 {
-    constexpr int N = 1 << LOGN, NT = threads_for(LOGN);
-    __shared__ uint64_t lds[N];
+    constexpr int N = 1 << LOGN, NT = threads_for(LOGN, 4);
+    __shared__ uint64_t lds[padded_size(N)];
     const int tid = threadIdx.x, l = blockIdx.x;
     const RlweLimb &P = a.limb[l];
     const uint64_t q = P.red.q;
     Twiddle *const t = tables + (size_t)l * limb_table_entries(N);
     for (int c = tid; c < N; c += NT) {
         const int v = s[c];
-        lds[c] = v < 0 ? q - (uint64_t)(-v) : (uint64_t)v;
+        lds[pad(c)] = v < 0 ? q - (uint64_t)(-v) : (uint64_t)v;
     }
     __syncthreads();
-    forward_only<LOGN, 0, NT>(lds, t, q, tid);
+    forward_only<LOGN, 4, 0, NT>(lds, t, q, tid);
     for (int c = tid; c < N; c += NT) {
-        uint64_t v = lds[c];                    // [0, 4q)
+        uint64_t v = lds[pad(c)];               // [0, 4q)
         v = v >= 2 * q ? v - 2 * q : v;
         v = v >= q ? v - q : v;
         v = mulmod(v, P.n_inv, P.red);
@@ -257,11 +268,11 @@ struct PolyArgs {
     RlweArgs limbs;
 };
 
-template <int LOGN, bool ENCRYPT>
-__global__ __launch_bounds__(threads_for(LOGN)) void rlwe_poly_kernel(PolyArgs a)
+template <int LOGN, int MAXS, bool ENCRYPT>
+__global__ __launch_bounds__(threads_for(LOGN, MAXS)) void rlwe_poly_kernel(PolyArgs a)
 {
-    constexpr int N = 1 << LOGN, NT = threads_for(LOGN);
-    __shared__ uint64_t lds[N];
+    constexpr int N = 1 << LOGN, NT = threads_for(LOGN, MAXS);
+    __shared__ uint64_t lds[padded_size(N)];
     const int tid = threadIdx.x;
     const uint32_t row = blockIdx.x / (uint32_t)a.L, l = blockIdx.x % (uint32_t)a.L;
     const RlweLimb &P = a.limbs.limb[l];
@@ -271,14 +282,14 @@ __global__ __launch_bounds__(threads_for(LOGN)) void rlwe_poly_kernel(PolyArgs a
     const uint64_t *const mul_in =
         ENCRYPT ? a.src + ((size_t)row * a.L + l) * N
                 : a.src + (((size_t)row * 2 + 1) * a.L + l) * N;
-    for (int c = tid; c < N; c += NT) lds[c] = mul_in[c];
+    for (int c = tid; c < N; c += NT) lds[pad(c)] = mul_in[c];
     __syncthreads();
-    multiply_by_secret<LOGN, 0, NT>(lds, t, t + N, t + 2 * N, q, tid);
+    multiply_by_secret<LOGN, MAXS, 0, NT>(lds, t, t + N, t + 2 * N, q, tid);
     if constexpr (!ENCRYPT) {
         const uint64_t *const c0 = a.src + (((size_t)row * 2 + 0) * a.L + l) * N;
         uint64_t *const phi = a.dst + ((size_t)row * a.L + l) * N;
         for (int c = tid; c < N; c += NT) {
-            uint64_t v = lds[c];                // [0, 2q)
+            uint64_t v = lds[pad(c)];           // [0, 2q)
             v = v >= q ? v - q : v;
             v += c0[c];
             phi[c] = v >= q ? v - q : v;
@@ -290,7 +301,7 @@ __global__ __launch_bounds__(threads_for(LOGN)) void rlwe_poly_kernel(PolyArgs a
         const uint64_t *const Wrow = a.W + (size_t)i * a.n;
         const int8_t *const e = a.e + (size_t)row * N;
         for (int c = tid; c < N; c += NT) {
-            uint64_t as = lds[c];               // [0, 2q)
+            uint64_t as = lds[pad(c)];          // [0, 2q)
             as = as >= q ? as - q : as;
             // Eq. (2) with chunking: coefficient c of chunk ch is column ch N + c, zero past n
             const uint32_t col = ch * (uint32_t)N + (uint32_t)c;
@@ -477,17 +488,36 @@ static hipError_t launch_secret(const RlweArgs &a, int logN, int L, const int8_t
                                 Twiddle *tables, hipStream_t stream)
 {
     NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL(rlwe_secret_kernel<LOGN>, dim3((unsigned)L),
-                                                  dim3(threads_for(LOGN)), 0, stream, a, s, tables));
+                                                  dim3(threads_for(LOGN, 4)), 0, stream, a, s, tables));
     return hipGetLastError();
 }
 
+template <bool ENCRYPT, int MAXS>
+static hipError_t launch_poly_with(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
+{
+    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL((rlwe_poly_kernel<LOGN, MAXS, ENCRYPT>),
+                                                  dim3((unsigned)polys),
+                                                  dim3(threads_for(LOGN, MAXS)), 0, stream, a));
+    return hipGetLastError();
+}
+
+// Stages per round by ring degree and batch size (one workgroup per polynomial, 256 compute
+// units).  A batch that fills the chip several times runs 256 threads per polynomial where
+// the ring allows it (several workgroups per compute unit hide each other's latencies); a
+// smaller batch runs up to 1024 threads per polynomial, because then one workgroup has the
+// compute unit to itself and its own waves are all there is to overlap.
 template <bool ENCRYPT>
 static hipError_t launch_poly(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
 {
-    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL((rlwe_poly_kernel<LOGN, ENCRYPT>),
-                                                  dim3((unsigned)polys), dim3(threads_for(LOGN)),
-                                                  0, stream, a));
-    return hipGetLastError();
+#ifdef NIMBUS_RLWE_FORCE_MAXS
+    return launch_poly_with<ENCRYPT, NIMBUS_RLWE_FORCE_MAXS>(a, logN, polys, stream);
+#else
+    int maxs = polys >= 1024 ? logN - 8 : logN - 10;
+    maxs = maxs < 2 ? 2 : (maxs > 4 ? 4 : maxs);
+    if (maxs == 4) return launch_poly_with<ENCRYPT, 4>(a, logN, polys, stream);
+    if (maxs == 3) return launch_poly_with<ENCRYPT, 3>(a, logN, polys, stream);
+    return launch_poly_with<ENCRYPT, 2>(a, logN, polys, stream);
+#endif
 }
 
 }  // namespace nimbus
