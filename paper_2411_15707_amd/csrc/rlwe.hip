@@ -282,7 +282,17 @@ __global__ __launch_bounds__(threads_for(LOGN, MAXS)) void rlwe_poly_kernel(Poly
     const uint64_t *const mul_in =
         ENCRYPT ? a.src + ((size_t)row * a.L + l) * N
                 : a.src + (((size_t)row * 2 + 1) * a.L + l) * N;
-    for (int c = tid; c < N; c += NT) lds[pad(c)] = mul_in[c];
+    if constexpr (ENCRYPT) {
+        // c1 = a, copied while a is on its way into the LDS (one read of a in all)
+        uint64_t *const c1 = a.dst + (((size_t)row * 2 + 1) * a.L + l) * N;
+        for (int c = tid; c < N; c += NT) {
+            const uint64_t v = mul_in[c];
+            lds[pad(c)] = v;
+            c1[c] = v;
+        }
+    } else {
+        for (int c = tid; c < N; c += NT) lds[pad(c)] = mul_in[c];
+    }
     __syncthreads();
     multiply_by_secret<LOGN, MAXS, 0, NT>(lds, t, t + N, t + 2 * N, q, tid);
     if constexpr (!ENCRYPT) {
@@ -296,7 +306,6 @@ __global__ __launch_bounds__(threads_for(LOGN, MAXS)) void rlwe_poly_kernel(Poly
         }
     } else {
         uint64_t *const c0 = a.dst + (((size_t)row * 2 + 0) * a.L + l) * N;
-        uint64_t *const c1 = a.dst + (((size_t)row * 2 + 1) * a.L + l) * N;
         const uint32_t i = row / (uint32_t)a.Ch, ch = row % (uint32_t)a.Ch;
         const uint64_t *const Wrow = a.W + (size_t)i * a.n;
         const int8_t *const e = a.e + (size_t)row * N;
@@ -313,7 +322,6 @@ __global__ __launch_bounds__(threads_for(LOGN, MAXS)) void rlwe_poly_kernel(Poly
             v = v >= q ? v - q : v;
             v = v >= q ? v - q : v;
             c0[c] = v;
-            c1[c] = mul_in[c];
         }
     }
 }
