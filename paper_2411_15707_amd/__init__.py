@@ -23,6 +23,12 @@ from .binding import (  # noqa: F401
     CALIBRATION_SYMBOLS,
     nimbus_calib_mfma_i8,
     nimbus_calib_stream_read,
+    LOADER_SYMBOLS,
+    nimbus_loader_create,
+    nimbus_loader_destroy,
+    nimbus_loader_load,
+    nimbus_loader_acquire,
+    nimbus_loader_release,
     RLWE_SYMBOLS,
     nimbus_rlwe_tables_bytes,
     nimbus_rlwe_setup,

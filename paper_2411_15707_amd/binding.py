@@ -31,6 +31,14 @@ EXPORTED_SYMBOLS = (
 
 CALIBRATION_SYMBOLS = ("nimbus_calib_mfma_i8", "nimbus_calib_stream_read")
 
+LOADER_SYMBOLS = (
+    "nimbus_loader_create",
+    "nimbus_loader_destroy",
+    "nimbus_loader_load",
+    "nimbus_loader_acquire",
+    "nimbus_loader_release",
+)
+
 RLWE_SYMBOLS = (
     "nimbus_rlwe_tables_bytes",
     "nimbus_rlwe_setup",
@@ -97,6 +105,16 @@ def load_library():
     lib.nimbus_rlwe_decrypt.argtypes = [vp, ci, ci, ci, vp, ci, vp, vp, vp, vp]
     lib.nimbus_rlwe_encrypt.restype = ci
     lib.nimbus_rlwe_encrypt.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.nimbus_loader_create.restype = ci
+    lib.nimbus_loader_create.argtypes = [ci, ctypes.POINTER(vp)]
+    lib.nimbus_loader_destroy.restype = ci
+    lib.nimbus_loader_destroy.argtypes = [vp]
+    lib.nimbus_loader_load.restype = ci
+    lib.nimbus_loader_load.argtypes = [vp, ci, vp, vp, sz, vp]
+    lib.nimbus_loader_acquire.restype = ci
+    lib.nimbus_loader_acquire.argtypes = [vp, ci, vp]
+    lib.nimbus_loader_release.restype = ci
+    lib.nimbus_loader_release.argtypes = [vp, ci, vp]
     lib.nimbus_cop_strerror.restype = ctypes.c_char_p
     lib.nimbus_cop_strerror.argtypes = [ci]
     lib.nimbus_cop_version.restype = ci
@@ -332,3 +350,49 @@ def nimbus_rlwe_encrypt(W, k, n, t_bits, N, L, moduli, tables, a, e, ctW, stream
                                  _dev_ptr(ctW, "ctW"), _stream(stream))
     if rc != 0:
         raise NimbusCopError(rc, "nimbus_rlwe_encrypt")
+
+
+# ---------------------------------------------------------------------------
+# asynchronous weight loading (pinned host memory -> device slot on a copy stream)
+# ---------------------------------------------------------------------------
+def nimbus_loader_create(slots: int):
+    """returns the opaque loader handle"""
+    handle = ctypes.c_void_p()
+    rc = load_library().nimbus_loader_create(slots, ctypes.byref(handle))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_loader_create")
+    return handle
+
+
+def nimbus_loader_destroy(loader):
+    rc = load_library().nimbus_loader_destroy(loader)
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_loader_destroy")
+
+
+def nimbus_loader_load(loader, slot, dst, src_host, copy_stream):
+    """dst: device tensor; src_host: pinned host tensor of the same byte size"""
+    if src_host.is_cuda or not src_host.is_pinned():
+        raise ValueError("src_host must be a pinned host tensor")
+    nbytes = src_host.numel() * src_host.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("dst is smaller than src_host")
+    if not src_host.is_contiguous():
+        raise ValueError("src_host must be contiguous")
+    rc = load_library().nimbus_loader_load(loader, slot, _dev_ptr(dst, "dst"),
+                                           ctypes.c_void_p(src_host.data_ptr()), nbytes,
+                                           _stream(copy_stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_loader_load")
+
+
+def nimbus_loader_acquire(loader, slot, compute_stream=None):
+    rc = load_library().nimbus_loader_acquire(loader, slot, _stream(compute_stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_loader_acquire")
+
+
+def nimbus_loader_release(loader, slot, compute_stream=None):
+    rc = load_library().nimbus_loader_release(loader, slot, _stream(compute_stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_loader_release")

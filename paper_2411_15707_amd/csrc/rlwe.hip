@@ -536,7 +536,7 @@ extern "C" {
 
 size_t nimbus_rlwe_tables_bytes(int N, int L)
 {
-    if (N < 32 || N > (1 << kRlweMaxLogN) || (N & (N - 1)) != 0) return 0;
+    if (N < (1 << kRlweMinLogN) || N > (1 << kRlweMaxLogN) || (N & (N - 1)) != 0) return 0;
     if (L < 1 || L > kMaxLimbs) return 0;
     return (size_t)L * limb_table_entries(N) * sizeof(Twiddle);
 }

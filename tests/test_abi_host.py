@@ -205,3 +205,21 @@ def test_rlwe_argument_checks_on_the_host():
                                    None) == -2
     assert lib.nimbus_rlwe_encrypt(0x6000, 4, 8, 20, N, L, mod, 0x1000, None, 0x8000, 0x9000,
                                    None) == -1
+
+
+def test_loader_header_binding_and_argument_checks():
+    text = open(os.path.join(ROOT, "include", "nimbus_loader.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(nimbus_loader_\w+)\s*\(", text)))
+    assert declared == sorted(nc.LOADER_SYMBOLS)
+    lib = _raw()
+    for name in declared:
+        assert hasattr(lib, name), name
+    handle = ctypes.c_void_p()
+    assert lib.nimbus_loader_create(0, ctypes.byref(handle)) == -1
+    assert lib.nimbus_loader_create(65, ctypes.byref(handle)) == -1
+    assert lib.nimbus_loader_create(2, None) == -1
+    assert lib.nimbus_loader_destroy(None) == 0
+    assert lib.nimbus_loader_load(None, 0, 0x1000, 0x2000, 16, None) == -1
+    assert lib.nimbus_loader_acquire(None, 0, None) == -1
+    assert lib.nimbus_loader_release(None, 0, None) == -1
