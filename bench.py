@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="BASELINE.json config number (1-5)")
     ap.add_argument("--buffers", type=int, default=0, help="distinct weight buffers (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefetch", action="store_true", help="skip the weight-loading stack")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path shards over coefficient columns "
@@ -259,6 +260,63 @@ def main():
         }
         del ct_big, phi_big, ct_enc, a_dev, e_dev
 
+    # ---- asynchronous weight loading (Section 3.2): a stack of layers whose prepared weights
+    # sit in pinned host memory, streamed through two device slots while the previous layer
+    # computes; against the same copies and kernels in one stream ----
+    prefetch = None
+    if not args.no_prefetch:
+        layers = 12
+        host_w = []
+        for i in range(layers):
+            hw = torch.empty(prep_bytes, dtype=torch.uint8, pin_memory=True)
+            hw.copy_(preps[i % R])
+            host_w.append(hw)
+        slots = [torch.empty(prep_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        copy_stream = torch.cuda.Stream()
+        ld = nc.nimbus_loader_create(2)
+
+        def stack_overlapped():
+            nc.nimbus_loader_load(ld, 0, slots[0], host_w[0], copy_stream)
+            for i in range(layers):
+                if i + 1 < layers:
+                    nc.nimbus_loader_load(ld, (i + 1) % 2, slots[(i + 1) % 2], host_w[i + 1],
+                                          copy_stream)
+                nc.nimbus_loader_acquire(ld, i % 2, stream)
+                nc.nimbus_cop_matmul_prepared(Xs[i % R], m, k, xb, slots[i % 2], n, N, L, moduli,
+                                              masks[i % R], outs[i % R], ws)
+                nc.nimbus_loader_release(ld, i % 2, stream)
+
+        def stack_serial():
+            for i in range(layers):
+                slots[0].copy_(host_w[i], non_blocking=True)
+                nc.nimbus_cop_matmul_prepared(Xs[i % R], m, k, xb, slots[0], n, N, L, moduli,
+                                              masks[i % R], outs[i % R], ws)
+
+        def copies_only():
+            for i in range(layers):
+                slots[i % 2].copy_(host_w[i], non_blocking=True)
+
+        def wall_ms(fn, reps=3):
+            fn()
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - c0) * 1e3 / reps
+        over_ms, serial_ms, copy_ms = wall_ms(stack_overlapped), wall_ms(stack_serial), wall_ms(copies_only)
+        nc.nimbus_loader_destroy(ld)
+        prefetch = {
+            "layers": layers,
+            "bytes_per_layer": prep_bytes,
+            "stack_ms_overlapped": round(over_ms, 3),
+            "stack_ms_one_stream": round(serial_ms, 3),
+            "stack_ms_copies_only": round(copy_ms, 3),
+            "stack_ms_compute_only": round(layers * ms_per_step, 3),
+            "host_to_device_gbps": round(layers * prep_bytes / (copy_ms * 1e-3) / 1e9, 1),
+        }
+        del host_w, slots
+
     # ---- calibration: what this chip sustains on the two resources that bound the kernel ----
     # (register-only int8 matrix-core loop with zero and with random operand bytes; streaming
     # read of one prepared weight buffer per launch, rotating over all of them)
@@ -351,6 +409,7 @@ def main():
         "roofline": roofline,
         "pack": pack,
         "server": server,
+        "prefetch": prefetch,
         "calibration": calibration,
         "cpu_baseline": cpu_baseline,
         "output_matches_oracle": verified,
