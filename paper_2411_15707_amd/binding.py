@@ -69,6 +69,10 @@ def load_library():
         raise FileNotFoundError(
             f"{path} is missing: build it with `python -m paper_2411_15707_amd.build` "
             "(there is no CPU fallback)")
+    # The library launches on PyTorch's streams and pointers, so both must use one and the
+    # same HIP runtime: PyTorch ships its own copy and loads it by path, and whichever copy
+    # is mapped first serves every later request for that soname.  Import torch first.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(path)
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.nimbus_cop_matmul.restype = ci

@@ -255,6 +255,6 @@ const char *nimbus_cop_strerror(int status)
     }
 }
 
-int nimbus_cop_version(void) { return 102; }
+int nimbus_cop_version(void) { return 110; }
 
 }  // extern "C"
