@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--buffers", type=int, default=0, help="distinct weight buffers (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefetch", action="store_true", help="skip the weight-loading stack")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the steps")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path shards over coefficient columns "
@@ -111,6 +112,31 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = cfg.mod_macs / (ms_per_step * 1e-3)
+
+    # ---- the same steps recorded once in a HIP graph (one step per weight buffer) and replayed:
+    # what a caller who records its layer loop pays per step ----
+    graph_ms_per_step = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for r in range(R):
+                step(r)
+        replays = max(1, args.steps // R)
+        for _ in range(max(1, args.warmup // R)):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms_per_step = (time.perf_counter() - g0) * 1e3 / (replays * R)
+        del graph
 
     # ---- dominant kernel alone (shares already staged), events on the launch stream ----
     staged = []
@@ -404,6 +430,7 @@ def main():
             "weight_buffers_rotated": R,
             "mod_macs_per_step": cfg.mod_macs,
         },
+        "ms_per_step_hip_graph": None if graph_ms_per_step is None else round(graph_ms_per_step, 5),
         "hbm_gbps_whole_step": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "canonical_layout_valu_kernel_ms": round(valu_ms, 4),
         "roofline": roofline,
