@@ -624,15 +624,18 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // g1 and g0 + mask each round once when they are converted; every partial sum is a
     // prefix of the signed-digit expansion and stays below 4 * 2^sh q in magnitude (the
     // digit magnitudes of an operand add up to at most twice its bound), so the handful of
-    // roundings, each relative to such a sum, leave the estimate off by well under 1/2.
-    // With 1/2 taken off before truncating it is floor(V/q) or one less, never more; the
-    // remainder is then formed modulo 2^64 and corrected once.
+    // roundings (eight at most, each below 2^-53 * 2^47 = 2^-6 of a quotient unit) leave the
+    // estimate off by well under 1/4.  With 1/2 taken off, rounded to a multiple of 1/4 and
+    // then down, it is floor(V/q) or one less, never more; the remainder is then formed
+    // modulo 2^64 and corrected once.
     const double two32 = 4294967296.0;
     const int64_t c0 = (int64_t)(cst_lo & 0xffffffffu), c1 = (int64_t)(cst_lo >> 32);
     // cst < 2^108 (q << sh < 2^107, OFFX * S < 2^94): its upper word converts exactly
     const double k2 = fma((double)(uint32_t)(cst_hi >> 32), two32, (double)(uint32_t)cst_hi) *
                       (two32 * two32);
-    const uint32_t q_lo = (uint32_t)q, q_hi = (uint32_t)(q >> 32);
+    // (wave-uniform: the limb follows from the wave's column tile)
+    const uint32_t q_lo = __builtin_amdgcn_readfirstlane((uint32_t)q);
+    const uint32_t q_hi = __builtin_amdgcn_readfirstlane((uint32_t)(q >> 32));
     // First everything that does not need the mask words (their loads are in flight), then,
     // per element, mask, quotient, remainder, store.
     // (the powers of 256 are kept opaque so that each term is one multiply-add instead of a
@@ -689,6 +692,11 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(mk[r]));
+    // wave-uniform constants of the quotient estimate, kept in vector registers
+    double qinv_v = qinv, magic_c = 1688849860263936.0 - 0.5;      // 3 * 2^49 - 1/2
+    // (the subtract-with-borrow reads vcc, which leaves no room for a second scalar operand)
+    uint32_t q_hi_v = q_hi;
+    asm volatile("" : "+v"(qinv_v), "+v"(magic_c), "+v"(q_hi_v));
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int64_t t0 = g0[r] + (int64_t)mk[r];          // |g0| < 2^56, mask < 2^62
@@ -696,15 +704,36 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         const uint32_t lo_hi = (uint32_t)(t0 >> 32) + g1_lo[r];
         // quotient estimate
         const double vd = v_hi[r] + fma((double)(int32_t)(t0 >> 32), two32, (double)lo_lo);
-        const double qd = fmax(fma(vd, qinv, -0.5), 0.0);
-        const uint32_t qh = (uint32_t)(qd * (1.0 / two32));
-        const uint32_t ql = (uint32_t)fma(-(double)qh, two32, qd);
-        // remainder modulo 2^64: lo - (qh 2^32 + ql) q, then one correction
+        // est = V/q - 1/2 rounded to a multiple of 1/4, then down to an integer: the constant
+        // 3 * 2^49 - 1/2 puts the sum into [2^50, 2^51), where doubles are 1/4 apart, so bits
+        // 2..51 of the sum hold est + 2^49 (est > -2^48).  With the estimate of V/q off by
+        // less than 1/4, est is floor(V/q) or one less (-1 is possible for V < q); only est
+        // modulo 2^64 is needed, and the signed field extract gives its upper word.
+        // (written out as one instruction: the compiler would rebuild the constant in a
+        // fresh register pair for every element to feed a two-operand multiply-add)
+        double magic;
+        asm("v_fma_f64 %0, %1, %2, %3" : "=v"(magic) : "v"(vd), "v"(qinv_v), "v"(magic_c));
+        const uint64_t mbits = __builtin_bit_cast(uint64_t, magic);
+        const uint32_t m_hi = (uint32_t)(mbits >> 32);
+        const uint32_t ql = (uint32_t)(mbits >> 2);
+        const uint32_t qh = (uint32_t)__builtin_amdgcn_sbfe((int32_t)m_hi, 2, 17);
+        // remainder modulo 2^64: lo - (qh 2^32 + ql) q, in [0, 2q); then one correction
         const uint64_t t = (((uint64_t)lo_hi << 32) | lo_lo) - (uint64_t)ql * q_lo;
+        const uint32_t t_lo = (uint32_t)t;
         const uint32_t t_hi = (uint32_t)(t >> 32) - (ql * q_hi + qh * q_lo);   // upper word only
-        uint64_t res = ((uint64_t)t_hi << 32) | (uint32_t)t;
-        const uint64_t res_q = res - q;
-        res = res < q ? res : res_q;
+        // res = t - q if that does not borrow, else t (subtract with borrow, then select on
+        // the borrow; a value written to vcc may be read two wait states later)
+        uint32_t r_lo, r_hi;
+        asm("v_subrev_co_u32_e32 %0, vcc, %4, %2\n\t"
+            "s_nop 1\n\t"
+            "v_subbrev_co_u32_e32 %1, vcc, %5, %3, vcc\n\t"
+            "s_nop 1\n\t"
+            "v_cndmask_b32_e32 %0, %0, %2, vcc\n\t"
+            "v_cndmask_b32_e32 %1, %1, %3, vcc"
+            : "=&v"(r_lo), "=&v"(r_hi)
+            : "v"(t_lo), "v"(t_hi), "s"(q_lo), "v"(q_hi_v)
+            : "vcc");
+        const uint64_t res = ((uint64_t)r_hi << 32) | r_lo;
         // (streaming store: the output is not read again by this kernel, and lines that do
         // not sit dirty in L2 need no write-back when the kernel ends)
         if (row0 + roff(r) < a.m) __builtin_nontemporal_store(res, &out0[(size_t)roff(r) * a.C]);
