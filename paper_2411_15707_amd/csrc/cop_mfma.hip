@@ -297,7 +297,10 @@ __device__ __forceinline__ void wait_vmem_n(int n)
         : "s96", "s97", "s98", "scc", "memory");
 }
 
-template <int DX, int DQ>
+// FULL: m is a multiple of 128, so every wave has its 32 rows: the code for waves without
+// rows and the row tests around the loads and stores of the epilogue (a compare, an exec
+// update and a branch each) are left out.
+template <int DX, int DQ, bool FULL>
 __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 {
     using P_ = Pipe<DX, DQ>;
@@ -334,7 +337,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     }
     const int RT = (a.m + kTile - 1) / kTile;       // row tiles that exist in the workspace
     const int rt = (int)rb * 4 + wr;                // this wave's row tile
-    const bool active = rt < RT;                    // wave-uniform
+    const bool active = FULL || rt < RT;            // wave-uniform
     const int KB = a.KB;
 
     // ---- this wave's share of the loads of one stage (sources at k-block 0) ----
@@ -605,7 +608,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     uint64_t mk[16];                                // read once: streaming loads
 #pragma unroll
     for (int r = 0; r < 16; ++r)
-        mk[r] = (mask0 && row0 + roff(r) < a.m)
+        mk[r] = (a.mask && (FULL || row0 + roff(r) < a.m))
                     ? __builtin_nontemporal_load(&mask0[(size_t)roff(r) * a.C])
                     : 0;
     uint64_t cst_hi = a.cst_hi[limb], cst_lo = a.cst_lo[limb];
@@ -676,11 +679,11 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // the same lane, and every read comes before the first write).  2^32 prev < 2^32 q keeps
     // V below 2^47 q.  (A block of its own behind one wave-uniform branch: the narrow path
     // does not execute any of it.)
-    if (prev0) {
+    if (a.prev) {
         uint64_t pv[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-            pv[r] = row0 + roff(r) < a.m ? __builtin_nontemporal_load(&prev0[(size_t)roff(r) * a.C]) : 0;
+            pv[r] = (FULL || row0 + roff(r) < a.m) ? __builtin_nontemporal_load(&prev0[(size_t)roff(r) * a.C]) : 0;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             g1_lo[r] += (uint32_t)pv[r];
@@ -736,7 +739,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         const uint64_t res = ((uint64_t)r_hi << 32) | r_lo;
         // (streaming store: the output is not read again by this kernel, and lines that do
         // not sit dirty in L2 need no write-back when the kernel ends)
-        if (row0 + roff(r) < a.m) __builtin_nontemporal_store(res, &out0[(size_t)roff(r) * a.C]);
+        if (FULL || row0 + roff(r) < a.m) __builtin_nontemporal_store(res, &out0[(size_t)roff(r) * a.C]);
     }
 }
 
@@ -863,7 +866,11 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
         a.cst_hi[l] = (uint64_t)(c >> 64);
         a.cst_lo[l] = (uint64_t)c;
     }
-    hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ>), dim3((CT / 2) * (uint32_t)a.RB), dim3(512), 0, stream, a);
+    const dim3 grid((CT / 2) * (uint32_t)a.RB);
+    if (p.m % 128 == 0)
+        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, true>), grid, dim3(512), 0, stream, a);
+    else
+        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, false>), grid, dim3(512), 0, stream, a);
     return hipGetLastError();
 }
 
