@@ -155,6 +155,8 @@ struct MfmaArgs {
     int m, KB, RB, N, L;
     uint32_t C, CT;
     uint32_t kb_magic;        // floor(2^32 / KB): x / KB = umulhi(x, kb_magic) or one more
+    uint32_t log_n;           // N = 2^log_n
+    uint32_t l_magic;         // ceil(2^32 / L) for L >= 2: x / L = umulhi(x, l_magic) for x < 2^31
     uint32_t offx;            // OFFX
     uint64_t q[kMaxLimbs];
     double qinv[kMaxLimbs];   // 1 / q_l, rounded
@@ -382,6 +384,16 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         }
     }
     n_loads = __builtin_amdgcn_readfirstlane(n_loads);
+    // The limb of this wave's 32 columns (they lie in one (polynomial, limb) block of N >= 32
+    // columns), worked out here with a shift and a multiply-high: after the loop it would sit
+    // on the path to the first loads of the epilogue.
+    uint32_t limb;
+    {
+        const uint32_t blk = ((ct2 * 2u + (uint32_t)wc) * kTile) >> a.log_n;
+        limb = a.L == 1 ? 0u : blk - (uint32_t)a.L * __umulhi(blk, a.l_magic);
+        limb = __builtin_amdgcn_readfirstlane(limb);
+        asm volatile("" : "+s"(limb));
+    }
     // Stage s of this workgroup is k-block (s + k_start) mod KB: the sum over k does not
     // care about the order, and workgroups that walk their (equally spaced) ciphertext
     // regions in lockstep would otherwise ask the same memory channels for data at the
@@ -591,8 +603,6 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 
     // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
     const uint32_t col = (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
-    // the wave's 32 columns lie in one (polynomial, limb) block of N >= 32 columns
-    const uint32_t limb = ((ct2 * 2u + (uint32_t)wc) * kTile / (uint32_t)a.N) % (uint32_t)a.L;
     const uint64_t q = a.q[limb];
     const double qinv = a.qinv[limb];
     const int row0 = rt * kTile + 4 * (lane >> 5);
@@ -606,11 +616,16 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     const uint64_t *const prev0 = a.prev ? a.prev + lane_elem : nullptr;
     uint64_t *const out0 = a.out + lane_elem;
     uint64_t mk[16];                                // read once: streaming loads
+    if (a.mask) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-        mk[r] = (a.mask && (FULL || row0 + roff(r) < a.m))
-                    ? __builtin_nontemporal_load(&mask0[(size_t)roff(r) * a.C])
-                    : 0;
+        for (int r = 0; r < 16; ++r)
+            mk[r] = (FULL || row0 + roff(r) < a.m)
+                        ? __builtin_nontemporal_load(&mask0[(size_t)roff(r) * a.C])
+                        : 0;
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mk[r] = 0;
+    }
     uint64_t cst_hi = a.cst_hi[limb], cst_lo = a.cst_lo[limb];
     {
         const uint64_t S = colsum_S;
@@ -857,6 +872,9 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
     a.offx = share_offset(p.x_bits, DX);
     a.kb_magic = (uint32_t)((1ull << 32) / (uint64_t)KB);   // KB = 1: 2^32 does not fit, see below
     if (KB == 1) a.kb_magic = 0xffffffffu;
+    a.log_n = 0;
+    while ((1 << a.log_n) < p.N) ++a.log_n;
+    a.l_magic = p.L >= 2 ? (uint32_t)(((1ull << 32) + (uint64_t)p.L - 1) / (uint64_t)p.L) : 0u;
     const int sh = bias_shift(p);
     for (int l = 0; l < p.L; ++l) {
         const uint64_t q = p.limbs.limb[l].q;
