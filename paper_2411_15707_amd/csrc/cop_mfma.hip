@@ -306,6 +306,11 @@ template <int DX, int DQ, bool FULL>
 __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 {
     using P_ = Pipe<DX, DQ>;
+    // Every scalar argument the setup needs, asked for in one batch: left to the compiler the
+    // loads sit next to their first uses, and the setup waits for the constant cache once
+    // per group of them instead of once.
+    asm volatile("" ::"s"(a.xd), "s"(a.planes), "s"(a.colsum), "s"(a.m), "s"(a.KB), "s"(a.RB),
+                 "s"(a.L), "s"(a.CT), "s"(a.kb_magic), "s"(a.log_n), "s"(a.l_magic));
     constexpr int ND = P_::ND;
     constexpr bool PIPELINED = P_::PIPELINED;
     constexpr int AHEAD = P_::AHEAD, LEAD = P_::LEAD, RING = P_::RING;
@@ -437,21 +442,25 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     }
 
     // ---- up front: stages 0 .. LEAD-1 ----
-    for (int st = 0; st < LEAD && st < KB; ++st) {
-        static_for<0, P_::MAXU>([&](auto u_c) {
-            if (decltype(u_c)::value < n_loads) issue_one(u_c);
-        });
-        NIMBUS_NEXT_ISSUE();
-    }
-
-    // (cleared after the loads are on their way, not before)
+    // The accumulators are cleared between the stages: the memory pipeline takes the first
+    // loads of a launch slowly (nothing is translated or cached yet), and the moves fill
+    // the time the wave would spend waiting for it to accept the next one.
     v16i acc[ND];
 #pragma unroll
-    for (int d = 0; d < ND; ++d)
+    for (int st = 0; st < LEAD; ++st) {
+        if (st < KB) {
+            static_for<0, P_::MAXU>([&](auto u_c) {
+                if (decltype(u_c)::value < n_loads) issue_one(u_c);
+            });
+            NIMBUS_NEXT_ISSUE();
+        }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[d][r] = 0;
+        for (int d = st; d < ND; d += LEAD) {
 #pragma unroll
-    for (int d = 0; d < ND; ++d) tie_acc(acc[d]);
+            for (int r = 0; r < 16; ++r) acc[d][r] = 0;
+            tie_acc(acc[d]);
+        }
+    }
 
     // Operands come out of LDS through explicit ds_read_b128 instructions: reads the
     // compiler can see would each be made to wait for every direct-to-LDS load in flight.
