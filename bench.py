@@ -171,7 +171,7 @@ def main():
     i8_ops = 2.0 * DX * DQ * m * (-(-k // 32) * 32) * C
     workload_key = f"config{args.config}"
     roofline = {
-        "kernel": f"cop_mfma_kernel<{DX},{DQ}>",
+        "kernel": f"cop_mfma_kernel<{DX},{DQ},{'true' if m % 128 == 0 else 'false'}>",
         "bound": "hbm",
         "achieved": round(achieved_gbps, 1),
         "peak": HBM_PEAK_GBPS,
