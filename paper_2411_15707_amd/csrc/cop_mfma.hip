@@ -230,19 +230,23 @@ __device__ __forceinline__ void dma_tile_stream(const void *src_lane, void *dst_
 // and 2*DQ operand tiles of ciphertext planes (14 KB for DQ = 7), each in an LDS ring of
 // its own.  Both are filled by direct-to-LDS loads of whole tiles (64 lanes x 16 B; the
 // texture address unit spends the same time on narrower loads); nothing passes through
-// registers on the way in.  The tiles of a stage are dealt round-robin to the eight
-// waves.  A wave knows how many loads it issues per stage, so "stage s has landed" is a
-// wait on the number of its younger loads, then the barrier.
+// registers on the way in.  The X tiles of a stage are dealt to waves 0-3, the ciphertext
+// tiles to waves 4-7 (one wave of each kind per SIMD).  A wave knows how many loads it
+// issues per stage, so "stage s has landed" is a wait on the number of its younger loads,
+// then the barrier.
 //
 // Inside a wave the loop is software pipelined: the LDS reads of stage s+1 are issued
 // between the matrix-core instructions of stage s, into the other of two operand sets.
 //
-// What the loop is bound by, in this order (measured): the matrix cores (42
-// instructions per SIMD and k-block); the number of bytes a CU can have in flight to
-// HBM (about 16 KB: a load instruction that does not fit stalls its wave until earlier
-// loads return, so the ciphertext loads are spread over all waves and over the whole
-// iteration, where the other wave of the SIMD can fill the gap with its own matrix-core
-// instructions); instruction issue (a wave issues an instruction every four or five
+// What the loop is bound by (measured).  Its duration follows the operand values: the
+// chip lowers its clock under the combined matrix-core and memory load, and a k-block
+// costs the matrix-core time of its 42 instructions per SIMD at the rate a register-only
+// loop reaches on random bytes, plus a memory-side term; the two add up instead of
+// overlapping.  Within that, what the schedule has to respect: the number of bytes a CU
+// can have in flight to HBM (about 16 KB: a load instruction that does not fit stalls its
+// wave until earlier loads return, so the ciphertext loads are spread over the iteration,
+// where the other wave of the SIMD can fill the gap with its own matrix-core
+// instructions), and instruction issue (a wave issues an instruction every four or five
 // cycles at best and all eight waves run in lockstep between barriers, so every scalar
 // instruction costs: one stage issued per iteration from the first iteration on,
 // ring offsets carried and wrapped instead of recomputed, and the wait for "at most n
