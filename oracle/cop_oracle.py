@@ -46,6 +46,13 @@ def _load():
                                    _u64p, _i64p]
     lib.oracle_share_mask.restype = ctypes.c_int
     lib.oracle_share_mask.argtypes = [_u64p, ctypes.c_int, ctypes.c_int, _u64p, ctypes.c_int, _u64p]
+    lib.oracle_encrypt_rns.restype = ctypes.c_int
+    lib.oracle_encrypt_rns.argtypes = lib.oracle_encrypt.argtypes
+    lib.oracle_decrypt_rns.restype = ctypes.c_int
+    lib.oracle_decrypt_rns.argtypes = [_u64p, _i8p, ctypes.c_int, ctypes.c_int, _u64p, ctypes.c_int,
+                                       _u64p]
+    lib.oracle_share_mask_rns.restype = ctypes.c_int
+    lib.oracle_share_mask_rns.argtypes = lib.oracle_share_mask.argtypes
     lib.oracle_rshift.restype = None
     lib.oracle_rshift.argtypes = [_u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _u64p, _u64p]
     lib.oracle_pack_ref.restype = ctypes.c_int
@@ -180,6 +187,56 @@ def share_mask(R_row, moduli, t_bits):
     rc = lib.oracle_share_mask(_p(R_row), N, L, _p(mod), int(t_bits), _p(mask))
     if rc != 0:
         raise ValueError("oracle_share_mask: L > 2 is not supported")
+    return mask
+
+
+def encrypt_rns(w_hat, s, a, e, moduli, t_bits, threads=None):
+    """encrypt() for one to four limbs (256-bit integers instead of 128-bit ones)"""
+    lib = _load()
+    w_hat = _u64(w_hat)
+    rows, N = w_hat.shape
+    L = len(moduli)
+    s = np.ascontiguousarray(s, dtype=np.int8)
+    a = _u64(a, (rows, L, N))
+    e = np.ascontiguousarray(e, dtype=np.int8)
+    assert s.shape == (N,) and e.shape == (rows, N)
+    mod = np.asarray(moduli, dtype=np.uint64)
+    ct = np.empty((rows, 2, L, N), dtype=np.uint64)
+    if threads is None:
+        threads = max_threads()
+    rc = lib.oracle_encrypt_rns(_p(w_hat), rows, _p(s, _i8p), _p(a), _p(e, _i8p), N, L, _p(mod),
+                                int(t_bits), _p(ct), int(threads))
+    if rc != 0:
+        raise ValueError("oracle_encrypt_rns: L out of range")
+    return ct
+
+
+def decrypt_rns(ct, s, moduli, t_bits):
+    """decrypt() for one to four limbs: ct [2][L][N] -> m_hat [N]"""
+    lib = _load()
+    ct = _u64(ct)
+    _, L, N = ct.shape
+    assert ct.shape[0] == 2 and L == len(moduli)
+    s = np.ascontiguousarray(s, dtype=np.int8)
+    mod = np.asarray(moduli, dtype=np.uint64)
+    m_hat = np.empty(N, dtype=np.uint64)
+    rc = lib.oracle_decrypt_rns(_p(ct), _p(s, _i8p), N, L, _p(mod), int(t_bits), _p(m_hat))
+    if rc != 0:
+        raise ValueError("oracle_decrypt_rns: L out of range")
+    return m_hat
+
+
+def share_mask_rns(R_row, moduli, t_bits):
+    """share_mask() for one to four limbs"""
+    lib = _load()
+    R_row = _u64(R_row)
+    N = R_row.shape[0]
+    L = len(moduli)
+    mod = np.asarray(moduli, dtype=np.uint64)
+    mask = np.empty((2, L, N), dtype=np.uint64)
+    rc = lib.oracle_share_mask_rns(_p(R_row), N, L, _p(mod), int(t_bits), _p(mask))
+    if rc != 0:
+        raise ValueError("oracle_share_mask_rns: L out of range")
     return mask
 
 

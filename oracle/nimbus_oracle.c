@@ -403,3 +403,211 @@ int oracle_pack_ref(const uint64_t *rows, int m, int n, int N, int L, const uint
     free(tmp);
     return T;
 }
+
+/* ========================================================================
+ * The same scheme for up to four limbs (Q up to 2^248): 256-bit integers as
+ * four 64-bit words, least significant first, with the schoolbook routines
+ * below (add, subtract, compare, times a word, shift right, remainder by a
+ * word, and bit-by-bit long division).  Slow and plain on purpose.
+ * Pins (tests/test_oracle_rns.py): agreement with oracle_encrypt /
+ * oracle_decrypt for one and two limbs, Python integers for three and four
+ * limbs (reconstructed value congruent to every limb phase and below Q,
+ * rounding division at and next to its boundaries), enc/dec round trip.
+ * ====================================================================== */
+typedef struct { uint64_t w[4]; } u256;
+
+static u256 u256_from_u64(uint64_t v)
+{
+    u256 r = {{v, 0, 0, 0}};
+    return r;
+}
+
+static int u256_cmp(const u256 *a, const u256 *b)
+{
+    for (int i = 3; i >= 0; --i) {
+        if (a->w[i] < b->w[i]) return -1;
+        if (a->w[i] > b->w[i]) return 1;
+    }
+    return 0;
+}
+
+static u256 u256_add(const u256 *a, const u256 *b)
+{
+    u256 r;
+    u128 carry = 0;
+    for (int i = 0; i < 4; ++i) {
+        const u128 s = (u128)a->w[i] + b->w[i] + carry;
+        r.w[i] = (uint64_t)s;
+        carry = s >> 64;
+    }
+    return r;
+}
+
+static u256 u256_sub(const u256 *a, const u256 *b)      /* a >= b */
+{
+    u256 r;
+    uint64_t borrow = 0;
+    for (int i = 0; i < 4; ++i) {
+        const u128 d = (u128)a->w[i] - b->w[i] - borrow;
+        r.w[i] = (uint64_t)d;
+        borrow = (uint64_t)(d >> 64) & 1u;
+    }
+    return r;
+}
+
+static u256 u256_mul_u64(const u256 *a, uint64_t m)     /* product must fit 256 bits */
+{
+    u256 r;
+    u128 carry = 0;
+    for (int i = 0; i < 4; ++i) {
+        const u128 p = (u128)a->w[i] * m + carry;
+        r.w[i] = (uint64_t)p;
+        carry = p >> 64;
+    }
+    return r;
+}
+
+static u256 u256_shr(const u256 *a, int s)              /* 0 <= s < 256 */
+{
+    u256 r = {{0, 0, 0, 0}};
+    const int ws = s / 64, bs = s % 64;
+    for (int i = 0; i + ws < 4; ++i) {
+        uint64_t v = a->w[i + ws] >> bs;
+        if (bs && i + ws + 1 < 4) v |= a->w[i + ws + 1] << (64 - bs);
+        r.w[i] = v;
+    }
+    return r;
+}
+
+static uint64_t u256_mod_u64(const u256 *a, uint64_t m)
+{
+    u128 rem = 0;
+    for (int i = 3; i >= 0; --i) rem = ((rem << 64) | a->w[i]) % m;
+    return (uint64_t)rem;
+}
+
+static int u256_bit(const u256 *a, int i) { return (int)((a->w[i / 64] >> (i % 64)) & 1u); }
+
+/* quotient of a by d (d > 0), bit by bit from the top */
+static u256 u256_div(const u256 *a, const u256 *d)
+{
+    u256 quo = {{0, 0, 0, 0}}, rem = {{0, 0, 0, 0}};
+    for (int i = 255; i >= 0; --i) {
+        /* rem = 2 rem + bit i of a   (rem < d <= 2^255 would be needed for the shift not
+         * to overflow; Q < 2^248 keeps every value here far below that) */
+        const u256 twice = u256_add(&rem, &rem);
+        rem = twice;
+        rem.w[0] |= (uint64_t)u256_bit(a, i);
+        if (u256_cmp(&rem, d) >= 0) {
+            rem = u256_sub(&rem, d);
+            quo.w[i / 64] |= (uint64_t)1 << (i % 64);
+        }
+    }
+    return quo;
+}
+
+static u256 rns_Q(const uint64_t *moduli, int L)
+{
+    u256 Q = u256_from_u64(1);
+    for (int l = 0; l < L; ++l) Q = u256_mul_u64(&Q, moduli[l]);
+    return Q;
+}
+
+/* ------------------------------------------------------------------------
+ * Encryption as oracle_encrypt, for 1 <= L <= 4:
+ *     c1 = a,   c0 = -a s + e + Delta * w_hat  (mod Q),   Delta = floor(Q / 2^t_bits),
+ * limb by limb with (Delta mod q_l).  Shapes as oracle_encrypt.  Returns 0, or -1 for L
+ * out of range.
+ * ---------------------------------------------------------------------- */
+int oracle_encrypt_rns(const uint64_t *w_hat, int rows, const int8_t *s,
+                       const uint64_t *a, const int8_t *e,
+                       int N, int L, const uint64_t *moduli, int t_bits,
+                       uint64_t *ct, int threads)
+{
+    if (L < 1 || L > 4) return -1;
+    const u256 Q = rns_Q(moduli, L);
+    const u256 Delta = u256_shr(&Q, t_bits);
+    if (threads < 1) threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+    for (int r = 0; r < rows; ++r) {
+        uint64_t *as = (uint64_t *)malloc(sizeof(uint64_t) * N);
+        for (int l = 0; l < L; ++l) {
+            const uint64_t q = moduli[l];
+            const uint64_t dl = u256_mod_u64(&Delta, q);
+            const uint64_t *al = a + ((size_t)r * L + l) * N;
+            uint64_t *c0 = ct + (((size_t)r * 2 + 0) * L + l) * N;
+            uint64_t *c1 = ct + (((size_t)r * 2 + 1) * L + l) * N;
+            oracle_negacyclic_mul_small(al, s, N, q, as);
+            for (int c = 0; c < N; ++c) {
+                i128 v = (i128)((u128)dl * w_hat[(size_t)r * N + c] % q);
+                v += e[(size_t)r * N + c];
+                v -= as[c];
+                v %= (i128)q;
+                if (v < 0) v += q;
+                c0[c] = (uint64_t)v;
+                c1[c] = al[c];
+            }
+        }
+        free(as);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Decryption + decoding of one ciphertext [2][L][N] for 1 <= L <= 4:
+ *   phase per limb, then the unique phi in [0, Q) with phi = phi_l (mod q_l) for every l
+ *   (Chinese remainder theorem, built limb by limb: if v is right modulo q_0 .. q_{j-1},
+ *   whose product is M, then v + M * ((phi_j - v) * M^-1 mod q_j) is right modulo q_j as
+ *   well), then  m_hat[c] = floor((phi[c] + floor(Delta/2)) / Delta) mod 2^t_bits.
+ * Returns 0, or -1 for L out of range.
+ * ---------------------------------------------------------------------- */
+int oracle_decrypt_rns(const uint64_t *ct, const int8_t *s, int N, int L,
+                       const uint64_t *moduli, int t_bits, uint64_t *m_hat)
+{
+    if (L < 1 || L > 4) return -1;
+    const u256 Q = rns_Q(moduli, L);
+    const u256 Delta = u256_shr(&Q, t_bits);
+    const u256 half = u256_shr(&Delta, 1);
+    const uint64_t tmask = t_bits >= 64 ? ~(uint64_t)0 : (((uint64_t)1 << t_bits) - 1);
+    uint64_t *phi = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)L * N);
+    oracle_phase(ct, s, N, L, moduli, phi);
+    for (int c = 0; c < N; ++c) {
+        u256 v = u256_from_u64(phi[c]);
+        u256 M = u256_from_u64(moduli[0]);
+        for (int j = 1; j < L; ++j) {
+            const uint64_t qj = moduli[j];
+            const uint64_t vj = u256_mod_u64(&v, qj);
+            const uint64_t Mj = u256_mod_u64(&M, qj);
+            const uint64_t diff = (uint64_t)(((u128)phi[(size_t)j * N + c] + qj - vj) % qj);
+            const uint64_t h = (uint64_t)((u128)diff * inv_mod(Mj, qj) % qj);
+            const u256 step = u256_mul_u64(&M, h);
+            v = u256_add(&v, &step);
+            M = u256_mul_u64(&M, qj);
+        }
+        const u256 num = u256_add(&v, &half);
+        const u256 mm = u256_div(&num, &Delta);
+        m_hat[c] = mm.w[0] & tmask;
+    }
+    free(phi);
+    return 0;
+}
+
+/* Mask polynomial pair of oracle_share_mask for 1 <= L <= 4:
+ * c0 part = (Q - Delta * R[c]) mod Q per limb, c1 part = 0. */
+int oracle_share_mask_rns(const uint64_t *R, int N, int L, const uint64_t *moduli,
+                          int t_bits, uint64_t *mask)
+{
+    if (L < 1 || L > 4) return -1;
+    const u256 Q = rns_Q(moduli, L);
+    const u256 Delta = u256_shr(&Q, t_bits);
+    for (int c = 0; c < N; ++c) {
+        const u256 dr = u256_mul_u64(&Delta, R[c]);          /* <= Delta * (t - 1) < Q */
+        u256 v = u256_sub(&Q, &dr);
+        if (u256_cmp(&v, &Q) >= 0) v = u256_sub(&v, &Q);     /* R[c] = 0 */
+        for (int l = 0; l < L; ++l) {
+            mask[((size_t)0 * L + l) * N + c] = u256_mod_u64(&v, moduli[l]);
+            mask[((size_t)1 * L + l) * N + c] = 0;
+        }
+    }
+    return 0;
+}
