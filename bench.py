@@ -231,7 +231,7 @@ def main():
     # rows and decryption of the m returned rows, plus the rate of the transform kernel on a
     # batch large enough to fill the chip several times ----
     server = None
-    if L <= 2 and N <= 16384:
+    if N <= 16384:
         logN = N.bit_length() - 1
         seed = ci.config_seed(args.config, call=100)
         s_dev = torch.from_numpy(ci.gen_secret(seed, N)).cuda()

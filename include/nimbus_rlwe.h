@@ -34,8 +34,8 @@
  *     2N-th root of unity exists; a modulus without one is NIMBUS_COP_ERR_INVALID_ARG);
  *   - N is a power of two, 32 <= N <= 16384 (one polynomial is transformed inside the
  *     local memory of one compute unit; N = 32768 is NIMBUS_COP_ERR_UNSUPPORTED);
- *   - 1 <= L <= 4; decoding and encryption need Q < 2^128 and are limited to L <= 2
- *     (NIMBUS_COP_ERR_UNSUPPORTED otherwise); 1 <= t_bits <= 32 and 2^t_bits < q_l;
+ *   - 1 <= L <= 4 distinct primes (Q < 2^248); 1 <= t_bits <= 32 and 2^t_bits < q_l for
+ *     decoding and encryption;
  *   - nothing is allocated, freed or synchronised; all work is enqueued on `stream`
  *     (a hipStream_t, NULL = the default stream); on any error nothing is enqueued;
  *   - residues handed in must be canonical (in [0, q_l)); residues written are canonical;
@@ -81,8 +81,7 @@ int nimbus_rlwe_phase(const uint64_t *ct, int T, int N, int L, const uint64_t *m
  * Chinese remainder theorem into phi in [0, Q), then
  *   m_hat[r][c] = floor((phi[r][c] + floor(Delta/2)) / Delta) mod 2^t_bits,  Delta = floor(Q / 2^t_bits).
  *   phi    [T][L][N] canonical residues
- *   m_hat  [T][N], written, values < 2^t_bits
- * L <= 2 (UNSUPPORTED above). */
+ *   m_hat  [T][N], written, values < 2^t_bits */
 int nimbus_rlwe_decode(const uint64_t *phi, int T, int N, int L, const uint64_t *moduli,
                        int t_bits, uint64_t *m_hat, void *stream);
 
@@ -103,7 +102,7 @@ int nimbus_rlwe_decrypt(const uint64_t *ct, int T, int N, int L, const uint64_t 
  *        ctW[i][ch][1] = a[i][ch],
  *        ctW[i][ch][0][l] = (Delta mod q_l) * w-hat_{i,ch} + e[i][ch] - a[i][ch][l] * s  (mod q_l)
  *        must not overlap the inputs
- * L <= 2 (UNSUPPORTED above).  k >= 1, n >= 1. */
+ * k >= 1, n >= 1. */
 int nimbus_rlwe_encrypt(const uint64_t *W, int k, int n, int t_bits, int N, int L,
                         const uint64_t *moduli, const void *tables, const uint64_t *a,
                         const int8_t *e, uint64_t *ctW, void *stream);

@@ -376,6 +376,113 @@ __global__ __launch_bounds__(256) void rlwe_decode_kernel(DecodeArgs a)
     a.m_hat[gid] = est & a.t_mask;
 }
 
+// The same for three and four limbs: Q < 2^248, so the reconstructed phase and Delta take
+// four 64-bit words (least significant first).  Mixed-radix form of the Chinese remainder
+// theorem: phi = a_0 + q_0 (a_1 + q_1 (a_2 + q_2 a_3)) with
+//   a_j = ( ... ((phi_j - a_0) q_0^-1 - a_1) q_1^-1 - ... - a_{j-1}) q_{j-1}^-1  mod q_j,
+// all of it 64-bit modular arithmetic; only the final Horner evaluation is wide.
+struct Wide {
+    uint64_t w[4];
+};
+
+__device__ __forceinline__ Wide wide_mul_add(const Wide &a, uint64_t m, uint64_t add)   // a m + add
+{
+    Wide r;
+    u128 carry = add;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const u128 p = (u128)a.w[i] * m + carry;
+        r.w[i] = (uint64_t)p;
+        carry = p >> 64;
+    }
+    return r;
+}
+
+__device__ __forceinline__ Wide wide_add(const Wide &a, const Wide &b)
+{
+    Wide r;
+    u128 carry = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const u128 t = (u128)a.w[i] + b.w[i] + carry;
+        r.w[i] = (uint64_t)t;
+        carry = t >> 64;
+    }
+    return r;
+}
+
+// a - b modulo 2^256 and whether it borrowed (a < b)
+__device__ __forceinline__ bool wide_sub(const Wide &a, const Wide &b, Wide &r)
+{
+    uint64_t borrow = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const u128 t = (u128)a.w[i] - b.w[i] - borrow;
+        r.w[i] = (uint64_t)t;
+        borrow = (uint64_t)(t >> 64) & 1u;
+    }
+    return borrow != 0;
+}
+
+struct DecodeWideArgs {
+    const uint64_t *phi;    // [T][L][N]
+    uint64_t *m_hat;        // [T][N]
+    int L, logN;            // L = 3 or 4
+    uint64_t total;         // T * N
+    Limb red[kMaxLimbs];
+    uint64_t inv[kMaxLimbs][kMaxLimbs];     // inv[i][j] = q_i^-1 mod q_j for i < j
+    Wide delta, half;       // Delta and floor(Delta / 2)
+    double delta_inv;       // 1 / Delta, rounded
+    uint64_t t_mask;
+};
+
+__global__ __launch_bounds__(256) void rlwe_decode_wide_kernel(DecodeWideArgs a)
+{
+    const uint64_t gid = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (gid >= a.total) return;
+    const uint64_t N = 1ull << a.logN;
+    const uint64_t row = gid >> a.logN, c = gid & (N - 1);
+    const uint64_t *const ph = a.phi + row * (uint64_t)a.L * N + c;
+    uint64_t digit[kMaxLimbs] = {0, 0, 0, 0};
+    digit[0] = ph[0];
+#pragma unroll
+    for (int j = 1; j < kMaxLimbs; ++j) {
+        if (j >= a.L) break;
+        const Limb &P = a.red[j];
+        uint64_t v = ph[(uint64_t)j * N];
+#pragma unroll
+        for (int i = 0; i < j; ++i) {
+            const uint64_t d = barrett128(0, digit[i], P);      // a_i mod q_j
+            v = v + P.q - d;
+            v = v >= P.q ? v - P.q : v;
+            v = mulmod(v, a.inv[i][j], P);
+        }
+        digit[j] = v;
+    }
+    Wide v = {{a.L == 4 ? digit[3] : 0, 0, 0, 0}};
+    if (a.L == 4) v = wide_mul_add(v, a.red[2].q, digit[2]);
+    else v.w[0] = digit[2];
+    v = wide_mul_add(v, a.red[1].q, digit[1]);
+    v = wide_mul_add(v, a.red[0].q, digit[0]);
+    const Wide num = wide_add(v, a.half);
+    // quotient <= 2^32 + 1: a double-precision estimate is within one of it
+    const double two64 = 18446744073709551616.0;
+    double nd = (double)num.w[3];
+    nd = fma(nd, two64, (double)num.w[2]);
+    nd = fma(nd, two64, (double)num.w[1]);
+    nd = fma(nd, two64, (double)num.w[0]);
+    uint64_t est = (uint64_t)(nd * a.delta_inv);
+    Wide prod = wide_mul_add(a.delta, est, 0);  // about num: no overflow
+    Wide rem;
+    if (wide_sub(num, prod, rem)) {             // one too many
+        est -= 1;
+        rem = wide_add(rem, a.delta);           // wraps back to num - (est) Delta
+    }
+    Wide over;
+    if (!wide_sub(rem, a.delta, over)) est += 1;    // one too few
+    a.m_hat[gid] = est & a.t_mask;
+}
+
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
@@ -465,15 +572,64 @@ static bool find_psi(uint64_t q, int N, uint64_t *psi)
     return false;
 }
 
-// Delta = floor(Q / 2^t_bits) for L <= 2
-static int scaling(int L, const uint64_t *moduli, int t_bits, u128 *Q, u128 *delta)
+// Q and Delta = floor(Q / 2^t_bits) as four 64-bit words, least significant first
+struct HostWide {
+    uint64_t w[4] = {0, 0, 0, 0};
+};
+
+static HostWide hw_times(const HostWide &a, uint64_t m)
+{
+    HostWide r;
+    u128 carry = 0;
+    for (int i = 0; i < 4; ++i) {
+        const u128 p = (u128)a.w[i] * m + carry;
+        r.w[i] = (uint64_t)p;
+        carry = p >> 64;
+    }
+    return r;
+}
+
+static HostWide hw_shift_right(const HostWide &a, int s)       // 0 < s < 64
+{
+    HostWide r;
+    for (int i = 0; i < 4; ++i) {
+        r.w[i] = a.w[i] >> s;
+        if (i + 1 < 4) r.w[i] |= a.w[i + 1] << (64 - s);
+    }
+    return r;
+}
+
+static uint64_t hw_mod(const HostWide &a, uint64_t m)
+{
+    u128 rem = 0;
+    for (int i = 3; i >= 0; --i) rem = ((rem << 64) | a.w[i]) % m;
+    return (uint64_t)rem;
+}
+
+static double hw_to_double(const HostWide &a)
+{
+    double d = 0.0;
+    for (int i = 3; i >= 0; --i) d = d * 18446744073709551616.0 + (double)a.w[i];
+    return d;
+}
+
+struct Scaling {
+    HostWide delta, half;
+    double delta_inv;
+};
+
+// checks shared by decoding and encryption; max_limbs: what the caller can handle
+static int scaling(int L, const uint64_t *moduli, int t_bits, Scaling *out)
 {
     if (t_bits < 1 || t_bits > 32) return NIMBUS_COP_ERR_INVALID_ARG;
     for (int l = 0; l < L; ++l)
         if (moduli[l] <= (1ull << t_bits)) return NIMBUS_COP_ERR_INVALID_ARG;
-    if (L > 2) return NIMBUS_COP_ERR_UNSUPPORTED;
-    *Q = L == 1 ? (u128)moduli[0] : (u128)moduli[0] * moduli[1];
-    *delta = *Q >> t_bits;
+    HostWide Q;
+    Q.w[0] = 1;
+    for (int l = 0; l < L; ++l) Q = hw_times(Q, moduli[l]);
+    out->delta = hw_shift_right(Q, t_bits);
+    out->half = hw_shift_right(out->delta, 1);
+    out->delta_inv = 1.0 / hw_to_double(out->delta);
     return NIMBUS_COP_OK;
 }
 
@@ -591,32 +747,57 @@ int nimbus_rlwe_decode(const uint64_t *phi, int T, int N, int L, const uint64_t 
     RlweArgs limbs;
     int rc = rlwe_check(N, L, moduli, &limbs);
     if (rc != NIMBUS_COP_OK) return rc;
-    u128 Q, delta;
-    rc = scaling(L, moduli, t_bits, &Q, &delta);
+    Scaling sc;
+    rc = scaling(L, moduli, t_bits, &sc);
     if (rc != NIMBUS_COP_OK) return rc;
+    const uint64_t total = (uint64_t)T * (uint64_t)N;
+    if (total >= (1ull << 39)) return NIMBUS_COP_ERR_INVALID_ARG;
+    // inverses of the Chinese remainder theorem; 0 = the moduli are not coprime
+    uint64_t inv[kMaxLimbs][kMaxLimbs] = {};
+    for (int j = 1; j < L; ++j)
+        for (int i = 0; i < j; ++i) {
+            inv[i][j] = h_invmod(moduli[i] % moduli[j], moduli[j]);
+            if (inv[i][j] == 0) return NIMBUS_COP_ERR_INVALID_ARG;
+        }
     if (T == 0) return NIMBUS_COP_OK;
-    DecodeArgs a{};
-    a.phi = phi;
-    a.m_hat = m_hat;
-    a.L = L;
-    a.logN = log2_exact(N);
-    a.total = (uint64_t)T * (uint64_t)N;
-    if (a.total >= (1ull << 39)) return NIMBUS_COP_ERR_INVALID_ARG;
-    a.q0 = moduli[0];
-    if (L == 2) {
-        a.red1 = limbs.limb[1].red;
-        a.q0_inv = h_invmod(moduli[0] % moduli[1], moduli[1]);
-        if (a.q0_inv == 0) return NIMBUS_COP_ERR_INVALID_ARG;       // moduli not coprime
+    const dim3 grid((unsigned)((total + 255u) / 256u));
+    if (L <= 2) {
+        DecodeArgs a{};
+        a.phi = phi;
+        a.m_hat = m_hat;
+        a.L = L;
+        a.logN = log2_exact(N);
+        a.total = total;
+        a.q0 = moduli[0];
+        if (L == 2) {
+            a.red1 = limbs.limb[1].red;
+            a.q0_inv = inv[0][1];
+        }
+        a.delta_hi = sc.delta.w[1];
+        a.delta_lo = sc.delta.w[0];
+        a.half_hi = sc.half.w[1];
+        a.half_lo = sc.half.w[0];
+        a.delta_inv = sc.delta_inv;
+        a.t_mask = (1ull << t_bits) - 1;
+        hipLaunchKernelGGL(rlwe_decode_kernel, grid, dim3(256), 0, (hipStream_t)stream, a);
+    } else {
+        DecodeWideArgs a{};
+        a.phi = phi;
+        a.m_hat = m_hat;
+        a.L = L;
+        a.logN = log2_exact(N);
+        a.total = total;
+        for (int l = 0; l < L; ++l) a.red[l] = limbs.limb[l].red;
+        for (int i = 0; i < kMaxLimbs; ++i)
+            for (int j = 0; j < kMaxLimbs; ++j) a.inv[i][j] = inv[i][j];
+        for (int i = 0; i < 4; ++i) {
+            a.delta.w[i] = sc.delta.w[i];
+            a.half.w[i] = sc.half.w[i];
+        }
+        a.delta_inv = sc.delta_inv;
+        a.t_mask = (1ull << t_bits) - 1;
+        hipLaunchKernelGGL(rlwe_decode_wide_kernel, grid, dim3(256), 0, (hipStream_t)stream, a);
     }
-    const u128 half = delta >> 1;
-    a.delta_hi = (uint64_t)(delta >> 64);
-    a.delta_lo = (uint64_t)delta;
-    a.half_hi = (uint64_t)(half >> 64);
-    a.half_lo = (uint64_t)half;
-    a.delta_inv = 1.0 / ((double)a.delta_hi * 18446744073709551616.0 + (double)a.delta_lo);
-    a.t_mask = (1ull << t_bits) - 1;
-    hipLaunchKernelGGL(rlwe_decode_kernel, dim3((unsigned)((a.total + 255u) / 256u)), dim3(256), 0,
-                       (hipStream_t)stream, a);
     return hipGetLastError() == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 
@@ -629,11 +810,13 @@ int nimbus_rlwe_decrypt(const uint64_t *ct, int T, int N, int L, const uint64_t 
     RlweArgs limbs;
     int rc = rlwe_check(N, L, moduli, &limbs);
     if (rc != NIMBUS_COP_OK) return rc;
-    u128 Q, delta;
-    rc = scaling(L, moduli, t_bits, &Q, &delta);
+    Scaling sc;
+    rc = scaling(L, moduli, t_bits, &sc);
     if (rc != NIMBUS_COP_OK) return rc;
     if ((uint64_t)T * (uint64_t)N >= (1ull << 39)) return NIMBUS_COP_ERR_INVALID_ARG;
-    if (L == 2 && h_invmod(moduli[0] % moduli[1], moduli[1]) == 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    for (int j = 1; j < L; ++j)
+        for (int i = 0; i < j; ++i)
+            if (h_invmod(moduli[i] % moduli[j], moduli[j]) == 0) return NIMBUS_COP_ERR_INVALID_ARG;
     rc = nimbus_rlwe_phase(ct, T, N, L, moduli, tables, phi, stream);
     if (rc != NIMBUS_COP_OK) return rc;
     return nimbus_rlwe_decode(phi, T, N, L, moduli, t_bits, m_hat, stream);
@@ -648,13 +831,13 @@ int nimbus_rlwe_encrypt(const uint64_t *W, int k, int n, int t_bits, int N, int 
     PolyArgs a{};
     int rc = rlwe_check(N, L, moduli, &a.limbs);
     if (rc != NIMBUS_COP_OK) return rc;
-    u128 Q, delta;
-    rc = scaling(L, moduli, t_bits, &Q, &delta);
+    Scaling sc;
+    rc = scaling(L, moduli, t_bits, &sc);
     if (rc != NIMBUS_COP_OK) return rc;
     const unsigned long long Ch = ((unsigned long long)n + (unsigned)N - 1) / (unsigned)N;
     const unsigned long long polys = (unsigned long long)k * Ch * (unsigned)L;
     if (polys >= (1ull << 31) || Ch * (unsigned)N >= (1ull << 31)) return NIMBUS_COP_ERR_INVALID_ARG;
-    for (int l = 0; l < L; ++l) a.limbs.limb[l].delta = (uint64_t)(delta % moduli[l]);
+    for (int l = 0; l < L; ++l) a.limbs.limb[l].delta = hw_mod(sc.delta, moduli[l]);
     a.tables = (const Twiddle *)tables;
     a.L = L;
     a.src = a_poly;

@@ -188,21 +188,20 @@ def test_rlwe_argument_checks_on_the_host():
     assert lib.nimbus_rlwe_phase(0x4000, -1, N, L, mod, 0x1000, 0x3000, None) == -1
     assert lib.nimbus_rlwe_phase(0x4000, 0, N, L, mod, 0x1000, 0x3000, None) == 0   # nothing to do
     assert lib.nimbus_rlwe_phase(0x4000, 1, N, L, bad, 0x1000, 0x3000, None) == -1
-    # decode / decrypt / encrypt: at most two limbs, 1 <= t_bits <= 32, t < q
-    three = ci.limb_primes(54, 20, 3)
-    mod3 = (ctypes.c_uint64 * 3)(*three)
-    assert lib.nimbus_rlwe_decode(0x3000, 1, N, 3, mod3, 20, 0x5000, None) == -2
+    # decode / decrypt / encrypt: 1 <= t_bits <= 32, t < q
+    five = (ctypes.c_uint64 * 5)(*ci.limb_primes(54, 20, 5))
+    assert lib.nimbus_rlwe_decode(0x3000, 1, N, 5, five, 20, 0x5000, None) == -1
     assert lib.nimbus_rlwe_decode(0x3000, 1, N, L, mod, 0, 0x5000, None) == -1
     assert lib.nimbus_rlwe_decode(0x3000, 1, N, L, mod, 33, 0x5000, None) == -1
     assert lib.nimbus_rlwe_decode(0x3000, 0, N, L, mod, 20, 0x5000, None) == 0
     small = (ctypes.c_uint64 * 1)(ci.limb_primes(20, 7, 1)[0])
     assert lib.nimbus_rlwe_decode(0x3000, 1, N, 1, small, 20, 0x5000, None) == -1   # t >= q
-    assert lib.nimbus_rlwe_decrypt(0x4000, 1, N, 3, mod3, 20, 0x1000, 0x3000, 0x5000, None) == -2
+    assert lib.nimbus_rlwe_decrypt(0x4000, 1, N, 5, five, 20, 0x1000, 0x3000, 0x5000, None) == -1
     assert lib.nimbus_rlwe_decrypt(0x4000, 1, N, L, mod, 20, 0x1000, None, 0x5000, None) == -1
     assert lib.nimbus_rlwe_encrypt(0x6000, 0, 8, 20, N, L, mod, 0x1000, 0x7000, 0x8000, 0x9000,
                                    None) == -1
-    assert lib.nimbus_rlwe_encrypt(0x6000, 4, 8, 20, N, 3, mod3, 0x1000, 0x7000, 0x8000, 0x9000,
-                                   None) == -2
+    assert lib.nimbus_rlwe_encrypt(0x6000, 4, 8, 33, N, L, mod, 0x1000, 0x7000, 0x8000, 0x9000,
+                                   None) == -1
     assert lib.nimbus_rlwe_encrypt(0x6000, 4, 8, 20, N, L, mod, 0x1000, None, 0x8000, 0x9000,
                                    None) == -1
 

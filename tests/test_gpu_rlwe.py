@@ -143,6 +143,10 @@ DECRYPT_SHAPES = [
     (64, 1, 30, 7, 3),
     (2048, 2, 62, 32, 3),        # widest plaintext modulus and moduli: Q just below 2^124
     (128, 2, 40, 1, 2),          # t = 2
+    (8192, 3, 55, 24, 2),        # config 5 parameters: three limbs, Q ~ 2^165
+    (256, 4, 54, 20, 3),         # four limbs
+    (512, 4, 62, 32, 2),         # four limbs of 62 bits: Q just below 2^248
+    (64, 3, 30, 7, 3),           # three small limbs
 ]
 
 
@@ -158,10 +162,13 @@ def test_decrypt_of_uniform_ciphertexts_matches_oracle(oracle, N, L, q_bits, t_b
     got, phi = _gpu_decrypt(ct, moduli, t_bits, _tables(N, moduli, s))
     for r in range(T):
         assert np.array_equal(phi[r], oracle.phase(ct[r], s, moduli)), f"phase of {r}"
-        assert np.array_equal(got[r], oracle.decrypt(ct[r], s, moduli, t_bits)), f"ciphertext {r}"
+        want = oracle.decrypt(ct[r], s, moduli, t_bits) if L <= 2 else \
+            oracle.decrypt_rns(ct[r], s, moduli, t_bits)
+        assert np.array_equal(got[r], want), f"ciphertext {r}"
 
 
-@pytest.mark.parametrize("L,q_bits,t_bits", [(1, 50, 16), (2, 54, 20), (2, 62, 32), (1, 20, 3)])
+@pytest.mark.parametrize("L,q_bits,t_bits", [(1, 50, 16), (2, 54, 20), (2, 62, 32), (1, 20, 3),
+                                             (3, 55, 24), (4, 62, 32), (4, 40, 1), (3, 54, 20)])
 def test_decode_at_the_rounding_boundaries(oracle, L, q_bits, t_bits):
     """phases placed on and next to the rounding boundaries Delta m + Delta/2, at 0, at Q - 1
     and at the largest m: c1 = 0, so the phase is c0 itself"""
@@ -186,7 +193,7 @@ def test_decode_at_the_rounding_boundaries(oracle, L, q_bits, t_bits):
     values.append(min(Q - 1, delta * t + delta // 2 - 1))
     rng = np.random.default_rng(5)
     while len(values) % N:
-        values.append(int(rng.integers(0, 1 << 62)) % Q)
+        values.append(int.from_bytes(rng.bytes(40), "little") % Q)
     T = len(values) // N
     ct = np.zeros((T, 2, L, N), dtype=np.uint64)
     for i, v in enumerate(values):
@@ -195,7 +202,7 @@ def test_decode_at_the_rounding_boundaries(oracle, L, q_bits, t_bits):
     s = ci.gen_secret(1, N)
     got, _ = _gpu_decrypt(ct, moduli, t_bits, _tables(N, moduli, s))
     for r in range(T):
-        want = oracle.decrypt(ct[r], s, moduli, t_bits)
+        want = oracle.decrypt_rns(ct[r], s, moduli, t_bits)
         assert np.array_equal(got[r], want), f"row {r}"
     # and against the plain formula on Python integers
     flat = got.reshape(-1)
@@ -211,6 +218,8 @@ ENCRYPT_SHAPES = [
     (3, 3072, 4096, 2, 54, 20),      # BERT-base FFN row
     (2, 4096, 8192, 2, 55, 24),      # config 5 row
     (4, 100, 64, 2, 62, 32),         # 32-bit plaintexts, widest moduli, ragged chunks
+    (3, 4096, 8192, 3, 55, 24),      # config 5 row with its three limbs
+    (5, 200, 128, 4, 54, 20),        # four limbs, two chunks
 ]
 
 
@@ -228,8 +237,9 @@ def test_encrypt_matches_oracle(oracle, k, n, N, L, q_bits, t_bits):
     a, e = ci.gen_enc_randomness(seed, k, Ch, moduli, N)
     _say(f"[rlwe] encrypt k={k} n={n} N={N} L={L} q_bits={q_bits} t_bits={t_bits}")
     w_hat = oracle.encode_rows(W, N)                       # [k][Ch][N]
-    want = oracle.encrypt(w_hat.reshape(k * Ch, N), s, a.reshape(k * Ch, L, N),
-                          e.reshape(k * Ch, N), moduli, t_bits).reshape(k, Ch, 2, L, N)
+    enc = oracle.encrypt if L <= 2 else oracle.encrypt_rns
+    want = enc(w_hat.reshape(k * Ch, N), s, a.reshape(k * Ch, L, N),
+               e.reshape(k * Ch, N), moduli, t_bits).reshape(k, Ch, 2, L, N)
     tables = _tables(N, moduli, s)
     ctW = torch.empty((k, Ch, 2, L, N), dtype=torch.int64, device="cuda")
     nc.nimbus_rlwe_encrypt(gu.dev(W), k, n, t_bits, N, L, moduli, tables, gu.dev(a),
