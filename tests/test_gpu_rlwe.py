@@ -299,3 +299,44 @@ def test_whole_layer_on_the_gpu_config1(oracle):
     pk = gu.host(packed)
     for th in range(Tn):
         assert np.array_equal(share_server[th], oracle.decrypt(pk[th], s, moduli, t_bits))
+
+
+def test_whole_layer_on_the_gpu_three_limbs(oracle):
+    """the same end to end with config 5's parameters (three 55-bit limbs, t = 2^24) on a small
+    shape with three rows per packed ciphertext"""
+    import torch
+    import gpu_util as gu
+    import paper_2411_15707_amd as nc
+    m, k, n, N, L, t_bits, q_bits = 8, 48, 40, 128, 3, 24, 55
+    moduli = _primes(q_bits, t_bits, N, L)
+    seed = 5150
+    t = 1 << t_bits
+    s = ci.gen_secret(seed, N)
+    W = ci.gen_W(seed, k, n, t_bits)
+    X = ci.gen_X(seed, m, k, t_bits)
+    a, e = ci.gen_enc_randomness(seed, k, 1, moduli, N)
+    tables = _tables(N, moduli, s)
+    ctW = torch.empty((k, 1, 2, L, N), dtype=torch.int64, device="cuda")
+    nc.nimbus_rlwe_encrypt(gu.dev(W), k, n, t_bits, N, L, moduli, tables, gu.dev(a),
+                           torch.from_numpy(e).cuda(), ctW)
+    P = N // n
+    Tn = nc.nimbus_cop_packed_count(m, n, N)
+    R = ci.gen_R(seed, Tn, N, t_bits)
+    pmask = np.stack([oracle.share_mask_rns(R[th], moduli, t_bits) for th in range(Tn)])
+    rows = gu.run_mfma(X, gu.host(ctW), moduli, n, N, t_bits, None)
+    packed = torch.empty((Tn, 2, L, N), dtype=torch.int64, device="cuda")
+    nc.nimbus_cop_pack(gu.dev(rows[:, 0]), m, n, N, L, moduli, gu.dev(pmask), packed)
+    phi = torch.empty((Tn, L, N), dtype=torch.int64, device="cuda")
+    m_hat = torch.empty((Tn, N), dtype=torch.int64, device="cuda")
+    nc.nimbus_rlwe_decrypt(packed, Tn, N, L, moduli, t_bits, tables, phi, m_hat)
+    torch.cuda.synchronize()
+    share_server = gu.host(m_hat)
+    Y = (X.astype(object) @ W.astype(object)) % t
+    for th in range(Tn):
+        total = (share_server[th].astype(object) + R[th].astype(object)) % t
+        for u in range(P):
+            j = th * P + u
+            want = Y[j] if j < m else np.zeros(n, dtype=object)
+            assert np.array_equal(total[u * n:(u + 1) * n], want), (th, u)
+        assert np.array_equal(share_server[th],
+                              oracle.decrypt_rns(gu.host(packed)[th], s, moduli, t_bits))
