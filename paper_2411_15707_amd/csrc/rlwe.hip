@@ -137,77 +137,221 @@ enum RoundKind { kForward, kInverse, kMiddle };
 // One round over the stages P0 .. P0+S-1.  A group is the 2^S coefficients
 //   base + r * 2^LT,  r < 2^S,  base = i0 * 2^(LOGN-P0) + o,  o < 2^LT,  LT = LOGN - P0 - S:
 // block i0 of stage P0 (2^P0 blocks), offset o inside the smallest stride of the round.
-// In stage P0+st coefficient r of the group sits in block i0 * 2^st + (r >> (S - st)).
+// In stage P0+st coefficient r of the group sits in block i0 * 2^st + (r >> (S - st)), so the
+// stage uses 2^st table entries per group, 2^S - 1 per direction in all.
+template <int LOGN, int P0, int S>
+struct Group {
+    static constexpr int N = 1 << LOGN, R = 1 << S, LT = LOGN - P0 - S, G = N / R;
+    int i0, base;
+    __device__ __forceinline__ explicit Group(int g)
+        : i0(g >> LT), base(((g >> LT) << (LOGN - P0)) + (g & ((1 << LT) - 1))) {}
+    __device__ __forceinline__ int at(int r) const { return base + (r << LT); }
+    // table index of entry j (j < 2^st) of stage st
+    __device__ __forceinline__ int entry(int st, int j) const { return (1 << (P0 + st)) + (i0 << st) + j; }
+};
+
+// The table entries one group needs in one round, in registers: loaded before the barrier
+// that ends the round before, so that their latency does not come after it.
+template <int S, RoundKind KIND>
+struct RoundTable {
+    static constexpr int R = 1 << S;
+    static constexpr int NF = KIND != kInverse ? R - 1 : 1;
+    static constexpr int NI = KIND != kForward ? R - 1 : 1;
+    static constexpr int NS = KIND == kMiddle ? R : 1;
+    Twiddle f[NF], i[NI], s[NS];
+};
+
+template <int LOGN, int P0, int S, RoundKind KIND>
+__device__ __forceinline__ RoundTable<S, KIND> load_round_table(const Twiddle *__restrict__ fwd,
+                                                                const Twiddle *__restrict__ inv,
+                                                                const Twiddle *__restrict__ shat,
+                                                                int g)
+{
+    const Group<LOGN, P0, S> grp(g);
+    RoundTable<S, KIND> t;
+#pragma unroll
+    for (int st = 0; st < S; ++st)
+#pragma unroll
+        for (int j = 0; j < (1 << st); ++j) {
+            if constexpr (KIND != kInverse) t.f[(1 << st) - 1 + j] = fwd[grp.entry(st, j)];
+            if constexpr (KIND != kForward) t.i[(1 << st) - 1 + j] = inv[grp.entry(st, j)];
+        }
+    if constexpr (KIND == kMiddle) {
+#pragma unroll
+        for (int r = 0; r < (1 << S); ++r) t.s[r] = shat[grp.at(r)];
+    }
+    return t;
+}
+
+// the butterflies of one group; F(st, j), I(st, j), Sh(r) hand out the table entries
+template <int S, RoundKind KIND, typename FwdT, typename InvT, typename SecT>
+__device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], uint64_t q, FwdT F, InvT I,
+                                                  SecT Sh)
+{
+    constexpr int R = 1 << S;
+    const uint64_t two_q = 2 * q;
+    if constexpr (KIND != kInverse) {
+#pragma unroll
+        for (int st = 0; st < S; ++st) {
+            const int half = R >> (st + 1);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (r & half) continue;
+                const Twiddle t = F(st, r >> (S - st));
+                uint64_t u = x[r];
+                u = u >= two_q ? u - two_q : u;
+                const uint64_t v = mul_lazy(x[r + half], t, q);
+                x[r] = u + v;
+                x[r + half] = u - v + two_q;
+            }
+        }
+    }
+    if constexpr (KIND == kMiddle) {
+        // bit-reversed position = LDS index: the transformed secret uses the same order
+#pragma unroll
+        for (int r = 0; r < R; ++r) x[r] = mul_lazy(x[r], Sh(r), q);
+    }
+    if constexpr (KIND != kForward) {
+#pragma unroll
+        for (int st = S - 1; st >= 0; --st) {
+            const int half = R >> (st + 1);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (r & half) continue;
+                const Twiddle t = I(st, r >> (S - st));
+                const uint64_t u = x[r], v = x[r + half];
+                const uint64_t sum = u + v;
+                x[r] = sum >= two_q ? sum - two_q : sum;
+                x[r + half] = mul_lazy(u - v + two_q, t, q);
+            }
+        }
+    }
+}
+
+// a round with the table entries read from memory inside it (any number of groups per thread)
 template <int LOGN, int P0, int S, RoundKind KIND, int NT>
 __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restrict__ fwd,
                                           const Twiddle *__restrict__ inv,
                                           const Twiddle *__restrict__ shat, uint64_t q, int tid)
 {
-    constexpr int N = 1 << LOGN, R = 1 << S, LT = LOGN - P0 - S, G = N / R;
-    const uint64_t two_q = 2 * q;
-    for (int g = tid; g < G; g += NT) {
-        const int i0 = g >> LT, o = g & ((1 << LT) - 1);
-        const int base = (i0 << (LOGN - P0)) + o;
-        uint64_t x[R];
+    using Grp = Group<LOGN, P0, S>;
+    for (int g = tid; g < Grp::G; g += NT) {
+        const Grp grp(g);
+        uint64_t x[Grp::R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) x[r] = lds[pad(base + (r << LT))];
-        if constexpr (KIND != kInverse) {
+        for (int r = 0; r < Grp::R; ++r) x[r] = lds[pad(grp.at(r))];
+        group_butterflies<S, KIND>(
+            x, q, [&](int st, int j) { return fwd[grp.entry(st, j)]; },
+            [&](int st, int j) { return inv[grp.entry(st, j)]; },
+            [&](int r) { return shat[grp.at(r)]; });
 #pragma unroll
-            for (int st = 0; st < S; ++st) {
-                const int half = R >> (st + 1);
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    if (r & half) continue;
-                    const Twiddle t = fwd[(1 << (P0 + st)) + (i0 << st) + (r >> (S - st))];
-                    uint64_t u = x[r];
-                    u = u >= two_q ? u - two_q : u;
-                    const uint64_t v = mul_lazy(x[r + half], t, q);
-                    x[r] = u + v;
-                    x[r + half] = u - v + two_q;
-                }
-            }
-        }
-        if constexpr (KIND == kMiddle) {
-            // bit-reversed position = LDS index: the transformed secret uses the same order
-#pragma unroll
-            for (int r = 0; r < R; ++r) x[r] = mul_lazy(x[r], shat[base + (r << LT)], q);
-        }
-        if constexpr (KIND != kForward) {
-#pragma unroll
-            for (int st = S - 1; st >= 0; --st) {
-                const int half = R >> (st + 1);
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    if (r & half) continue;
-                    const Twiddle t = inv[(1 << (P0 + st)) + (i0 << st) + (r >> (S - st))];
-                    const uint64_t u = x[r], v = x[r + half];
-                    const uint64_t sum = u + v;
-                    x[r] = sum >= two_q ? sum - two_q : sum;
-                    x[r + half] = mul_lazy(u - v + two_q, t, q);
-                }
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) lds[pad(base + (r << LT))] = x[r];
+        for (int r = 0; r < Grp::R; ++r) lds[pad(grp.at(r))] = x[r];
     }
 }
 
-// forward rounds from stage P0 on, the pointwise product, and the inverse rounds back to P0
-template <int LOGN, int MAXS, int P0, int NT>
+// a round of at most one group per thread with the table entries already in registers
+template <int LOGN, int P0, int S, RoundKind KIND>
+__device__ __forceinline__ void ntt_round_preloaded(uint64_t *lds, const RoundTable<S, KIND> &t,
+                                                    uint64_t q, int tid)
+{
+    using Grp = Group<LOGN, P0, S>;
+    if (tid >= Grp::G) return;
+    const Grp grp(tid);
+    uint64_t x[Grp::R];
+#pragma unroll
+    for (int r = 0; r < Grp::R; ++r) x[r] = lds[pad(grp.at(r))];
+    group_butterflies<S, KIND>(
+        x, q, [&](int st, int j) { return t.f[(1 << st) - 1 + j]; },
+        [&](int st, int j) { return t.i[(1 << st) - 1 + j]; }, [&](int r) { return t.s[r]; });
+#pragma unroll
+    for (int r = 0; r < Grp::R; ++r) lds[pad(grp.at(r))] = x[r];
+}
+
+// The rounds of a product by the secret, in order: forward rounds 0 .. F-2, the round in the
+// middle (last forward stages, pointwise product, first inverse stages), inverse rounds
+// F-2 .. 0, F = rounds_for(LOGN, MAXS).
+template <int LOGN, int MAXS, int IDX>
+struct RoundOf {
+    static constexpr int F = rounds_for(LOGN, MAXS);
+    static constexpr int TOTAL = 2 * F - 1;
+    static constexpr int J = IDX < F ? IDX : 2 * F - 2 - IDX;       // forward round it mirrors
+    static constexpr int start_of(int j)
+    {
+        int p = 0;
+        for (int i = 0; i < j; ++i) p += round_stages(LOGN - p, MAXS);
+        return p;
+    }
+    static constexpr int P0 = start_of(J);
+    static constexpr int S = round_stages(LOGN - P0, MAXS);
+    static constexpr RoundKind KIND = IDX == F - 1 ? kMiddle : (IDX < F ? kForward : kInverse);
+    static constexpr int G = (1 << LOGN) >> S;
+};
+
+struct NoTable {};
+
+// Stages per round by ring degree and batch size (see launch_poly): a batch that fills the
+// chip several times runs 256 threads per polynomial where the ring allows it, a smaller one
+// up to 1024.
+constexpr int clamp_stages(int s) { return s < 2 ? 2 : (s > 4 ? 4 : s); }
+constexpr int stages_large_batch(int logN) { return clamp_stages(logN - 8); }
+constexpr int stages_small_batch(int logN) { return clamp_stages(logN - 10); }
+// Table entries are asked for ahead of the barrier only in kernels that no large batch uses
+// (a large batch hides the latency with other workgroups, and the registers cost it
+// occupancy), only in rounds of at most two stages (3 to 10 entries), and only where a thread
+// has a single group.
+template <int LOGN, int MAXS, int IDX, int NT>
+constexpr bool preload_round()
+{
+    using Rd = RoundOf<LOGN, MAXS, IDX>;
+    return MAXS == stages_small_batch(LOGN) && MAXS != stages_large_batch(LOGN) && Rd::S <= 2 &&
+           Rd::G <= NT;
+}
+
+// Round IDX and everything after it.  Where preload_round() says so, the next round's table
+// entries are asked for before the barrier between the two rounds.
+template <int LOGN, int MAXS, int IDX, int NT, typename Table>
+__device__ __forceinline__ void rounds_from(uint64_t *lds, const Twiddle *fwd, const Twiddle *inv,
+                                            const Twiddle *shat, uint64_t q, int tid,
+                                            const Table &mine)
+{
+    using Me = RoundOf<LOGN, MAXS, IDX>;
+    if constexpr (preload_round<LOGN, MAXS, IDX, NT>())
+        ntt_round_preloaded<LOGN, Me::P0, Me::S, Me::KIND>(lds, mine, q, tid);
+    else
+        ntt_round<LOGN, Me::P0, Me::S, Me::KIND, NT>(lds, fwd, inv, shat, q, tid);
+    if constexpr (IDX + 1 < Me::TOTAL) {
+        using Next = RoundOf<LOGN, MAXS, IDX + 1>;
+        if constexpr (preload_round<LOGN, MAXS, IDX + 1, NT>()) {
+            const int g = tid < Next::G ? tid : Next::G - 1;        // idle threads: any valid group
+            const auto next = load_round_table<LOGN, Next::P0, Next::S, Next::KIND>(fwd, inv, shat, g);
+            __syncthreads();
+            rounds_from<LOGN, MAXS, IDX + 1, NT>(lds, fwd, inv, shat, q, tid, next);
+        } else {
+            __syncthreads();
+            rounds_from<LOGN, MAXS, IDX + 1, NT>(lds, fwd, inv, shat, q, tid, NoTable{});
+        }
+    } else {
+        __syncthreads();
+    }
+}
+
+// the polynomial in the LDS times the secret; ends with a barrier.  The caller has not yet
+// passed the barrier behind its own writes to the LDS: the first round's table entries are
+// asked for in front of it.
+template <int LOGN, int MAXS, int NT>
 __device__ __forceinline__ void multiply_by_secret(uint64_t *lds, const Twiddle *fwd,
                                                    const Twiddle *inv, const Twiddle *shat,
                                                    uint64_t q, int tid)
 {
-    constexpr int S = round_stages(LOGN - P0, MAXS);
-    if constexpr (P0 + S == LOGN) {
-        ntt_round<LOGN, P0, S, kMiddle, NT>(lds, fwd, inv, shat, q, tid);
+    using First = RoundOf<LOGN, MAXS, 0>;
+    if constexpr (preload_round<LOGN, MAXS, 0, NT>()) {
+        const int g = tid < First::G ? tid : First::G - 1;
+        const auto first = load_round_table<LOGN, First::P0, First::S, First::KIND>(fwd, inv, shat, g);
         __syncthreads();
+        rounds_from<LOGN, MAXS, 0, NT>(lds, fwd, inv, shat, q, tid, first);
     } else {
-        ntt_round<LOGN, P0, S, kForward, NT>(lds, fwd, inv, shat, q, tid);
         __syncthreads();
-        multiply_by_secret<LOGN, MAXS, P0 + S, NT>(lds, fwd, inv, shat, q, tid);
-        ntt_round<LOGN, P0, S, kInverse, NT>(lds, fwd, inv, shat, q, tid);
-        __syncthreads();
+        rounds_from<LOGN, MAXS, 0, NT>(lds, fwd, inv, shat, q, tid, NoTable{});
     }
 }
 
@@ -293,8 +437,7 @@ __global__ __launch_bounds__(threads_for(LOGN, MAXS)) void rlwe_poly_kernel(Poly
     } else {
         for (int c = tid; c < N; c += NT) lds[pad(c)] = mul_in[c];
     }
-    __syncthreads();
-    multiply_by_secret<LOGN, MAXS, 0, NT>(lds, t, t + N, t + 2 * N, q, tid);
+    multiply_by_secret<LOGN, MAXS, NT>(lds, t, t + N, t + 2 * N, q, tid);
     if constexpr (!ENCRYPT) {
         const uint64_t *const c0 = a.src + (((size_t)row * 2 + 0) * a.L + l) * N;
         uint64_t *const phi = a.dst + ((size_t)row * a.L + l) * N;
@@ -676,8 +819,7 @@ static hipError_t launch_poly(const PolyArgs &a, int logN, size_t polys, hipStre
 #ifdef NIMBUS_RLWE_FORCE_MAXS
     return launch_poly_with<ENCRYPT, NIMBUS_RLWE_FORCE_MAXS>(a, logN, polys, stream);
 #else
-    int maxs = polys >= 1024 ? logN - 8 : logN - 10;
-    maxs = maxs < 2 ? 2 : (maxs > 4 ? 4 : maxs);
+    const int maxs = polys >= 1024 ? stages_large_batch(logN) : stages_small_batch(logN);
     if (maxs == 4) return launch_poly_with<ENCRYPT, 4>(a, logN, polys, stream);
     if (maxs == 3) return launch_poly_with<ENCRYPT, 3>(a, logN, polys, stream);
     return launch_poly_with<ENCRYPT, 2>(a, logN, polys, stream);
