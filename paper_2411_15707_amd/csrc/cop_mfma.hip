@@ -242,11 +242,12 @@ __device__ __forceinline__ void dma_tile_stream(const void *src_lane, void *dst_
 // chip lowers its clock under the combined matrix-core and memory load, and a k-block
 // costs the matrix-core time of its 42 instructions per SIMD at the rate a register-only
 // loop reaches on random bytes, plus a memory-side term; the two add up instead of
-// overlapping.  Within that, what the schedule has to respect: the number of bytes a CU
-// can have in flight to HBM (about 16 KB: a load instruction that does not fit stalls its
-// wave until earlier loads return, so the ciphertext loads are spread over the iteration,
-// where the other wave of the SIMD can fill the gap with its own matrix-core
-// instructions), and instruction issue (a wave issues an instruction every four or five
+// overlapping.  Within that, what the schedule has to respect: enough bytes in flight per
+// CU (a streaming read reaches 3.9 TB/s chip-wide with 8 KB in flight per CU, 6.5 with 16 KB,
+// 7.0 from 32 KB on, direct-to-LDS and register loads alike; two to three stages of 26 KB
+// are in flight here), the ciphertext loads spread over the iteration, where the other
+// wave of the SIMD can fill a gap with its own matrix-core instructions, and
+// instruction issue (a wave issues an instruction every four or five
 // cycles at best and all eight waves run in lockstep between barriers, so every scalar
 // instruction costs: one stage issued per iteration from the first iteration on,
 // ring offsets carried and wrapped instead of recomputed, and the wait for "at most n
