@@ -32,8 +32,9 @@
  *   - every pointer is a DEVICE pointer owned by the caller, except `moduli`, which is a
  *     HOST pointer to L primes, each odd, < 2^62 and = 1 modulo 2N (so that a primitive
  *     2N-th root of unity exists; a modulus without one is NIMBUS_COP_ERR_INVALID_ARG);
- *   - N is a power of two, 32 <= N <= 16384 (one polynomial is transformed inside the
- *     local memory of one compute unit; N = 32768 is NIMBUS_COP_ERR_UNSUPPORTED);
+ *   - N is a power of two, 32 <= N <= 32768 (up to 16384 one polynomial is transformed
+ *     inside the local memory of one compute unit, 32768 in two halves and a joining pass;
+ *     N = 65536 is NIMBUS_COP_ERR_UNSUPPORTED);
  *   - 1 <= L <= 4 distinct primes (Q < 2^248); 1 <= t_bits <= 32 and 2^t_bits < q_l for
  *     decoding and encryption;
  *   - nothing is allocated, freed or synchronised; all work is enqueued on `stream`
@@ -65,7 +66,7 @@ size_t nimbus_rlwe_tables_bytes(int N, int L);
  *   tables  written; read-only afterwards, shared by every later call with the same
  *           (N, L, moduli, s)
  * Errors: INVALID_ARG (null pointer, N / L / modulus out of range, no 2N-th root of unity
- * found), UNSUPPORTED (N > 16384), BUFFER_SIZE (tables_bytes too small), LAUNCH. */
+ * found), UNSUPPORTED (N > 32768), BUFFER_SIZE (tables_bytes too small), LAUNCH. */
 int nimbus_rlwe_setup(int N, int L, const uint64_t *moduli, const int8_t *s,
                       void *tables, size_t tables_bytes, void *stream);
 

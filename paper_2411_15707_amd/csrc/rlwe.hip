@@ -32,7 +32,7 @@ namespace nimbus {
 typedef unsigned __int128 u128;
 
 constexpr int kRlweMinLogN = 5;
-constexpr int kRlweMaxLogN = 14;        // 2^14 coefficients of 8 bytes = 128 KiB of the 160 KiB LDS
+constexpr int kRlweMaxLogN = 15;        // 2^14 coefficients (128 KiB of the 160 KiB LDS) at a time
 
 struct Twiddle {
     uint64_t w;     // < q
@@ -228,63 +228,82 @@ __device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], uint64_
     }
 }
 
+// A ring too large for the LDS (2^15 coefficients) is handled in 2^PRE parts: the stages
+// below PRE are done on the way in (forward) and in a pass of their own afterwards
+// (inverse), and between them every part is a transform of 2^(LOGN-PRE) coefficients with
+// its own table entries.  Part h holds the coefficients h * 2^(LOGN-PRE) ... of the ring
+// (blocks of the stages from PRE on never straddle two parts), so its groups are the ring's
+// groups  h * G / 2^PRE ... and its LDS index is the ring index minus h * 2^(LOGN-PRE).
+struct Part {
+    int group0;     // first group of the part (in the numbering of the round at hand)
+    int index0;     // first coefficient of the part
+};
+template <int LOGN, int PRE, int S>
+__device__ __forceinline__ Part part_of(int h)
+{
+    return Part{h * (((1 << LOGN) >> S) >> PRE), h << (LOGN - PRE)};
+}
+
 // a round with the table entries read from memory inside it (any number of groups per thread)
-template <int LOGN, int P0, int S, RoundKind KIND, int NT>
+template <int LOGN, int PRE, int P0, int S, RoundKind KIND, int NT>
 __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restrict__ fwd,
                                           const Twiddle *__restrict__ inv,
-                                          const Twiddle *__restrict__ shat, uint64_t q, int tid)
+                                          const Twiddle *__restrict__ shat, uint64_t q, int tid,
+                                          int h)
 {
     using Grp = Group<LOGN, P0, S>;
-    for (int g = tid; g < Grp::G; g += NT) {
-        const Grp grp(g);
+    const Part part = part_of<LOGN, PRE, S>(h);
+    for (int g = tid; g < (Grp::G >> PRE); g += NT) {
+        const Grp grp(part.group0 + g);
         uint64_t x[Grp::R];
 #pragma unroll
-        for (int r = 0; r < Grp::R; ++r) x[r] = lds[pad(grp.at(r))];
+        for (int r = 0; r < Grp::R; ++r) x[r] = lds[pad(grp.at(r) - part.index0)];
         group_butterflies<S, KIND>(
             x, q, [&](int st, int j) { return fwd[grp.entry(st, j)]; },
             [&](int st, int j) { return inv[grp.entry(st, j)]; },
             [&](int r) { return shat[grp.at(r)]; });
 #pragma unroll
-        for (int r = 0; r < Grp::R; ++r) lds[pad(grp.at(r))] = x[r];
+        for (int r = 0; r < Grp::R; ++r) lds[pad(grp.at(r) - part.index0)] = x[r];
     }
 }
 
 // a round of at most one group per thread with the table entries already in registers
-template <int LOGN, int P0, int S, RoundKind KIND>
+template <int LOGN, int PRE, int P0, int S, RoundKind KIND>
 __device__ __forceinline__ void ntt_round_preloaded(uint64_t *lds, const RoundTable<S, KIND> &t,
-                                                    uint64_t q, int tid)
+                                                    uint64_t q, int tid, int h)
 {
     using Grp = Group<LOGN, P0, S>;
-    if (tid >= Grp::G) return;
-    const Grp grp(tid);
+    if (tid >= (Grp::G >> PRE)) return;
+    const Part part = part_of<LOGN, PRE, S>(h);
+    const Grp grp(part.group0 + tid);
     uint64_t x[Grp::R];
 #pragma unroll
-    for (int r = 0; r < Grp::R; ++r) x[r] = lds[pad(grp.at(r))];
+    for (int r = 0; r < Grp::R; ++r) x[r] = lds[pad(grp.at(r) - part.index0)];
     group_butterflies<S, KIND>(
         x, q, [&](int st, int j) { return t.f[(1 << st) - 1 + j]; },
         [&](int st, int j) { return t.i[(1 << st) - 1 + j]; }, [&](int r) { return t.s[r]; });
 #pragma unroll
-    for (int r = 0; r < Grp::R; ++r) lds[pad(grp.at(r))] = x[r];
+    for (int r = 0; r < Grp::R; ++r) lds[pad(grp.at(r) - part.index0)] = x[r];
 }
 
-// The rounds of a product by the secret, in order: forward rounds 0 .. F-2, the round in the
-// middle (last forward stages, pointwise product, first inverse stages), inverse rounds
-// F-2 .. 0, F = rounds_for(LOGN, MAXS).
-template <int LOGN, int MAXS, int IDX>
+// The rounds of a product by the secret over the stages PRE .. LOGN-1, in order: forward
+// rounds 0 .. F-2, the round in the middle (last forward stages, pointwise product, first
+// inverse stages), inverse rounds F-2 .. 0, F = rounds_for(LOGN - PRE, MAXS).
+template <int LOGN, int PRE, int MAXS, int IDX>
 struct RoundOf {
-    static constexpr int F = rounds_for(LOGN, MAXS);
+    static constexpr int F = rounds_for(LOGN - PRE, MAXS);
     static constexpr int TOTAL = 2 * F - 1;
     static constexpr int J = IDX < F ? IDX : 2 * F - 2 - IDX;       // forward round it mirrors
     static constexpr int start_of(int j)
     {
-        int p = 0;
+        int p = PRE;
         for (int i = 0; i < j; ++i) p += round_stages(LOGN - p, MAXS);
         return p;
     }
     static constexpr int P0 = start_of(J);
     static constexpr int S = round_stages(LOGN - P0, MAXS);
     static constexpr RoundKind KIND = IDX == F - 1 ? kMiddle : (IDX < F ? kForward : kInverse);
-    static constexpr int G = (1 << LOGN) >> S;
+    static constexpr int G = ((1 << LOGN) >> S) >> PRE;             // groups of one part
 };
 
 struct NoTable {};
@@ -299,70 +318,72 @@ constexpr int stages_small_batch(int logN) { return clamp_stages(logN - 10); }
 // (a large batch hides the latency with other workgroups, and the registers cost it
 // occupancy), only in rounds of at most two stages (3 to 10 entries), and only where a thread
 // has a single group.
-template <int LOGN, int MAXS, int IDX, int NT>
+template <int LOGN, int PRE, int MAXS, int IDX, int NT>
 constexpr bool preload_round()
 {
-    using Rd = RoundOf<LOGN, MAXS, IDX>;
-    return MAXS == stages_small_batch(LOGN) && MAXS != stages_large_batch(LOGN) && Rd::S <= 2 &&
-           Rd::G <= NT;
+    using Rd = RoundOf<LOGN, PRE, MAXS, IDX>;
+    return PRE == 0 && MAXS == stages_small_batch(LOGN) && MAXS != stages_large_batch(LOGN) &&
+           Rd::S <= 2 && Rd::G <= NT;
 }
 
 // Round IDX and everything after it.  Where preload_round() says so, the next round's table
 // entries are asked for before the barrier between the two rounds.
-template <int LOGN, int MAXS, int IDX, int NT, typename Table>
+template <int LOGN, int PRE, int MAXS, int IDX, int NT, typename Table>
 __device__ __forceinline__ void rounds_from(uint64_t *lds, const Twiddle *fwd, const Twiddle *inv,
-                                            const Twiddle *shat, uint64_t q, int tid,
+                                            const Twiddle *shat, uint64_t q, int tid, int h,
                                             const Table &mine)
 {
-    using Me = RoundOf<LOGN, MAXS, IDX>;
-    if constexpr (preload_round<LOGN, MAXS, IDX, NT>())
-        ntt_round_preloaded<LOGN, Me::P0, Me::S, Me::KIND>(lds, mine, q, tid);
+    using Me = RoundOf<LOGN, PRE, MAXS, IDX>;
+    if constexpr (preload_round<LOGN, PRE, MAXS, IDX, NT>())
+        ntt_round_preloaded<LOGN, PRE, Me::P0, Me::S, Me::KIND>(lds, mine, q, tid, h);
     else
-        ntt_round<LOGN, Me::P0, Me::S, Me::KIND, NT>(lds, fwd, inv, shat, q, tid);
+        ntt_round<LOGN, PRE, Me::P0, Me::S, Me::KIND, NT>(lds, fwd, inv, shat, q, tid, h);
     if constexpr (IDX + 1 < Me::TOTAL) {
-        using Next = RoundOf<LOGN, MAXS, IDX + 1>;
-        if constexpr (preload_round<LOGN, MAXS, IDX + 1, NT>()) {
+        using Next = RoundOf<LOGN, PRE, MAXS, IDX + 1>;
+        if constexpr (preload_round<LOGN, PRE, MAXS, IDX + 1, NT>()) {
             const int g = tid < Next::G ? tid : Next::G - 1;        // idle threads: any valid group
             const auto next = load_round_table<LOGN, Next::P0, Next::S, Next::KIND>(fwd, inv, shat, g);
             __syncthreads();
-            rounds_from<LOGN, MAXS, IDX + 1, NT>(lds, fwd, inv, shat, q, tid, next);
+            rounds_from<LOGN, PRE, MAXS, IDX + 1, NT>(lds, fwd, inv, shat, q, tid, h, next);
         } else {
             __syncthreads();
-            rounds_from<LOGN, MAXS, IDX + 1, NT>(lds, fwd, inv, shat, q, tid, NoTable{});
+            rounds_from<LOGN, PRE, MAXS, IDX + 1, NT>(lds, fwd, inv, shat, q, tid, h, NoTable{});
         }
     } else {
         __syncthreads();
     }
 }
 
-// the polynomial in the LDS times the secret; ends with a barrier.  The caller has not yet
-// passed the barrier behind its own writes to the LDS: the first round's table entries are
-// asked for in front of it.
-template <int LOGN, int MAXS, int NT>
+// The part in the LDS times the secret (stages PRE .. LOGN-1 and back); ends with a barrier.
+// The caller has not yet passed the barrier behind its own writes to the LDS: the first
+// round's table entries are asked for in front of it.
+template <int LOGN, int PRE, int MAXS, int NT>
 __device__ __forceinline__ void multiply_by_secret(uint64_t *lds, const Twiddle *fwd,
                                                    const Twiddle *inv, const Twiddle *shat,
-                                                   uint64_t q, int tid)
+                                                   uint64_t q, int tid, int h)
 {
-    using First = RoundOf<LOGN, MAXS, 0>;
-    if constexpr (preload_round<LOGN, MAXS, 0, NT>()) {
+    using First = RoundOf<LOGN, PRE, MAXS, 0>;
+    if constexpr (preload_round<LOGN, PRE, MAXS, 0, NT>()) {
         const int g = tid < First::G ? tid : First::G - 1;
         const auto first = load_round_table<LOGN, First::P0, First::S, First::KIND>(fwd, inv, shat, g);
         __syncthreads();
-        rounds_from<LOGN, MAXS, 0, NT>(lds, fwd, inv, shat, q, tid, first);
+        rounds_from<LOGN, PRE, MAXS, 0, NT>(lds, fwd, inv, shat, q, tid, h, first);
     } else {
         __syncthreads();
-        rounds_from<LOGN, MAXS, 0, NT>(lds, fwd, inv, shat, q, tid, NoTable{});
+        rounds_from<LOGN, PRE, MAXS, 0, NT>(lds, fwd, inv, shat, q, tid, h, NoTable{});
     }
 }
 
-template <int LOGN, int MAXS, int P0, int NT>
-__device__ __forceinline__ void forward_only(uint64_t *lds, const Twiddle *fwd, uint64_t q, int tid)
+// forward stages P0 .. LOGN-1 of the part in the LDS; ends with a barrier
+template <int LOGN, int PRE, int MAXS, int P0, int NT>
+__device__ __forceinline__ void forward_only(uint64_t *lds, const Twiddle *fwd, uint64_t q, int tid,
+                                             int h)
 {
     if constexpr (P0 < LOGN) {
         constexpr int S = round_stages(LOGN - P0, MAXS);
-        ntt_round<LOGN, P0, S, kForward, NT>(lds, fwd, nullptr, nullptr, q, tid);
+        ntt_round<LOGN, PRE, P0, S, kForward, NT>(lds, fwd, nullptr, nullptr, q, tid, h);
         __syncthreads();
-        forward_only<LOGN, MAXS, P0 + S, NT>(lds, fwd, q, tid);
+        forward_only<LOGN, PRE, MAXS, P0 + S, NT>(lds, fwd, q, tid, h);
     }
 }
 
@@ -370,28 +391,46 @@ __device__ __forceinline__ void forward_only(uint64_t *lds, const Twiddle *fwd, 
 // setup: transform of the secret, times 1/N, with companions
 // one workgroup per limb
 // ---------------------------------------------------------------------------
-template <int LOGN>
-__global__ __launch_bounds__(threads_for(LOGN, 4)) void rlwe_secret_kernel(
+// the first PRE (0 or 1) forward stages on a pair (u, v) of coefficients N/2 apart: what part h
+// of the ring starts from.  u, v < q; result below 3q.
+template <int PRE>
+__device__ __forceinline__ uint64_t enter_part(uint64_t u, uint64_t v, const Twiddle &w0, uint64_t q,
+                                               int h)
+{
+    static_assert(PRE == 1, "one stage ahead of the parts");
+    const uint64_t wv = mul_lazy(v, w0, q);                 // [0, 2q)
+    return h == 0 ? u + wv : u + 2 * q - wv;
+}
+
+template <int LOGN, int PRE>
+__global__ __launch_bounds__(threads_for(LOGN - PRE, 4)) void rlwe_secret_kernel(
     RlweArgs a, const int8_t *__restrict__ s, Twiddle *__restrict__ tables)
 {
-    constexpr int N = 1 << LOGN, NT = threads_for(LOGN, 4);
-    __shared__ uint64_t lds[padded_size(N)];
-    const int tid = threadIdx.x, l = blockIdx.x;
+    constexpr int N = 1 << LOGN, NP = N >> PRE, NT = threads_for(LOGN - PRE, 4);
+    __shared__ uint64_t lds[padded_size(NP)];
+    const int tid = threadIdx.x, l = blockIdx.x >> PRE, h = blockIdx.x & ((1 << PRE) - 1);
     const RlweLimb &P = a.limb[l];
     const uint64_t q = P.red.q;
     Twiddle *const t = tables + (size_t)l * limb_table_entries(N);
-    for (int c = tid; c < N; c += NT) {
+    auto lifted = [&](int c) -> uint64_t {
         const int v = s[c];
-        lds[pad(c)] = v < 0 ? q - (uint64_t)(-v) : (uint64_t)v;
+        return v < 0 ? q - (uint64_t)(-v) : (uint64_t)v;
+    };
+    if constexpr (PRE == 0) {
+        for (int c = tid; c < N; c += NT) lds[pad(c)] = lifted(c);
+    } else {
+        const Twiddle w0 = t[1];                            // stage 0 has one block: entry 1
+        for (int c = tid; c < NP; c += NT)
+            lds[pad(c)] = enter_part<PRE>(lifted(c), lifted(c + NP), w0, q, h);
     }
     __syncthreads();
-    forward_only<LOGN, 4, 0, NT>(lds, t, q, tid);
-    for (int c = tid; c < N; c += NT) {
+    forward_only<LOGN, PRE, 4, PRE, NT>(lds, t, q, tid, h);
+    for (int c = tid; c < NP; c += NT) {
         uint64_t v = lds[pad(c)];               // [0, 4q)
         v = v >= 2 * q ? v - 2 * q : v;
         v = v >= q ? v - q : v;
         v = mulmod(v, P.n_inv, P.red);
-        t[2 * N + c] = Twiddle{v, companion(v, q)};
+        t[2 * N + h * NP + c] = Twiddle{v, companion(v, q)};
     }
 }
 
@@ -412,13 +451,43 @@ struct PolyArgs {
     RlweArgs limbs;
 };
 
-template <int LOGN, int MAXS, bool ENCRYPT>
-__global__ __launch_bounds__(threads_for(LOGN, MAXS)) void rlwe_poly_kernel(PolyArgs a)
+// what becomes of coefficient c of the product as = (c1 or a) * s, as < q
+__device__ __forceinline__ uint64_t finish_phase(uint64_t as, uint64_t c0, uint64_t q)
 {
-    constexpr int N = 1 << LOGN, NT = threads_for(LOGN, MAXS);
-    __shared__ uint64_t lds[padded_size(N)];
+    const uint64_t v = as + c0;
+    return v >= q ? v - q : v;
+}
+
+// Eq. (2) with chunking: coefficient c of chunk ch is column ch N + c, zero past n
+__device__ __forceinline__ uint64_t finish_encrypt(uint64_t as, const PolyArgs &a, const RlweLimb &P,
+                                                   uint32_t row, uint32_t c, int N)
+{
+    const uint64_t q = P.red.q;
+    const uint32_t i = row / (uint32_t)a.Ch, ch = row % (uint32_t)a.Ch;
+    const uint32_t col = ch * (uint32_t)N + c;
+    const uint64_t w = col < (uint32_t)a.n ? a.W[(size_t)i * a.n + col] : 0;
+    uint64_t v = barrett128(__umul64hi(P.delta, w), P.delta * w, P.red);       // w < t < q
+    const int ev = a.e[(size_t)row * N + c];
+    v += ev < 0 ? q - (uint64_t)(-ev) : (uint64_t)ev;
+    v += q - as;                                // < 3q
+    v = v >= q ? v - q : v;
+    return v >= q ? v - q : v;
+}
+
+// PRE = 0: the whole product and what follows it in one kernel.  PRE = 1 (ring of 2^15
+// coefficients): workgroup (polynomial, h) does part h: first forward stage on the way in,
+// stages 1 .. LOGN-1 and back in the LDS, and leaves its half of the not yet joined product
+// where the result will be (phi, or the c0 half of the ciphertext); rlwe_join_kernel does
+// the last inverse stage and what follows.
+template <int LOGN, int PRE, int MAXS, bool ENCRYPT>
+__global__ __launch_bounds__(threads_for(LOGN - PRE, MAXS)) void rlwe_poly_kernel(PolyArgs a)
+{
+    constexpr int N = 1 << LOGN, NP = N >> PRE, NT = threads_for(LOGN - PRE, MAXS);
+    __shared__ uint64_t lds[padded_size(NP)];
     const int tid = threadIdx.x;
-    const uint32_t row = blockIdx.x / (uint32_t)a.L, l = blockIdx.x % (uint32_t)a.L;
+    const uint32_t poly = blockIdx.x >> PRE;
+    const int h = (int)(blockIdx.x & ((1u << PRE) - 1u));
+    const uint32_t row = poly / (uint32_t)a.L, l = poly % (uint32_t)a.L;
     const RlweLimb &P = a.limbs.limb[l];
     const uint64_t q = P.red.q;
     const Twiddle *const t = a.tables + (size_t)l * limb_table_entries(N);
@@ -426,46 +495,67 @@ __global__ __launch_bounds__(threads_for(LOGN, MAXS)) void rlwe_poly_kernel(Poly
     const uint64_t *const mul_in =
         ENCRYPT ? a.src + ((size_t)row * a.L + l) * N
                 : a.src + (((size_t)row * 2 + 1) * a.L + l) * N;
-    if constexpr (ENCRYPT) {
-        // c1 = a, copied while a is on its way into the LDS (one read of a in all)
-        uint64_t *const c1 = a.dst + (((size_t)row * 2 + 1) * a.L + l) * N;
+    // where the result goes: phi[row][l], or c0 of ciphertext `row`
+    uint64_t *const out = ENCRYPT ? a.dst + (((size_t)row * 2 + 0) * a.L + l) * N
+                                  : a.dst + ((size_t)row * a.L + l) * N;
+    // c1 = a is copied while a is on its way into the LDS (one read of a in all)
+    uint64_t *const c1 = a.dst + (((size_t)row * 2 + 1) * a.L + l) * N;
+    if constexpr (PRE == 0) {
         for (int c = tid; c < N; c += NT) {
             const uint64_t v = mul_in[c];
             lds[pad(c)] = v;
-            c1[c] = v;
+            if constexpr (ENCRYPT) c1[c] = v;
         }
     } else {
-        for (int c = tid; c < N; c += NT) lds[pad(c)] = mul_in[c];
+        const Twiddle w0 = t[1];
+        for (int c = tid; c < NP; c += NT) {
+            const uint64_t u = mul_in[c], v = mul_in[c + NP];
+            lds[pad(c)] = enter_part<PRE>(u, v, w0, q, h);
+            if constexpr (ENCRYPT) c1[h * NP + c] = h == 0 ? u : v;
+        }
     }
-    multiply_by_secret<LOGN, MAXS, NT>(lds, t, t + N, t + 2 * N, q, tid);
-    if constexpr (!ENCRYPT) {
-        const uint64_t *const c0 = a.src + (((size_t)row * 2 + 0) * a.L + l) * N;
-        uint64_t *const phi = a.dst + ((size_t)row * a.L + l) * N;
-        for (int c = tid; c < N; c += NT) {
-            uint64_t v = lds[pad(c)];           // [0, 2q)
-            v = v >= q ? v - q : v;
-            v += c0[c];
-            phi[c] = v >= q ? v - q : v;
+    multiply_by_secret<LOGN, PRE, MAXS, NT>(lds, t, t + N, t + 2 * N, q, tid, h);
+    for (int c = tid; c < NP; c += NT) {
+        uint64_t as = lds[pad(c)];              // [0, 2q)
+        as = as >= q ? as - q : as;
+        if constexpr (PRE != 0) {
+            out[h * NP + c] = as;
+        } else if constexpr (ENCRYPT) {
+            out[c] = finish_encrypt(as, a, P, row, (uint32_t)c, N);
+        } else {
+            out[c] = finish_phase(as, a.src[(((size_t)row * 2 + 0) * a.L + l) * N + c], q);
         }
+    }
+}
+
+// Last inverse stage of a ring handled in two parts, in place on the two halves the part
+// kernels left in `out`: (u, v) -> (u + v, (u - v) psi^-brv(1)), then what follows the
+// product.  One thread per pair of coefficients N/2 apart.
+template <bool ENCRYPT>
+__global__ __launch_bounds__(256) void rlwe_join_kernel(PolyArgs a, int logN, uint64_t pairs)
+{
+    const uint64_t gid = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (gid >= pairs) return;
+    const int N = 1 << logN, NP = N >> 1;
+    const uint32_t poly = (uint32_t)(gid >> (logN - 1)), c = (uint32_t)(gid & (uint64_t)(NP - 1));
+    const uint32_t row = poly / (uint32_t)a.L, l = poly % (uint32_t)a.L;
+    const RlweLimb &P = a.limbs.limb[l];
+    const uint64_t q = P.red.q;
+    const Twiddle w0_inv = a.tables[(size_t)l * limb_table_entries(N) + N + 1];
+    uint64_t *const out = ENCRYPT ? a.dst + (((size_t)row * 2 + 0) * a.L + l) * N
+                                  : a.dst + ((size_t)row * a.L + l) * N;
+    const uint64_t u = out[c], v = out[c + NP];             // < q
+    uint64_t lo = u + v;
+    lo = lo >= q ? lo - q : lo;
+    uint64_t hi = mul_lazy(u + q - v, w0_inv, q);           // [0, 2q)
+    hi = hi >= q ? hi - q : hi;
+    if constexpr (ENCRYPT) {
+        out[c] = finish_encrypt(lo, a, P, row, c, N);
+        out[c + NP] = finish_encrypt(hi, a, P, row, c + NP, N);
     } else {
-        uint64_t *const c0 = a.dst + (((size_t)row * 2 + 0) * a.L + l) * N;
-        const uint32_t i = row / (uint32_t)a.Ch, ch = row % (uint32_t)a.Ch;
-        const uint64_t *const Wrow = a.W + (size_t)i * a.n;
-        const int8_t *const e = a.e + (size_t)row * N;
-        for (int c = tid; c < N; c += NT) {
-            uint64_t as = lds[pad(c)];          // [0, 2q)
-            as = as >= q ? as - q : as;
-            // Eq. (2) with chunking: coefficient c of chunk ch is column ch N + c, zero past n
-            const uint32_t col = ch * (uint32_t)N + (uint32_t)c;
-            const uint64_t w = col < (uint32_t)a.n ? Wrow[col] : 0;
-            uint64_t v = barrett128(__umul64hi(P.delta, w), P.delta * w, P.red);   // w < t < q
-            const int ev = e[c];
-            v += ev < 0 ? q - (uint64_t)(-ev) : (uint64_t)ev;
-            v += q - as;                        // < 3q
-            v = v >= q ? v - q : v;
-            v = v >= q ? v - q : v;
-            c0[c] = v;
-        }
+        const uint64_t *const c0 = a.src + (((size_t)row * 2 + 0) * a.L + l) * N;
+        out[c] = finish_phase(lo, c0[c], q);
+        out[c + NP] = finish_phase(hi, c0[c + NP], q);
     }
 }
 
@@ -794,7 +884,12 @@ static int scaling(int L, const uint64_t *moduli, int t_bits, Scaling *out)
 static hipError_t launch_secret(const RlweArgs &a, int logN, int L, const int8_t *s,
                                 Twiddle *tables, hipStream_t stream)
 {
-    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL(rlwe_secret_kernel<LOGN>, dim3((unsigned)L),
+    if (logN == 15) {
+        hipLaunchKernelGGL((rlwe_secret_kernel<15, 1>), dim3(2u * (unsigned)L),
+                           dim3(threads_for(14, 4)), 0, stream, a, s, tables);
+        return hipGetLastError();
+    }
+    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL((rlwe_secret_kernel<LOGN, 0>), dim3((unsigned)L),
                                                   dim3(threads_for(LOGN, 4)), 0, stream, a, s, tables));
     return hipGetLastError();
 }
@@ -802,9 +897,23 @@ static hipError_t launch_secret(const RlweArgs &a, int logN, int L, const int8_t
 template <bool ENCRYPT, int MAXS>
 static hipError_t launch_poly_with(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
 {
-    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL((rlwe_poly_kernel<LOGN, MAXS, ENCRYPT>),
+    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL((rlwe_poly_kernel<LOGN, 0, MAXS, ENCRYPT>),
                                                   dim3((unsigned)polys),
                                                   dim3(threads_for(LOGN, MAXS)), 0, stream, a));
+    return hipGetLastError();
+}
+
+// ring of 2^15 coefficients: two workgroups per polynomial, then the joining pass
+template <bool ENCRYPT>
+static hipError_t launch_poly_in_parts(const PolyArgs &a, size_t polys, hipStream_t stream)
+{
+    hipLaunchKernelGGL((rlwe_poly_kernel<15, 1, 4, ENCRYPT>), dim3(2u * (unsigned)polys),
+                       dim3(threads_for(14, 4)), 0, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const uint64_t pairs = (uint64_t)polys << 14;
+    hipLaunchKernelGGL(rlwe_join_kernel<ENCRYPT>, dim3((unsigned)((pairs + 255u) / 256u)), dim3(256), 0,
+                       stream, a, 15, pairs);
     return hipGetLastError();
 }
 
@@ -816,6 +925,7 @@ static hipError_t launch_poly_with(const PolyArgs &a, int logN, size_t polys, hi
 template <bool ENCRYPT>
 static hipError_t launch_poly(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
 {
+    if (logN == 15) return launch_poly_in_parts<ENCRYPT>(a, polys, stream);
 #ifdef NIMBUS_RLWE_FORCE_MAXS
     return launch_poly_with<ENCRYPT, NIMBUS_RLWE_FORCE_MAXS>(a, logN, polys, stream);
 #else
@@ -872,7 +982,7 @@ int nimbus_rlwe_phase(const uint64_t *ct, int T, int N, int L, const uint64_t *m
     PolyArgs a{};
     const int rc = rlwe_check(N, L, moduli, &a.limbs);
     if (rc != NIMBUS_COP_OK) return rc;
-    if ((unsigned long long)T * (unsigned)L >= (1ull << 31)) return NIMBUS_COP_ERR_INVALID_ARG;
+    if ((unsigned long long)T * (unsigned)L >= (1ull << 30)) return NIMBUS_COP_ERR_INVALID_ARG;
     if (T == 0) return NIMBUS_COP_OK;
     a.tables = (const Twiddle *)tables;
     a.L = L;
@@ -978,7 +1088,7 @@ int nimbus_rlwe_encrypt(const uint64_t *W, int k, int n, int t_bits, int N, int 
     if (rc != NIMBUS_COP_OK) return rc;
     const unsigned long long Ch = ((unsigned long long)n + (unsigned)N - 1) / (unsigned)N;
     const unsigned long long polys = (unsigned long long)k * Ch * (unsigned)L;
-    if (polys >= (1ull << 31) || Ch * (unsigned)N >= (1ull << 31)) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (polys >= (1ull << 30) || Ch * (unsigned)N >= (1ull << 31)) return NIMBUS_COP_ERR_INVALID_ARG;
     for (int l = 0; l < L; ++l) a.limbs.limb[l].delta = hw_mod(sc.delta, moduli[l]);
     a.tables = (const Twiddle *)tables;
     a.L = L;

@@ -165,7 +165,8 @@ def test_rlwe_argument_checks_on_the_host():
     assert nc.nimbus_rlwe_tables_bytes(N, L) == L * 3 * N * 16
     assert nc.nimbus_rlwe_tables_bytes(48, 1) == 0
     assert nc.nimbus_rlwe_tables_bytes(16, 1) == 0
-    assert nc.nimbus_rlwe_tables_bytes(32768, 1) == 0      # does not fit the local memory
+    assert nc.nimbus_rlwe_tables_bytes(32768, 1) == 3 * 32768 * 16
+    assert nc.nimbus_rlwe_tables_bytes(65536, 1) == 0
     assert nc.nimbus_rlwe_tables_bytes(64, 5) == 0
     big = nc.nimbus_rlwe_tables_bytes(N, L)
     # setup
@@ -175,7 +176,7 @@ def test_rlwe_argument_checks_on_the_host():
     assert lib.nimbus_rlwe_setup(48, L, mod, 0x2000, 0x1000, big, None) == -1
     assert lib.nimbus_rlwe_setup(N, L, mod, 0x2000, 0x1008, big, None) == -1       # alignment
     assert lib.nimbus_rlwe_setup(N, L, mod, 0x2000, 0x1000, big - 1, None) == -4
-    assert lib.nimbus_rlwe_setup(32768, L, mod, 0x2000, 0x1000, 1 << 30, None) == -2
+    assert lib.nimbus_rlwe_setup(65536, L, mod, 0x2000, 0x1000, 1 << 30, None) == -2
     # a modulus that is not 1 modulo 2N has no 2N-th root of unity
     bad = (ctypes.c_uint64 * 1)(97)                         # 96 is not a multiple of 128
     assert lib.nimbus_rlwe_setup(N, 1, bad, 0x2000, 0x1000, big, None) == -1

@@ -77,6 +77,8 @@ PHASE_SHAPES = [
     (8192, 3, 55, 350),      # config 5 ring, 1050 polynomials: 4 + 3 + 3 + 3
     (16384, 2, 61, 520),     # largest ring, 4 + 4 + 3 + 3, two groups per thread and round
     (1024, 1, 50, 1100),     # config 1 ring in a large batch: 2 stages per round
+    (32768, 2, 54, 2),       # ring that does not fit the LDS: two halves and a joining pass
+    (32768, 1, 62, 3),
 ]
 
 
@@ -147,6 +149,7 @@ DECRYPT_SHAPES = [
     (256, 4, 54, 20, 3),         # four limbs
     (512, 4, 62, 32, 2),         # four limbs of 62 bits: Q just below 2^248
     (64, 3, 30, 7, 3),           # three small limbs
+    (32768, 2, 55, 24, 2),       # largest ring
 ]
 
 
@@ -220,6 +223,7 @@ ENCRYPT_SHAPES = [
     (4, 100, 64, 2, 62, 32),         # 32-bit plaintexts, widest moduli, ragged chunks
     (3, 4096, 8192, 3, 55, 24),      # config 5 row with its three limbs
     (5, 200, 128, 4, 54, 20),        # four limbs, two chunks
+    (2, 40000, 32768, 2, 55, 24),    # largest ring, two chunks: the joining pass assembles c0
 ]
 
 
