@@ -7,7 +7,10 @@
 // One workgroup transforms one polynomial of one limb entirely inside the LDS:
 //   load -> forward rounds -> pointwise product with the transformed secret -> inverse
 //   rounds -> (add c0 | assemble c0) -> store,
-// so a product c1 * s costs one read of c1 and one write of the result in HBM.
+// so a product c1 * s costs one read of c1 and one write of the result in HBM.  (A ring of
+// 2^15 coefficients does not fit: two workgroups per polynomial take one half each, with
+// the first forward stage done on the way in and the last inverse stage in a pass of its
+// own; see Part below.)
 //
 // Transform (the usual in-place pair for X^N + 1, psi a primitive 2N-th root of unity):
 //   forward:  stages m = 1, 2, 4, ..., N/2 blocks; in block i of a stage every pair
