@@ -57,6 +57,14 @@ SMALL = [
     (12, 192, 64, 64, 1, 32, 62),       # 4 x 8 planes, six k-blocks
     (100, 1024, 64, 64, 1, 16, 50),     # 2 x 7 planes, 32 k-blocks
     (6, 50, 32, 32, 3, 20, 54),         # smallest ring with several limbs: a 64-column tile spans two limbs
+    # m a multiple of 128: the builds of the kernel without row tests, one per plane count
+    (128, 64, 64, 64, 1, 16, 50),       # 2 x 7
+    (128, 96, 64, 64, 2, 20, 54),       # 3 x 7, two limbs
+    (128, 70, 64, 64, 1, 32, 54),       # 4 x 7
+    (128, 64, 64, 64, 1, 16, 62),       # 2 x 8
+    (128, 65, 64, 64, 2, 24, 62),       # 3 x 8
+    (128, 64, 32, 32, 1, 32, 62),       # 4 x 8, smallest ring
+    (256, 100, 64, 64, 2, 20, 54),      # two full row blocks
 ]
 
 
