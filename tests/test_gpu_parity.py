@@ -344,6 +344,8 @@ WIDE = [
     (17, 70, 64, 64, 2, 48, (62, 55)),       # 48-bit shares: upper half has two planes
     (9, 33, 32, 32, 1, 33, (50,)),           # one bit above 32
     (32, 128, 8192, 8192, 2, 64, (59, 55)),  # the paper's ring degree and moduli, one chunk
+    (128, 64, 64, 64, 2, 64, (59, 55)),      # full row block: both passes in the build without row tests
+    (128, 40, 32, 32, 1, 40, (54,)),         # the same with a one-plane upper half
 ]
 
 
