@@ -134,7 +134,6 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
                                void *workspace, size_t workspace_bytes,
                                void *stream);
 
-/* static, NUL-terminated description of a status code */
 /*
  * Output packing (Algorithm 1 step 3; Appendix B.1 "Right Shift"; Section 3.2 "Output
  * Communication"): when n <= N/2 the payload of an output ciphertext fills only its
@@ -163,6 +162,24 @@ int nimbus_cop_pack(const uint64_t *rows, int m, int n, int N, int L,
                     const uint64_t *moduli,
                     const uint64_t *mask, uint64_t *packed, void *stream);
 
+/*
+ * Debugging aid for the value-range preconditions above, which the other entry points do
+ * not test (Section 2.1: shares are elements of Z_t; Appendix B.1: ciphertext polynomials
+ * have coefficients in Z_q): counts the words that break them.
+ *
+ *   X, ctW, mask  as for nimbus_cop_matmul (x_bits <= 64; mask may be NULL)
+ *   violations    device, 3 words, written:
+ *                 [0] entries of X that are >= 2^x_bits,
+ *                 [1] words of ctW that are >= the modulus of their limb,
+ *                 [2] words of mask that are >= the modulus of their limb (0 without mask)
+ * The counts are complete when the work enqueued on `stream` has finished.
+ */
+int nimbus_cop_check_inputs(const uint64_t *X, int m, int k, int x_bits,
+                            const uint64_t *ctW, int n, int N, int L,
+                            const uint64_t *moduli,
+                            const uint64_t *mask, uint64_t *violations, void *stream);
+
+/* static, NUL-terminated description of a status code */
 const char *nimbus_cop_strerror(int status);
 
 /* library version, major*10000 + minor*100 + patch */

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     nimbus_cop_matmul_prepared,
     nimbus_cop_matmul_staged,
     nimbus_cop_pack,
+    nimbus_cop_check_inputs,
     nimbus_cop_packed_count,
     nimbus_cop_stage_shares,
     nimbus_cop_prepare,

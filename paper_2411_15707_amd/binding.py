@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = (
     "nimbus_cop_matmul_prepared",
     "nimbus_cop_packed_count",
     "nimbus_cop_pack",
+    "nimbus_cop_check_inputs",
     "nimbus_cop_strerror",
     "nimbus_cop_version",
 )
@@ -93,6 +94,8 @@ def load_library():
     lib.nimbus_cop_packed_count.argtypes = [ci, ci, ci]
     lib.nimbus_cop_pack.restype = ci
     lib.nimbus_cop_pack.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
+    lib.nimbus_cop_check_inputs.restype = ci
+    lib.nimbus_cop_check_inputs.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.nimbus_calib_mfma_i8.restype = ctypes.c_longlong
     lib.nimbus_calib_mfma_i8.argtypes = [ci, ci, ci, vp, sz, vp]
     lib.nimbus_calib_stream_read.restype = ctypes.c_longlong
@@ -265,6 +268,22 @@ def nimbus_cop_pack(rows, m, n, N, L, moduli, mask, packed, stream=None):
                              _stream(stream))
     if rc != 0:
         raise NimbusCopError(rc, "nimbus_cop_pack")
+
+
+def nimbus_cop_check_inputs(X, m, k, x_bits, ctW, n, N, L, moduli, mask, violations, stream=None):
+    """violations: device tensor of 3 64-bit words (shares, ciphertext residues, mask residues)"""
+    lib = load_library()
+    C = _columns(n, N, L)
+    _words(X, "X", m * k)
+    _words(ctW, "ctW", k * C)
+    if mask is not None:
+        _words(mask, "mask", m * C)
+    _words(violations, "violations", 3)
+    rc = lib.nimbus_cop_check_inputs(_dev_ptr(X, "X"), m, k, x_bits, _dev_ptr(ctW, "ctW"), n, N, L,
+                                     _moduli(moduli), _dev_ptr(mask, "mask", True),
+                                     _dev_ptr(violations, "violations"), _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_check_inputs")
 
 
 def nimbus_calib_mfma_i8(workgroups, iters, random_operands, sink, stream=None) -> int:

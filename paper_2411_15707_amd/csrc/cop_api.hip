@@ -243,6 +243,19 @@ int nimbus_cop_pack(const uint64_t *rows, int m, int n, int N, int L,
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 
+int nimbus_cop_check_inputs(const uint64_t *X, int m, int k, int x_bits,
+                            const uint64_t *ctW, int n, int N, int L,
+                            const uint64_t *moduli,
+                            const uint64_t *mask, uint64_t *violations, void *stream)
+{
+    if (!X || !ctW || !violations) return NIMBUS_COP_ERR_INVALID_ARG;
+    Problem p;
+    const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
+    if (rc != NIMBUS_COP_OK) return rc;
+    const hipError_t e = launch_cop_check(p, X, ctW, mask, violations, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
 const char *nimbus_cop_strerror(int status)
 {
     switch (status) {
@@ -255,6 +268,6 @@ const char *nimbus_cop_strerror(int status)
     }
 }
 
-int nimbus_cop_version(void) { return 110; }
+int nimbus_cop_version(void) { return 120; }
 
 }  // extern "C"

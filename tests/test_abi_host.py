@@ -223,3 +223,13 @@ def test_loader_header_binding_and_argument_checks():
     assert lib.nimbus_loader_load(None, 0, 0x1000, 0x2000, 16, None) == -1
     assert lib.nimbus_loader_acquire(None, 0, None) == -1
     assert lib.nimbus_loader_release(None, 0, None) == -1
+
+
+def test_check_inputs_argument_checks():
+    lib = _raw()
+    mod = (ctypes.c_uint64 * 1)(*ci.limb_primes(50, 16, 1))
+    assert lib.nimbus_cop_check_inputs(0x1000, 4, 8, 16, 0x2000, 32, 32, 1, mod, None, None, None) == -1
+    assert lib.nimbus_cop_check_inputs(None, 4, 8, 16, 0x2000, 32, 32, 1, mod, None, 0x3000, None) == -1
+    assert lib.nimbus_cop_check_inputs(0x1000, 4, 8, 16, None, 32, 32, 1, mod, None, 0x3000, None) == -1
+    assert lib.nimbus_cop_check_inputs(0x1000, 0, 8, 16, 0x2000, 32, 32, 1, mod, None, 0x3000, None) == -1
+    assert lib.nimbus_cop_check_inputs(0x1000, 4, 8, 16, 0x2000, 32, 48, 1, mod, None, 0x3000, None) == -1

@@ -445,3 +445,39 @@ def test_random_parameter_sweep(oracle):
         if x_bits <= 32:
             got = gu.run_valu(X, ctW, moduli, n, N, x_bits, mask)
             assert np.array_equal(got, want), label + " valu: " + gu.first_mismatch(got, want)
+
+
+def test_check_inputs_counts_planted_violations():
+    """the debugging aid counts exactly the words that break the value-range preconditions:
+    shares >= 2^x_bits, residues >= the modulus of their own limb (a word between the two
+    moduli counts only in the columns of the smaller one)"""
+    import torch
+    import gpu_util as gu
+    import paper_2411_15707_amd as nc
+    m, k, n, N, L, t_bits = 20, 37, 100, 64, 2, 20
+    moduli = (ci.limb_primes(54, t_bits, 1)[0], ci.limb_primes(50, t_bits, 1)[0])
+    Ch = -(-n // N)
+    X, ctW, mask = _inputs(77, m, k, n, N, moduli, t_bits)
+    v = torch.full((3,), 123, dtype=torch.int64, device="cuda")
+    nc.nimbus_cop_check_inputs(gu.dev(X), m, k, t_bits, gu.dev(ctW), n, N, L, moduli, gu.dev(mask), v)
+    torch.cuda.synchronize()
+    assert v.tolist() == [0, 0, 0]
+    X = X.copy(); ctW = ctW.copy(); mask = mask.copy()
+    X[3, 5] = 1 << t_bits                       # one too many bits
+    X[19, 36] = (1 << 64) - 1
+    between = np.uint64(moduli[1] + 5)          # >= q_1, < q_0
+    ctW[0, 0, 0, 1, 0] = between                # limb 1: counts
+    ctW[7, 1, 1, 0, 63] = between               # limb 0: a valid residue
+    ctW[36, 1, 1, 0, 63] = np.uint64(moduli[0]) # exactly q_0: counts
+    ctW[2, 0, 1, 1, 17] = np.uint64((1 << 64) - 1)
+    mask[19, Ch - 1, 1, 1, 63] = np.uint64(moduli[1])
+    nc.nimbus_cop_check_inputs(gu.dev(X), m, k, t_bits, gu.dev(ctW), n, N, L, moduli, gu.dev(mask), v)
+    torch.cuda.synchronize()
+    assert v.tolist() == [2, 3, 1]
+    nc.nimbus_cop_check_inputs(gu.dev(X), m, k, t_bits, gu.dev(ctW), n, N, L, moduli, None, v)
+    torch.cuda.synchronize()
+    assert v.tolist() == [2, 3, 0]
+    # 64-bit shares: nothing can be out of range
+    nc.nimbus_cop_check_inputs(gu.dev(X), m, k, 64, gu.dev(ctW), n, N, L, moduli, None, v)
+    torch.cuda.synchronize()
+    assert v.tolist() == [0, 3, 0]
