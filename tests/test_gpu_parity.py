@@ -187,6 +187,27 @@ def test_bert_base_real_encryption_spot_check(oracle, cfg_id):
         assert np.array_equal(got[:cfg.n], (XW[r] % t).astype(np.uint64))
         assert (got[cfg.n:] == 0).all()
         assert np.abs(noise).max() <= cfg.k * t * 20
+    # the server side at this config's full size: the GPU encrypts the same rows with the
+    # same randomness (all k ciphertexts must equal the oracle's) and decrypts the output
+    # rows (the four sampled rows must equal the oracle's decryption)
+    import torch
+    import paper_2411_15707_amd as nc
+    _say(f"[parity] config {cfg_id} real encryption: server side on the GPU")
+    tables = torch.empty(nc.nimbus_rlwe_tables_bytes(cfg.N, cfg.L), dtype=torch.uint8, device="cuda")
+    nc.nimbus_rlwe_setup(cfg.N, cfg.L, cfg.moduli, torch.from_numpy(s).cuda(), tables)
+    ct_gpu = torch.empty((cfg.k, 1, 2, cfg.L, cfg.N), dtype=torch.int64, device="cuda")
+    nc.nimbus_rlwe_encrypt(gu.dev(W), cfg.k, cfg.n, cfg.t_bits, cfg.N, cfg.L, cfg.moduli, tables,
+                           gu.dev(a), torch.from_numpy(e).cuda(), ct_gpu)
+    torch.cuda.synchronize()
+    assert np.array_equal(gu.host(ct_gpu), ctW), "GPU encryption differs from the oracle's"
+    phi = torch.empty((cfg.m, cfg.L, cfg.N), dtype=torch.int64, device="cuda")
+    m_hat = torch.empty((cfg.m, cfg.N), dtype=torch.int64, device="cuda")
+    nc.nimbus_rlwe_decrypt(gu.dev(out[:, 0]), cfg.m, cfg.N, cfg.L, cfg.moduli, cfg.t_bits, tables,
+                           phi, m_hat)
+    torch.cuda.synchronize()
+    got_all = gu.host(m_hat)
+    for j in rows:
+        assert np.array_equal(got_all[j], oracle.decrypt(out[j, 0], s, cfg.moduli, cfg.t_bits))
 
 
 def test_config5_layer_stack_on_one_stream(oracle):
