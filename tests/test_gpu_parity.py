@@ -502,3 +502,33 @@ def test_check_inputs_counts_planted_violations():
     nc.nimbus_cop_check_inputs(gu.dev(X), m, k, 64, gu.dev(ctW), n, N, L, moduli, None, v)
     torch.cuda.synchronize()
     assert v.tolist() == [0, 3, 0]
+
+
+def test_concurrent_calls_on_two_streams(oracle):
+    """the library keeps no state between calls: two layers enqueued alternately on two
+    streams (own workspaces and outputs, the same prepared weights) both come out right"""
+    import torch
+    import gpu_util as gu
+    import paper_2411_15707_amd as nc
+    m, k, n, N, L, t_bits = 128, 192, 256, 256, 2, 20
+    moduli = ci.limb_primes(54, t_bits, L)
+    C = 2 * L * N
+    ctW = ci.gen_ctW_uniform(606, k, 1, moduli, N)
+    prepared = gu.prepare(ctW, moduli, n, N)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    Xs = [ci.gen_X(607 + i, m, k, t_bits) for i in range(2)]
+    masks = [ci.gen_mask_uniform(609 + i, m, 1, moduli, N) for i in range(2)]
+    dX = [gu.dev(x) for x in Xs]
+    dM = [gu.dev(x) for x in masks]
+    ws = [torch.empty(nc.nimbus_cop_workspace_bytes(m, k, t_bits), dtype=torch.uint8, device="cuda")
+          for _ in range(2)]
+    outs = [torch.zeros((m, C), dtype=torch.int64, device="cuda") for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(20):
+        for i in range(2):
+            nc.nimbus_cop_matmul_prepared(dX[i], m, k, t_bits, prepared, n, N, L, moduli, dM[i],
+                                          outs[i], ws[i], stream=streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        want = oracle.cop_ref(Xs[i], ctW, moduli, n, N, masks[i])[0]
+        assert np.array_equal(gu.host(outs[i]).reshape(want.shape), want), f"stream {i}"
