@@ -344,3 +344,50 @@ def test_whole_layer_on_the_gpu_three_limbs(oracle):
             assert np.array_equal(total[u * n:(u + 1) * n], want), (th, u)
         assert np.array_equal(share_server[th],
                               oracle.decrypt_rns(gu.host(packed)[th], s, moduli, t_bits))
+
+
+def test_random_parameter_sweep_server_side(oracle):
+    """sixty seeded random parameter sets (ring degree 32..1024, one to four limbs of different
+    sizes, plaintext widths 1..32 bits, one or two chunks): decryption of uniform ciphertexts
+    and encryption of random rows against the oracle"""
+    import torch
+    import gpu_util as gu
+    import paper_2411_15707_amd as nc
+    rng = np.random.default_rng(241115707)
+    for case in range(60):
+        N = int(rng.choice([32, 64, 128, 256, 512, 1024]))
+        L = int(rng.integers(1, 5))
+        t_bits = int(rng.integers(1, 33))
+        need = max(t_bits, N.bit_length())
+        moduli = []
+        while len(moduli) < L:
+            b = int(rng.integers(max(need + 6, 20), 63))
+            try:
+                q = ci.limb_primes(b, need, 1)[0]
+            except ValueError:
+                continue
+            if q not in moduli:
+                moduli.append(q)
+        moduli = tuple(moduli)
+        T = int(rng.integers(1, 6))
+        k, n = int(rng.integers(1, 4)), int(rng.integers(1, 2 * N + 1))
+        Ch = -(-n // N)
+        label = (f"sweep {case}: N={N} L={L} t_bits={t_bits} "
+                 f"q_bits={[q.bit_length() for q in moduli]} T={T} k={k} n={n}")
+        _say("[rlwe] " + label)
+        s = ci.gen_secret(50000 + case, N)
+        ct = ci.uniform_residues(50000 + case, 3, (T, 2), moduli, N)
+        tables = _tables(N, moduli, s)
+        m_hat, phi = _gpu_decrypt(ct, moduli, t_bits, tables)
+        for r in range(T):
+            assert np.array_equal(phi[r], oracle.phase(ct[r], s, moduli)), label
+            assert np.array_equal(m_hat[r], oracle.decrypt_rns(ct[r], s, moduli, t_bits)), label
+        W = ci.gen_W(50000 + case, k, n, t_bits)
+        a, e = ci.gen_enc_randomness(50000 + case, k, Ch, moduli, N)
+        ctW = torch.empty((k, Ch, 2, L, N), dtype=torch.int64, device="cuda")
+        nc.nimbus_rlwe_encrypt(gu.dev(W), k, n, t_bits, N, L, moduli, tables, gu.dev(a),
+                               torch.from_numpy(e).cuda(), ctW)
+        torch.cuda.synchronize()
+        want = oracle.encrypt_rns(oracle.encode_rows(W, N).reshape(k * Ch, N), s,
+                                  a.reshape(k * Ch, L, N), e.reshape(k * Ch, N), moduli, t_bits)
+        assert np.array_equal(gu.host(ctW).reshape(want.shape), want), label
