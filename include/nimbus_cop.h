@@ -44,7 +44,7 @@
  *
  * Accepted parameters: m, k, n >= 1; N a power of two in [32, 65536];
  * L in [1, 4]; x_bits in [1, 32] with every q_l odd and 2^x_bits < q_l < 2^62;
- * k < 2^24; Ch*2*L*N < 2^31.
+ * k < 2^24; m <= 2^30; Ch*2*L*N < 2^31.
  * Shares of 33 to 64 bits (the paper's own setting is l = 64, Section 5.1
  * "Experimental setup") are accepted by the prepared-weights entry points only
  * (nimbus_cop_workspace_bytes, nimbus_cop_stage_shares, nimbus_cop_matmul_staged,

@@ -23,7 +23,8 @@ static int make_problem(int m, int k, int x_bits, int n, int N, int L,
     if (k < 1 || n < 1 || k >= (1 << 24)) return NIMBUS_COP_ERR_INVALID_ARG;
     if (N < 32 || N > 65536 || (N & (N - 1)) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
     if (L < 1 || L > kMaxLimbs) return NIMBUS_COP_ERR_INVALID_ARG;
-    if (with_x && (m < 1 || x_bits < 1 || x_bits > 64)) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (with_x && (m < 1 || m > kMaxRows || x_bits < 1 || x_bits > 64))
+        return NIMBUS_COP_ERR_INVALID_ARG;
     Problem p{};
     p.m = with_x ? m : 0;
     p.k = k;
@@ -31,9 +32,10 @@ static int make_problem(int m, int k, int x_bits, int n, int N, int L,
     p.n = n;
     p.N = N;
     p.L = L;
-    p.Ch = (n + N - 1) / N;
-    const unsigned long long C = (unsigned long long)p.Ch * 2ull * (unsigned)L * (unsigned)N;
+    const unsigned long long Ch = ((unsigned long long)n + (unsigned)N - 1) / (unsigned)N;
+    const unsigned long long C = Ch * 2ull * (unsigned)L * (unsigned)N;
     if (C >= (1ull << 31)) return NIMBUS_COP_ERR_INVALID_ARG;
+    p.Ch = (int)Ch;
     p.C = (size_t)C;
     p.q_bits_max = 0;
     for (int l = 0; l < L; ++l) {
@@ -163,7 +165,7 @@ int nimbus_cop_prepare(const uint64_t *ctW, int k, int n, int N, int L,
 
 size_t nimbus_cop_workspace_bytes(int m, int k, int x_bits)
 {
-    if (m < 1 || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 64) return 0;
+    if (m < 1 || m > kMaxRows || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 64) return 0;
     return workspace_bytes_of(m, k, x_bits);
 }
 
@@ -171,7 +173,7 @@ int nimbus_cop_stage_shares(const uint64_t *X, int m, int k, int x_bits,
                             void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!X || !workspace || ((uintptr_t)workspace & 15u) != 0) return NIMBUS_COP_ERR_INVALID_ARG;
-    if (m < 1 || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 64)
+    if (m < 1 || m > kMaxRows || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 64)
         return NIMBUS_COP_ERR_INVALID_ARG;
     if (!staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
@@ -222,7 +224,8 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
 
 int nimbus_cop_packed_count(int m, int n, int N)
 {
-    if (m < 1 || n < 1 || N < 32 || N > 65536 || (N & (N - 1)) != 0 || n > N) return 0;
+    if (m < 1 || m > kMaxRows || n < 1 || N < 32 || N > 65536 || (N & (N - 1)) != 0 || n > N)
+        return 0;
     const int P = N / n;
     return (m + P - 1) / P;
 }
@@ -232,7 +235,7 @@ int nimbus_cop_pack(const uint64_t *rows, int m, int n, int N, int L,
                     const uint64_t *mask, uint64_t *packed, void *stream)
 {
     if (!rows || !packed || rows == packed) return NIMBUS_COP_ERR_INVALID_ARG;
-    if (m < 1) return NIMBUS_COP_ERR_INVALID_ARG;
+    if (m < 1 || m > kMaxRows) return NIMBUS_COP_ERR_INVALID_ARG;
     Problem p;
     const int rc = make_problem(0, 1, 0, n, N, L, moduli, false, &p);
     if (rc != NIMBUS_COP_OK) return rc;

@@ -7,6 +7,7 @@
 namespace nimbus {
 
 constexpr int kMaxLimbs = 4;
+constexpr int kMaxRows = 1 << 30;     // rows of X: keeps every rounded-up row count inside an int
 
 // Per-limb constants for the final reduction.  For a prime q with bit length b
 // (2^(b-1) < q < 2^b) the reduction below takes a value V < 2^(b+63) held as

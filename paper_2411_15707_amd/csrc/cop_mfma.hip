@@ -806,6 +806,9 @@ bool mfma_supported(const Problem &p)
     const long long pairs = DX < DQ ? DX : DQ;
     // |D_d| < 2^30 (zero padding of k adds nothing)
     if ((long long)p.k * pairs * 16384ll >= (1ll << 30)) return false;
+    // one workgroup per 128 x 64 output tile in a one-dimensional grid
+    const uint64_t workgroups = (uint64_t)(p.C / (2 * kTile)) * (uint64_t)((p.m + 127) / 128);
+    if (workgroups >= (1ull << 31)) return false;
     // the value reduced in the epilogue is below (2^(sh+1) + 2^33 + 1) * q (the second
     // 2^32 q: the previous pass of a wide share); the floating-point quotient needs it
     // below 2^47 * q

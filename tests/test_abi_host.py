@@ -52,6 +52,11 @@ def test_size_queries():
     assert nc.nimbus_cop_workspace_bytes(33, 65, 16) == 2 * 3 * 2 * 1024
     assert nc.nimbus_cop_prepared_bytes(0, 8, 32, 1, (97,)) == 0
     assert nc.nimbus_cop_workspace_bytes(0, 8, 16) == 0
+    # sizes whose rounding up would leave the range of an int are refused, not wrapped
+    assert nc.nimbus_cop_workspace_bytes(2**31 - 1, 64, 20) == 0
+    assert nc.nimbus_cop_workspace_bytes(1 << 30, 64, 20) == (1 << 25) * 2 * 3 * 1024
+    assert nc.nimbus_cop_prepared_bytes(4, 2**31 - 1, 65536, 1, (cfg.moduli[0],)) == 0
+    assert nc.nimbus_cop_packed_count(2**31 - 1, 4, 32) == 0
 
 
 def _raw():
@@ -63,7 +68,8 @@ def _raw():
     dict(m=0), dict(k=0), dict(n=0), dict(N=48), dict(N=16), dict(N=1 << 17), dict(L=0), dict(L=5),
     dict(x_bits=0), dict(x_bits=65), dict(moduli=(1 << 54,)), dict(moduli=((1 << 62) + 1,)),
     dict(moduli=(65537,), x_bits=20), dict(X=None), dict(ctW=None), dict(out=None),
-    dict(moduli=None),
+    dict(moduli=None), dict(m=(1 << 30) + 1), dict(m=2**31 - 1), dict(n=2**31 - 1),
+    dict(n=2**31 - 1, N=65536),
 ])
 def test_invalid_arguments_are_rejected_on_the_host(kw):
     """every bad call returns INVALID_ARG without touching the (dummy, never dereferenced) pointers"""
