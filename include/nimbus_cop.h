@@ -32,7 +32,9 @@
  * the caller; `moduli` is a HOST pointer read during the call.  The library
  * never allocates, frees or synchronises: work is enqueued on `stream`
  * (a hipStream_t; NULL = the default stream) and the call returns at once.
- * `out` must not overlap any input.  Calls are re-entrant; calls that share a
+ * `out` (and `workspace`, `prepared`, `packed` where they are written) must not overlap any
+ * other buffer of the call: checked on the host from the sizes, NIMBUS_COP_ERR_INVALID_ARG.
+ * Calls are re-entrant; calls that share a
  * workspace must be ordered on one stream.
  *
  * Preconditions on device data (not checked): X[j][i] < 2^x_bits,

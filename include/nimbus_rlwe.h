@@ -39,6 +39,8 @@
  *     decoding and encryption;
  *   - nothing is allocated, freed or synchronised; all work is enqueued on `stream`
  *     (a hipStream_t, NULL = the default stream); on any error nothing is enqueued;
+ *   - a buffer that is written must not overlap a buffer that is read (checked on the host from
+ *     the sizes: NIMBUS_COP_ERR_INVALID_ARG);
  *   - residues handed in must be canonical (in [0, q_l)); residues written are canonical;
  *   - re-entrant; concurrent calls on different streams are allowed as long as their
  *     outputs do not overlap.

@@ -71,6 +71,14 @@ static bool staging_fits(int m, int k)
     return RT * KB <= (1ull << 23);
 }
 
+// byte ranges [a, a + na) and [b, b + nb) share a byte (a null pointer or an empty range shares none)
+static bool overlaps(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (!a || !b || na == 0 || nb == 0) return false;
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
 // Shares of more than 32 bits are staged as two halves: the lower 32 bits first (4 byte
 // planes), then the upper x_bits - 32 bits.
 static size_t half_bytes(int m, int k, int half_bits)
@@ -138,6 +146,11 @@ int nimbus_cop_matmul(const uint64_t *X, int m, int k, int x_bits,
     const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
     if (rc != NIMBUS_COP_OK) return rc;
     if (x_bits > 32) return NIMBUS_COP_ERR_UNSUPPORTED;    // wide shares: prepared path only
+    const size_t out_bytes = (size_t)m * p.C * sizeof(uint64_t);
+    if (overlaps(out, out_bytes, X, (size_t)m * (size_t)k * sizeof(uint64_t)) ||
+        overlaps(out, out_bytes, ctW, (size_t)k * p.C * sizeof(uint64_t)) ||
+        overlaps(out, out_bytes, mask, out_bytes))
+        return NIMBUS_COP_ERR_INVALID_ARG;
     const hipError_t e = launch_cop_valu(p, X, ctW, mask, out, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
@@ -159,6 +172,8 @@ int nimbus_cop_prepare(const uint64_t *ctW, int k, int n, int N, int L,
     const int rc = make_problem(0, k, 0, n, N, L, moduli, false, &p);
     if (rc != NIMBUS_COP_OK) return rc;
     if (prepared_bytes < prepared_bytes_of(p)) return NIMBUS_COP_ERR_BUFFER_SIZE;
+    if (overlaps(prepared, prepared_bytes_of(p), ctW, (size_t)k * p.C * sizeof(uint64_t)))
+        return NIMBUS_COP_ERR_INVALID_ARG;
     const hipError_t e = launch_prepare(p, ctW, prepared, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
@@ -177,6 +192,8 @@ int nimbus_cop_stage_shares(const uint64_t *X, int m, int k, int x_bits,
         return NIMBUS_COP_ERR_INVALID_ARG;
     if (!staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
+    if (overlaps(workspace, workspace_bytes_of(m, k, x_bits), X, (size_t)m * (size_t)k * sizeof(uint64_t)))
+        return NIMBUS_COP_ERR_INVALID_ARG;
     Problem p{};
     p.m = m;
     p.k = k;
@@ -197,6 +214,11 @@ int nimbus_cop_matmul_staged(const void *staged_shares, int m, int k, int x_bits
     const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
     if (rc != NIMBUS_COP_OK) return rc;
     if (!prepared_path_supported(p)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    const size_t out_bytes = (size_t)m * p.C * sizeof(uint64_t);
+    if (overlaps(out, out_bytes, staged_shares, workspace_bytes_of(m, k, x_bits)) ||
+        overlaps(out, out_bytes, prepared, prepared_bytes_of(p)) ||
+        overlaps(out, out_bytes, mask, out_bytes))
+        return NIMBUS_COP_ERR_INVALID_ARG;
     const hipError_t e = matmul_all(p, staged_shares, prepared, mask, out, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
@@ -216,6 +238,18 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
     if (rc != NIMBUS_COP_OK) return rc;
     if (!prepared_path_supported(p) || !staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
+    {
+        // both written buffers against everything that is read, and against each other
+        const size_t out_bytes = (size_t)m * p.C * sizeof(uint64_t);
+        const size_t ws_bytes = workspace_bytes_of(m, k, x_bits);
+        const size_t x_bytes = (size_t)m * (size_t)k * sizeof(uint64_t);
+        if (overlaps(out, out_bytes, X, x_bytes) || overlaps(out, out_bytes, mask, out_bytes) ||
+            overlaps(out, out_bytes, prepared, prepared_bytes_of(p)) ||
+            overlaps(out, out_bytes, workspace, ws_bytes) ||
+            overlaps(workspace, ws_bytes, X, x_bytes) || overlaps(workspace, ws_bytes, mask, out_bytes) ||
+            overlaps(workspace, ws_bytes, prepared, prepared_bytes_of(p)))
+            return NIMBUS_COP_ERR_INVALID_ARG;
+    }
     hipError_t e = stage_all(p, X, workspace, (hipStream_t)stream);
     if (e != hipSuccess) return NIMBUS_COP_ERR_LAUNCH;
     e = matmul_all(p, workspace, prepared, mask, out, (hipStream_t)stream);
@@ -241,6 +275,13 @@ int nimbus_cop_pack(const uint64_t *rows, int m, int n, int N, int L,
     if (rc != NIMBUS_COP_OK) return rc;
     if (n > N) return NIMBUS_COP_ERR_UNSUPPORTED;          // several ring chunks: nothing to pack
     if (nimbus_cop_packed_count(m, n, N) > 65535) return NIMBUS_COP_ERR_UNSUPPORTED;   // grid limit
+    {
+        const size_t ct_bytes = 2u * (size_t)L * (size_t)N * sizeof(uint64_t);    // one ciphertext
+        const size_t packed_bytes = (size_t)nimbus_cop_packed_count(m, n, N) * ct_bytes;
+        if (overlaps(packed, packed_bytes, rows, (size_t)m * ct_bytes) ||
+            overlaps(packed, packed_bytes, mask, packed_bytes))
+            return NIMBUS_COP_ERR_INVALID_ARG;
+    }
     p.m = m;
     const hipError_t e = launch_cop_pack(p, rows, mask, packed, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
@@ -271,6 +312,6 @@ const char *nimbus_cop_strerror(int status)
     }
 }
 
-int nimbus_cop_version(void) { return 120; }
+int nimbus_cop_version(void) { return 121; }
 
 }  // extern "C"

@@ -770,6 +770,14 @@ static int bit_length64(uint64_t v)
 }
 
 // shape and modulus checks shared by every entry point; fills the reduction constants
+// byte ranges [a, a + na) and [b, b + nb) share a byte
+static bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (!a || !b || na == 0 || nb == 0) return false;
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
 static int rlwe_check(int N, int L, const uint64_t *moduli, RlweArgs *out)
 {
     if (!moduli) return NIMBUS_COP_ERR_INVALID_ARG;
@@ -987,6 +995,11 @@ int nimbus_rlwe_phase(const uint64_t *ct, int T, int N, int L, const uint64_t *m
     if (rc != NIMBUS_COP_OK) return rc;
     if ((unsigned long long)T * (unsigned)L >= (1ull << 30)) return NIMBUS_COP_ERR_INVALID_ARG;
     if (T == 0) return NIMBUS_COP_OK;
+    {
+        const size_t poly_bytes = (size_t)L * (size_t)N * sizeof(uint64_t);
+        if (ranges_overlap(phi, (size_t)T * poly_bytes, ct, 2u * (size_t)T * poly_bytes))
+            return NIMBUS_COP_ERR_INVALID_ARG;
+    }
     a.tables = (const Twiddle *)tables;
     a.L = L;
     a.src = ct;
@@ -1015,6 +1028,8 @@ int nimbus_rlwe_decode(const uint64_t *phi, int T, int N, int L, const uint64_t 
             if (inv[i][j] == 0) return NIMBUS_COP_ERR_INVALID_ARG;
         }
     if (T == 0) return NIMBUS_COP_OK;
+    if (ranges_overlap(m_hat, (size_t)total * sizeof(uint64_t), phi, (size_t)total * (size_t)L * sizeof(uint64_t)))
+        return NIMBUS_COP_ERR_INVALID_ARG;
     const dim3 grid((unsigned)((total + 255u) / 256u));
     if (L <= 2) {
         DecodeArgs a{};
@@ -1072,6 +1087,12 @@ int nimbus_rlwe_decrypt(const uint64_t *ct, int T, int N, int L, const uint64_t 
     for (int j = 1; j < L; ++j)
         for (int i = 0; i < j; ++i)
             if (h_invmod(moduli[i] % moduli[j], moduli[j]) == 0) return NIMBUS_COP_ERR_INVALID_ARG;
+    {
+        const size_t words = (size_t)T * (size_t)N;
+        if (ranges_overlap(m_hat, words * sizeof(uint64_t), ct, 2u * words * (size_t)L * sizeof(uint64_t)) ||
+            ranges_overlap(m_hat, words * sizeof(uint64_t), phi, words * (size_t)L * sizeof(uint64_t)))
+            return NIMBUS_COP_ERR_INVALID_ARG;
+    }
     rc = nimbus_rlwe_phase(ct, T, N, L, moduli, tables, phi, stream);
     if (rc != NIMBUS_COP_OK) return rc;
     return nimbus_rlwe_decode(phi, T, N, L, moduli, t_bits, m_hat, stream);
@@ -1092,6 +1113,14 @@ int nimbus_rlwe_encrypt(const uint64_t *W, int k, int n, int t_bits, int N, int 
     const unsigned long long Ch = ((unsigned long long)n + (unsigned)N - 1) / (unsigned)N;
     const unsigned long long polys = (unsigned long long)k * Ch * (unsigned)L;
     if (polys >= (1ull << 30) || Ch * (unsigned)N >= (1ull << 31)) return NIMBUS_COP_ERR_INVALID_ARG;
+    {
+        const size_t rows = (size_t)k * (size_t)Ch;
+        const size_t ct_bytes = rows * 2u * (size_t)L * (size_t)N * sizeof(uint64_t);
+        if (ranges_overlap(ctW, ct_bytes, W, (size_t)k * (size_t)n * sizeof(uint64_t)) ||
+            ranges_overlap(ctW, ct_bytes, a_poly, ct_bytes / 2) ||
+            ranges_overlap(ctW, ct_bytes, e, rows * (size_t)N))
+            return NIMBUS_COP_ERR_INVALID_ARG;
+    }
     for (int l = 0; l < L; ++l) a.limbs.limb[l].delta = hw_mod(sc.delta, moduli[l]);
     a.tables = (const Twiddle *)tables;
     a.L = L;

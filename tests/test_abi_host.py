@@ -239,3 +239,40 @@ def test_check_inputs_argument_checks():
     assert lib.nimbus_cop_check_inputs(0x1000, 4, 8, 16, None, 32, 32, 1, mod, None, 0x3000, None) == -1
     assert lib.nimbus_cop_check_inputs(0x1000, 0, 8, 16, 0x2000, 32, 32, 1, mod, None, 0x3000, None) == -1
     assert lib.nimbus_cop_check_inputs(0x1000, 4, 8, 16, 0x2000, 32, 48, 1, mod, None, 0x3000, None) == -1
+
+
+def test_overlapping_buffers_are_rejected_on_the_host():
+    """a written buffer that shares a byte with a buffer that is read: INVALID_ARG, nothing enqueued
+    (dummy addresses, never dereferenced: every call returns before a launch)"""
+    lib = _raw()
+    mod = (ctypes.c_uint64 * 1)(*ci.limb_primes(54, 20, 1))
+    m, k, n, N, L = 4, 64, 32, 32, 1                     # X: 2 KiB, ctW: 32 KiB, out / mask: 2 KiB
+    X, W, MK, OUT = 0x100000, 0x200000, 0x300000, 0x400000
+    assert lib.nimbus_cop_matmul(X, m, k, 20, W, n, N, L, mod, MK, X + 0x7f8, None) == -1      # last word of X
+    assert lib.nimbus_cop_matmul(X, m, k, 20, W, n, N, L, mod, MK, W + 0x7000, None) == -1     # inside ctW
+    assert lib.nimbus_cop_matmul(X, m, k, 20, W, n, N, L, mod, MK, MK, None) == -1             # out = mask
+    prep = nc.nimbus_cop_prepared_bytes(k, n, N, L, tuple(mod))
+    wsb = nc.nimbus_cop_workspace_bytes(m, k, 20)
+    PREP, WS = 0x500000, 0x600000
+    args = lambda out, ws, prepared=PREP, mask=MK: (X, m, k, 20, prepared, n, N, L, mod, mask, out, ws, wsb, None)
+    assert lib.nimbus_cop_matmul_prepared(*args(PREP + prep - 16, WS)) == -1                  # out in prepared
+    assert lib.nimbus_cop_matmul_prepared(*args(OUT, OUT + 0x400)) == -1                      # workspace in out
+    assert lib.nimbus_cop_matmul_prepared(*args(OUT, X)) == -1                                # workspace = X
+    assert lib.nimbus_cop_matmul_staged(WS, m, k, 20, PREP, n, N, L, mod, MK, WS, None) == -1  # out = staged shares
+    assert lib.nimbus_cop_prepare(W, k, n, N, L, mod, W + 0x1000, prep, None) == -1
+    assert lib.nimbus_cop_stage_shares(X, m, k, 20, X + 0x400, wsb, None) == -1
+    # packing: 4 rows of n = 16 columns into one ciphertext of N = 64 (1 KiB each)
+    assert lib.nimbus_cop_pack(X, 4, 16, 64, 1, mod, None, X + 0xc00, None) == -1              # packed = last row
+    assert lib.nimbus_cop_pack(X, 4, 16, 64, 1, mod, MK, MK + 8, None) == -1                   # packed in mask
+    # server side
+    N2, L2 = 64, 2
+    mod2 = (ctypes.c_uint64 * L2)(*ci.limb_primes(54, 20, L2))
+    TAB, CT, PHI, MH = 0x700000, 0x800000, 0x900000, 0xa00000     # ct: 2 KiB per ciphertext, phi 1 KiB
+    assert lib.nimbus_rlwe_phase(CT, 2, N2, L2, mod2, TAB, CT + 0x800, None) == -1             # phi = second ciphertext
+    assert lib.nimbus_rlwe_decode(PHI, 2, N2, L2, mod2, 20, PHI + 0x400, None) == -1
+    assert lib.nimbus_rlwe_decrypt(CT, 2, N2, L2, mod2, 20, TAB, PHI, CT, None) == -1          # m_hat = ct
+    assert lib.nimbus_rlwe_decrypt(CT, 2, N2, L2, mod2, 20, TAB, PHI, PHI + 8, None) == -1     # m_hat in phi
+    Wp, A, E, CW = 0xb00000, 0xc00000, 0xd00000, 0xe00000
+    assert lib.nimbus_rlwe_encrypt(Wp, 4, 8, 20, N2, L2, mod2, TAB, A, E, A + 0x800, None) == -1   # ctW in a
+    assert lib.nimbus_rlwe_encrypt(Wp, 4, 8, 20, N2, L2, mod2, TAB, A, E, Wp, None) == -1          # ctW = W
+    assert lib.nimbus_rlwe_encrypt(Wp, 4, 8, 20, N2, L2, mod2, TAB, A, E, E, None) == -1           # ctW = e
