@@ -263,8 +263,10 @@ def main():
         p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         p0.record(stream)
+        h0 = time.perf_counter()
         for s in range(args.steps):
             nc.nimbus_cop_pack(outs[s % R], m, cfg.n, N, L, moduli, pmask[s % R], packed[s % R])
+        pack_host_us = (time.perf_counter() - h0) * 1e6 / args.steps
         p1.record(stream)
         torch.cuda.synchronize()
         pack_ms = p0.elapsed_time(p1) / args.steps
@@ -274,6 +276,7 @@ def main():
             "rows_per_ciphertext": P,
             "packed_ciphertexts": T,
             "kernel_ms_avg": round(pack_ms, 5),
+            "host_enqueue_us_per_call": round(pack_host_us, 2),
             "algorithmic_bytes_per_launch": pack_bytes,
             "achieved_gbps": round(pack_bytes / (pack_ms * 1e-3) / 1e9, 1),
             "frac_of_hbm_peak": round(pack_bytes / (pack_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
