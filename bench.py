@@ -237,6 +237,28 @@ def main():
         "mfma_int8_frac_of_peak": round(i8_tops / INT8_PEAK_TOPS, 4),
     })
 
+    # the kernel alone with its launches dealt alternately to the two streams
+    if two_streams is not None:
+        S = two_streams["streams"]
+        Rs = R - R % S
+
+        def run_kernel(count):
+            for s in range(count):
+                r = s % Rs
+                nc.nimbus_cop_matmul_staged(staged[r], m, k, xb, preps[r], n, N, L, moduli, masks[r],
+                                            outs[r], stream=streams[r % S])
+
+        run_kernel(max(Rs, args.warmup // 2))
+        torch.cuda.synchronize()
+        launches2 = max(Rs, args.steps // 2)
+        q0 = time.perf_counter()
+        run_kernel(launches2)
+        torch.cuda.synchronize()
+        k2 = (time.perf_counter() - q0) * 1e3 / launches2
+        two_streams["kernel_only_ms_per_launch"] = round(k2, 5)
+        two_streams["kernel_only_hbm_gbps"] = round(alg_bytes / (k2 * 1e-3) / 1e9, 1)
+        two_streams["kernel_only_frac_of_hbm_peak"] = round(alg_bytes / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+
     # ---- the canonical-layout vector-ALU entry point on the same workload, for reference ----
     dW0 = dev(first[1])
     for _ in range(2):
