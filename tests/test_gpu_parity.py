@@ -65,6 +65,11 @@ SMALL = [
     (128, 65, 64, 64, 2, 24, 62),       # 3 x 8
     (128, 64, 32, 32, 1, 32, 62),       # 4 x 8, smallest ring
     (256, 100, 64, 64, 2, 20, 54),      # two full row blocks
+    # the ends of the accepted ranges
+    (6, 50, 64, 64, 4, 20, 54),         # four limbs
+    (3, 33, 32768, 32768, 2, 20, 54),   # the paper's largest ring degree
+    (4, 40, 65536, 65536, 1, 20, 54),   # the largest ring degree the client side accepts
+    (2, 34, 70000, 65536, 1, 16, 50),   # two chunks of the largest ring, the second nearly empty
 ]
 
 
