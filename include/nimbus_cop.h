@@ -68,6 +68,7 @@ extern "C" {
 #define NIMBUS_COP_ERR_UNSUPPORTED   (-2)  /* valid, but outside what this entry point handles  */
 #define NIMBUS_COP_ERR_LAUNCH        (-3)  /* the HIP runtime refused a launch                  */
 #define NIMBUS_COP_ERR_BUFFER_SIZE   (-4)  /* prepared / workspace buffer smaller than required */
+#define NIMBUS_COP_ERR_STATIC_LIMIT  (-5)  /* shares exceed the built-in workspace (see below)  */
 
 /*
  * COP accumulation + mask on the canonical layout (Algorithm 1 step 2 + step 4).
@@ -135,6 +136,28 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
                                const uint64_t *mask, uint64_t *out,
                                void *workspace, size_t workspace_bytes,
                                void *stream);
+
+/*
+ * nimbus_cop_matmul_prepared for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments
+ * without `workspace`, same result bit for bit.  The byte planes of X go to a buffer of
+ * NIMBUS_COP_STATIC_WORKSPACE_BYTES that is part of the library's device image (each GPU
+ * the library runs on holds one copy until the process ends); the call allocates and frees
+ * nothing.  The device of `stream` must be the current device of the calling thread.
+ *   NIMBUS_COP_ERR_STATIC_LIMIT  nimbus_cop_workspace_bytes(m, k, x_bits) exceeds the
+ *                                built-in buffer (nothing is enqueued); use
+ *                                nimbus_cop_matmul_prepared with a workspace of your own.
+ * All calls on one GPU share that buffer: calls that may overlap in time (different
+ * streams, or different threads without ordering) race on it and must use
+ * nimbus_cop_matmul_prepared with separate workspaces instead.  Nothing in it has to be
+ * cleared between calls: every byte a call reads it has written first.
+ */
+#define NIMBUS_COP_STATIC_WORKSPACE_BYTES (8u << 20)
+int nimbus_cop_matmul_prepared_static(const uint64_t *X, int m, int k, int x_bits,
+                                      const void *prepared, int n, int N, int L,
+                                      const uint64_t *moduli,
+                                      const uint64_t *mask, uint64_t *out,
+                                      void *stream);
 
 /*
  * Output packing (Algorithm 1 step 3; Appendix B.1 "Right Shift"; Section 3.2 "Output

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     load_library,
     nimbus_cop_matmul,
     nimbus_cop_matmul_prepared,
+    nimbus_cop_matmul_prepared_static,
     nimbus_cop_matmul_staged,
     nimbus_cop_pack,
     nimbus_cop_check_inputs,

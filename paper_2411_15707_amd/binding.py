@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = (
     "nimbus_cop_stage_shares",
     "nimbus_cop_matmul_staged",
     "nimbus_cop_matmul_prepared",
+    "nimbus_cop_matmul_prepared_static",
     "nimbus_cop_packed_count",
     "nimbus_cop_pack",
     "nimbus_cop_check_inputs",
@@ -90,6 +91,8 @@ def load_library():
     lib.nimbus_cop_matmul_staged.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.nimbus_cop_matmul_prepared.restype = ci
     lib.nimbus_cop_matmul_prepared.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    lib.nimbus_cop_matmul_prepared_static.restype = ci
+    lib.nimbus_cop_matmul_prepared_static.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.nimbus_cop_packed_count.restype = ci
     lib.nimbus_cop_packed_count.argtypes = [ci, ci, ci]
     lib.nimbus_cop_pack.restype = ci
@@ -249,6 +252,22 @@ def nimbus_cop_matmul_prepared(X, m, k, x_bits, prepared, n, N, L, moduli, mask,
         _dev_ptr(workspace, "workspace"), ws_bytes, _stream(stream))
     if rc != 0:
         raise NimbusCopError(rc, "nimbus_cop_matmul_prepared")
+
+
+def nimbus_cop_matmul_prepared_static(X, m, k, x_bits, prepared, n, N, L, moduli, mask, out,
+                                      stream=None):
+    """nimbus_cop_matmul_prepared on the library's built-in share workspace (no allocation)"""
+    lib = load_library()
+    C = _columns(n, N, L)
+    _words(X, "X", m * k)
+    _words(out, "out", m * C)
+    if mask is not None:
+        _words(mask, "mask", m * C)
+    rc = lib.nimbus_cop_matmul_prepared_static(
+        _dev_ptr(X, "X"), m, k, x_bits, _dev_ptr(prepared, "prepared"), n, N, L,
+        _moduli(moduli), _dev_ptr(mask, "mask", True), _dev_ptr(out, "out"), _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_matmul_prepared_static")
 
 
 def nimbus_cop_packed_count(m, n, N) -> int:

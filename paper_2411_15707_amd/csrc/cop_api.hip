@@ -2,8 +2,34 @@
 // Declarations and the contract of every entry point: include/nimbus_cop.h.
 #include "cop_common.hpp"
 #include "../../include/nimbus_cop.h"
+#include <mutex>
 
 namespace nimbus {
+
+// Share workspace of nimbus_cop_matmul_prepared_static: device memory that is part of the
+// loaded code object, so the entry point needs no allocation.  Every GPU the library runs
+// on holds its own copy at its own address until the process ends.
+static __device__ __align__(256) unsigned char scratch[NIMBUS_COP_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void *scratch_ptr[kMaxDevices];          // device address of `scratch`, per device
+
+// Device address of this device's copy of `scratch` (the array's name in host code is only a
+// handle for the runtime, not an address a kernel could use).  Looked up once per device, with
+// that device current.
+static void *scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        scratch_ptr[dev] = ptr;
+    }
+    return scratch_ptr[dev];
+}
 
 static int bit_length(uint64_t v)
 {
@@ -223,21 +249,29 @@ int nimbus_cop_matmul_staged(const void *staged_shares, int m, int k, int x_bits
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 
-int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
-                               const void *prepared, int n, int N, int L,
-                               const uint64_t *moduli,
-                               const uint64_t *mask, uint64_t *out,
-                               void *workspace, size_t workspace_bytes,
-                               void *stream)
+// shared by the two entry points that stage and multiply in one call
+static int matmul_prepared_impl(const uint64_t *X, int m, int k, int x_bits,
+                                const void *prepared, int n, int N, int L,
+                                const uint64_t *moduli,
+                                const uint64_t *mask, uint64_t *out,
+                                void *workspace, size_t workspace_bytes, bool use_static,
+                                void *stream)
 {
-    if (!X || !prepared || !out || !workspace) return NIMBUS_COP_ERR_INVALID_ARG;
+    // use_static: the workspace is the library's own buffer; its address is looked up only
+    // after every check that needs no device has passed
+    if (!X || !prepared || !out || (!use_static && !workspace)) return NIMBUS_COP_ERR_INVALID_ARG;
     if ((((uintptr_t)prepared | (uintptr_t)workspace) & 15u) != 0)
         return NIMBUS_COP_ERR_INVALID_ARG;
     Problem p;
     const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
     if (rc != NIMBUS_COP_OK) return rc;
     if (!prepared_path_supported(p) || !staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
-    if (workspace_bytes < workspace_bytes_of(m, k, x_bits)) return NIMBUS_COP_ERR_BUFFER_SIZE;
+    if (workspace_bytes < workspace_bytes_of(m, k, x_bits))
+        return use_static ? NIMBUS_COP_ERR_STATIC_LIMIT : NIMBUS_COP_ERR_BUFFER_SIZE;
+    if (use_static) {
+        workspace = scratch_of_current_device();
+        if (!workspace) return NIMBUS_COP_ERR_LAUNCH;
+    }
     {
         // both written buffers against everything that is read, and against each other
         const size_t out_bytes = (size_t)m * p.C * sizeof(uint64_t);
@@ -254,6 +288,27 @@ int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
     if (e != hipSuccess) return NIMBUS_COP_ERR_LAUNCH;
     e = matmul_all(p, workspace, prepared, mask, out, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+int nimbus_cop_matmul_prepared(const uint64_t *X, int m, int k, int x_bits,
+                               const void *prepared, int n, int N, int L,
+                               const uint64_t *moduli,
+                               const uint64_t *mask, uint64_t *out,
+                               void *workspace, size_t workspace_bytes,
+                               void *stream)
+{
+    return matmul_prepared_impl(X, m, k, x_bits, prepared, n, N, L, moduli, mask, out, workspace,
+                                workspace_bytes, false, stream);
+}
+
+int nimbus_cop_matmul_prepared_static(const uint64_t *X, int m, int k, int x_bits,
+                                      const void *prepared, int n, int N, int L,
+                                      const uint64_t *moduli,
+                                      const uint64_t *mask, uint64_t *out,
+                                      void *stream)
+{
+    return matmul_prepared_impl(X, m, k, x_bits, prepared, n, N, L, moduli, mask, out, nullptr,
+                                (size_t)NIMBUS_COP_STATIC_WORKSPACE_BYTES, true, stream);
 }
 
 int nimbus_cop_packed_count(int m, int n, int N)
@@ -308,6 +363,8 @@ const char *nimbus_cop_strerror(int status)
     case NIMBUS_COP_ERR_UNSUPPORTED: return "parameters not supported by this entry point";
     case NIMBUS_COP_ERR_LAUNCH: return "HIP kernel launch failed";
     case NIMBUS_COP_ERR_BUFFER_SIZE: return "prepared or workspace buffer too small";
+    case NIMBUS_COP_ERR_STATIC_LIMIT:
+        return "shares need more than the built-in workspace of nimbus_cop_matmul_prepared_static";
     default: return "unknown status";
     }
 }

@@ -87,6 +87,27 @@ def test_invalid_arguments_are_rejected_on_the_host(kw):
                                         a["N"], a["L"], mod, a["mask"], a["out"], 0x4000, 1 << 30,
                                         None)
     assert rc == -1
+    rc = lib.nimbus_cop_matmul_prepared_static(a["X"], a["m"], a["k"], a["x_bits"], a["ctW"],
+                                               a["n"], a["N"], a["L"], mod, a["mask"], a["out"],
+                                               None)
+    assert rc == -1
+
+
+def test_static_workspace_limit_is_checked_on_the_host():
+    """the entry point without allocation refuses shares beyond its built-in 8 MiB buffer
+    before it asks the runtime for anything"""
+    lib = _raw()
+    mod = (ctypes.c_uint64 * 1)(*ci.limb_primes(54, 20, 1))
+    m = 32 * 2731 + 1                  # 2732 row tiles x 1 k-block x 3 planes x 1 KiB > 8 MiB
+    assert nc.nimbus_cop_workspace_bytes(m, 32, 20) == 2732 * 3 * 1024
+    rc = lib.nimbus_cop_matmul_prepared_static(0x1000, m, 32, 20, 0x2000, 32, 32, 1, mod, None,
+                                               0x1000000, None)
+    assert rc == -5
+    assert "built-in" in nc.nimbus_cop_strerror(-5)
+    # unsupported parameters are reported as such, not as a size problem
+    rc = lib.nimbus_cop_matmul_prepared_static(0x1000, 4, 50000, 20, 0x2000, 32, 32, 1, mod, None,
+                                               0x3000, None)
+    assert rc == -2
 
 
 def test_prepared_path_limits_and_buffer_sizes():
