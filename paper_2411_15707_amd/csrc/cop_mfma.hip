@@ -207,19 +207,18 @@ __device__ __forceinline__ void wait_vmem()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
 }
 
-// one wave copies 64 x 16 B (a whole operand tile) or 64 x 4 B (a quarter tile) from
-// global memory straight into LDS; lane l's bytes land at dst + l*16 (resp. l*4)
-__device__ __forceinline__ void dma_tile(const void *src_lane, void *dst_wave)
+// one wave copies 64 x 16 B (a whole operand tile) from global memory straight into LDS;
+// lane l's bytes land at dst + l*16.  The source is a buffer descriptor (wave-uniform base)
+// plus a per-lane offset plus a wave-uniform offset: the address needs no vector arithmetic.
+// Every tile carries the streaming hint: the ciphertext planes are read once and should not
+// push the X planes out of L2, and for the X planes, which all workgroups of an XCD read
+// within a few microseconds of each other, the hint makes no measurable difference; one kind
+// of load lets all eight waves run the same instructions.
+__device__ __forceinline__ void dma_tile(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_off,
+                                         uint32_t uniform_off, void *dst_wave)
 {
-    __builtin_amdgcn_global_load_lds((const NIMBUS_AS1 void *)src_lane,
-                                     (NIMBUS_AS3 void *)dst_wave, 16, 0, 0);
-}
-// the same with the streaming hint: data that is read once (the ciphertext planes) should
-// not push the X planes, which every workgroup reads again and again, out of L2
-__device__ __forceinline__ void dma_tile_stream(const void *src_lane, void *dst_wave)
-{
-    __builtin_amdgcn_global_load_lds((const NIMBUS_AS1 void *)src_lane,
-                                     (NIMBUS_AS3 void *)dst_wave, 16, 0, 2);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (NIMBUS_AS3 void *)dst_wave, 16, lane_off,
+                                             uniform_off, 0, 2);
 }
 
 // The pipeline.  A workgroup of eight waves (two per SIMD) owns 128 token rows x 64
@@ -252,9 +251,6 @@ __device__ __forceinline__ void dma_tile_stream(const void *src_lane, void *dst_
 // instruction costs: one stage issued per iteration from the first iteration on,
 // ring offsets carried and wrapped instead of recomputed, and the wait for "at most n
 // loads pending", an immediate of the instruction, done by a computed jump).
-#ifndef NIMBUS_LEAD
-#define NIMBUS_LEAD 3
-#endif
 
 template <int DX, int DQ>
 struct Pipe {
@@ -270,7 +266,7 @@ struct Pipe {
     // after its barrier, into the slot of stage s + LEAD - RING.  That slot has been read
     // by every wave once all have passed the barrier of iteration s + LEAD - RING + 1 -
     // AHEAD, so RING = LEAD + 1 - AHEAD slots are enough.
-    static constexpr int LEAD = NIMBUS_LEAD;
+    static constexpr int LEAD = 3;
     static constexpr int RING = LEAD + 1 - AHEAD;
     static_assert(LEAD >= 1 + AHEAD, "the stage read next must have been issued");
     // X tile t goes to wave t % 4 as its load t / 4, ciphertext tile t to wave 4 + t % 4
@@ -282,17 +278,19 @@ struct Pipe {
 
 // Wait until at most n of this wave's loads are pending, 0 <= n <= 63, n wave-uniform.
 // The count is an immediate of the wait instruction: jump into a table of 64 entries
-// of 8 bytes, entry i = { wait for at most i pending; branch to the end }.  The five
-// instructions between the program counter read and the table take 20 bytes.
+// of 8 bytes, entry i = { wait for at most i pending; branch to the end }.  The distance
+// from the program counter that was read to the table is left to the assembler.
 __device__ __forceinline__ void wait_vmem_n(int n)
 {
     asm volatile(
-        "s_getpc_b64 s[96:97]\n\t"
+        "s_getpc_b64 s[96:97]\n"
+        ".Lwait_vmem_pc_%=:\n\t"
         "s_lshl_b32 s98, %0, 3\n\t"
-        "s_add_u32 s98, s98, 20\n\t"
+        "s_add_u32 s98, s98, .Lwait_vmem_table_%=-.Lwait_vmem_pc_%=\n\t"
         "s_add_u32 s96, s96, s98\n\t"
         "s_addc_u32 s97, s97, 0\n\t"
-        "s_setpc_b64 s[96:97]\n\t"
+        "s_setpc_b64 s[96:97]\n"
+        ".Lwait_vmem_table_%=:\n\t"
         ".irp cnt,0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,"
         "32,33,34,35,36,37,38,39,40,41,42,43,44,45,46,47,48,49,50,51,52,53,54,55,56,57,58,59,60,61,62,63\n\t"
         "s_waitcnt vmcnt(\\cnt)\n\t"
@@ -302,6 +300,45 @@ __device__ __forceinline__ void wait_vmem_n(int n)
         :
         : "s"(__builtin_amdgcn_readfirstlane(n))
         : "s96", "s97", "s98", "scc", "memory");
+}
+
+// Wait until at most W * n of this wave's loads are pending, for n in [NLO, NHI] with
+// NHI - NLO <= 2, n wave-uniform: a short chain of compares in the order the code runs
+// through, instead of the table jump above.
+template <int W, int NHI, int NLO>
+__device__ __forceinline__ void wait_vmem_loads(int n)
+{
+    static_assert(NHI - NLO <= 2 && NHI >= NLO, "at most three cases");
+    if constexpr (NHI == NLO) {
+        wait_vmem<W * NHI>();
+    } else if constexpr (NHI - NLO == 1) {
+        asm volatile("s_cmp_eq_u32 %0, %1\n\t"
+                     "s_cbranch_scc1 .Lwl_hi_%=\n\t"
+                     "s_waitcnt vmcnt(%2)\n\t"
+                     "s_branch .Lwl_end_%=\n"
+                     ".Lwl_hi_%=:\n\t"
+                     "s_waitcnt vmcnt(%3)\n"
+                     ".Lwl_end_%=:"
+                     :
+                     : "s"(n), "n"(NHI), "n"(W * NLO), "n"(W * NHI)
+                     : "scc", "memory");
+    } else {
+        asm volatile("s_cmp_eq_u32 %0, %1\n\t"
+                     "s_cbranch_scc1 .Lwl_hi_%=\n\t"
+                     "s_cmp_eq_u32 %0, %2\n\t"
+                     "s_cbranch_scc1 .Lwl_mid_%=\n\t"
+                     "s_waitcnt vmcnt(%3)\n\t"
+                     "s_branch .Lwl_end_%=\n"
+                     ".Lwl_mid_%=:\n\t"
+                     "s_waitcnt vmcnt(%4)\n\t"
+                     "s_branch .Lwl_end_%=\n"
+                     ".Lwl_hi_%=:\n\t"
+                     "s_waitcnt vmcnt(%5)\n"
+                     ".Lwl_end_%=:"
+                     :
+                     : "s"(n), "n"(NHI), "n"(NHI - 1), "n"(W * NLO), "n"(W * (NHI - 1)), "n"(W * NHI)
+                     : "scc", "memory");
+    }
 }
 
 // FULL: m is a multiple of 128, so every wave has its 32 rows: the code for waves without
@@ -365,32 +402,37 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         (const unsigned char *)a.xd + (size_t)rb * 4u * a_tile_bytes;
     const unsigned char *const b_base =
         (const unsigned char *)a.planes + (size_t)ct2 * 2u * b_tile_bytes;
-    auto a_src = [&](int t) -> const unsigned char * {
+    auto a_off = [&](int t) -> uint32_t {               // byte offset from a_base
         int r = t / DX;                                 // row tile inside the row block
         const int last = RT - 1 - (int)rb * 4;          // last one that exists (>= 0)
         if (r > last) r = last;
-        return a_base + ((uint32_t)r * a_tile_bytes + (uint32_t)(t % DX) * kTileBytes);
+        return (uint32_t)r * a_tile_bytes + (uint32_t)(t % DX) * kTileBytes;
     };
-    auto b_src = [&](int u) -> const unsigned char * {
-        return b_base + ((uint32_t)(u / DQ) * b_tile_bytes + (uint32_t)(u % DQ) * kTileBytes);
+    auto b_off = [&](int u) -> uint32_t {               // byte offset from b_base
+        return (uint32_t)(u / DQ) * b_tile_bytes + (uint32_t)(u % DQ) * kTileBytes;
     };
     // Waves 0-3 (the first wave of each SIMD) load the X tiles, from L2; waves 4-7 (the
     // second of each SIMD) the ciphertext tiles, from HBM: load u (u < MAXU) of a wave
-    // moves tile wave % 4 + 4 u of its kind.
+    // moves tile wave % 4 + 4 u of its kind.  A load's source is the wave's buffer
+    // descriptor (base of the workgroup's X or ciphertext region), the lane's 16 bytes, and a
+    // wave-uniform offset: the tile's place at k-block 0 plus the carried k-block offset.
     const bool loads_x = wave < 4;
-    const unsigned char *src[P_::MAXU];             // lane's source address at k-block 0
-    unsigned char *dst[P_::MAXU];                   // the tile's place in slot 0 of its ring
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(loads_x ? a_base : b_base), 0, 0xffffffff, 0x00027000);
+    const uint32_t lane16 = (uint32_t)lane * 16u;
+    uint32_t toff[P_::MAXU];                        // the tile's byte offset at k-block 0
+    uint32_t dst[P_::MAXU];                         // the tile's byte offset in slot 0 of the LDS
     int n_loads = 0;                                // loads per stage
 #pragma unroll
     for (int u = 0; u < P_::MAXU; ++u) {
         const int t = (wave & 3) + 4 * u;
         if (loads_x ? (t < P_::A_TILES) : (t < P_::B_TILES)) {
-            src[u] = (loads_x ? a_src(t) : b_src(t)) + lane * 16;
-            dst[u] = (loads_x ? ldsA : ldsB) + (uint32_t)t * kTileBytes;
+            toff[u] = __builtin_amdgcn_readfirstlane(loads_x ? a_off(t) : b_off(t));
+            dst[u] = (loads_x ? 0u : (uint32_t)(RING * P_::A_BYTES)) + (uint32_t)t * kTileBytes;
             ++n_loads;
         } else {
-            src[u] = nullptr;
-            dst[u] = nullptr;
+            toff[u] = 0;
+            dst[u] = 0;
         }
     }
     n_loads = __builtin_amdgcn_readfirstlane(n_loads);
@@ -426,8 +468,8 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // load u of the stage at the carried offsets
     auto issue_one = [&](auto u_c) {
         constexpr int u = decltype(u_c)::value;
-        if (loads_x) dma_tile(src[u] + src_off, dst[u] + slot_off);
-        else dma_tile_stream(src[u] + src_off, dst[u] + slot_off);
+        unsigned char *const d = lds + (dst[u] + slot_off);
+        dma_tile(rsrc, lane16, toff[u] + src_off, d);
     };
 #define NIMBUS_NEXT_ISSUE()                                                   \
     do {                                                                      \
@@ -436,15 +478,13 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     } while (0)
 
     // the column's ciphertext sum is needed after the loop; asked for now (older than every
-    // direct-to-LDS load, so the counted waits cover it) it costs two registers, not a
-    // round trip to memory at the end
-    // (issued by hand: it must stay ahead of the first direct-to-LDS load, and the first
-    // counted wait, which every variant reaches before the loop ends, completes it)
-    uint64_t colsum_S;
-    {
-        const uint64_t *ps = a.colsum + (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
-        asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(colsum_S) : "v"(ps) : "memory");
-    }
+    // direct-to-LDS load, so the loop's counted waits have long covered it when it is used)
+    // it costs two registers, not a round trip to memory at the end.  An ordinary load: the
+    // compiler places the wait for it at its first use, and the statements below that
+    // clobber memory keep the load itself up here.
+    const uint64_t colsum_S =
+        a.colsum[(ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31)];
+    asm volatile("" ::: "memory");
 
     // ---- up front: stages 0 .. LEAD-1 ----
     // The accumulators are cleared between the stages: the memory pipeline takes the first
@@ -579,6 +619,56 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         });
         asm volatile("" ::: "memory");
     };
+    // Steady state, pipelined variants: as long as stage s + LEAD exists every load of the
+    // iteration is issued and the number of younger loads is the same every time.  All
+    // waves run the same instructions: the first NMIN loads of a stage are unconditional
+    // (every wave has that many), the others hang on one scalar test each.
+    constexpr int NMIN = DX < P_::B_TILES / 4 ? DX : P_::B_TILES / 4;
+    // The barrier of an iteration does not stand in front of its first matrix-core
+    // instructions: their operands are in registers already.  What has to follow it are the
+    // LDS reads of the next stage (its loads have landed everywhere) and the loads into the
+    // slot of the stage that every wave now holds in registers (each passed its LDS wait at
+    // the top).  With the barrier after instruction NPRE - 1, the wave of a SIMD that arrives
+    // first has left work in the matrix-core queue, and the later one finds the pipe free for
+    // its own first instructions: the pipe does not drain while the waves synchronise.
+    constexpr int NPRE = 4 < NPOS / 3 ? 4 : NPOS / 3;
+    // behind the barrier: the loads, then the reads, spread evenly over the remaining positions
+    constexpr int NITEMS = P_::MAXU + R0, SPAN = NPOS - NPRE;
+    auto steady_iteration = [&](auto set_c) {
+        constexpr int SET = decltype(set_c)::value;
+        constexpr int W = LEAD - 1 - AHEAD;
+        wait_ops(set_c);
+        static_for<0, NPOS>([&](auto i_c) {
+            constexpr int i = decltype(i_c)::value;
+            constexpr int dx = i / DQ, dq = i % DQ;
+            tie(xa[SET][dx]);
+            tie(xb[SET][dq]);
+            acc[dx + dq] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                xa[SET][dx], xb[SET][dq], acc[dx + dq], 0, 0, 0);
+            tie_acc(acc[dx + dq]);
+            if constexpr (i == NPRE - 1) {
+                wait_vmem_loads<W, P_::MAXU, NMIN>(n_loads);
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
+            if constexpr (i >= NPRE) {
+                static_for<0, NITEMS>([&](auto j_c) {
+                    constexpr int j = decltype(j_c)::value;
+                    if constexpr (NPRE + j * SPAN / NITEMS == i) {
+                        if constexpr (j < P_::MAXU) {
+                            if (j < NMIN || j < n_loads)
+                                dma_tile(rsrc, lane16, toff[j] + src_off,
+                                                lds + (dst[j] + slot_off));
+                        } else {
+                            read_one(std::integral_constant<int, 1 - SET>{},
+                                     std::integral_constant<int, j - P_::MAXU>{});
+                        }
+                    }
+                });
+            }
+        });
+        asm volatile("" ::: "memory");
+    };
     // the carried offsets move on between iterations (outside the lambda: plain locals)
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
@@ -590,7 +680,16 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         return;
     }
     if constexpr (PIPELINED) {
-        for (int s = 0; s < KB; s += 2) {
+        int s = 0;
+        for (; s + 2 <= KB - LEAD; s += 2) {        // iterations below KB - LEAD are steady
+            steady_iteration(C0{});
+            NIMBUS_NEXT_ISSUE();
+            NIMBUS_NEXT_READ();
+            steady_iteration(C1{});
+            NIMBUS_NEXT_ISSUE();
+            NIMBUS_NEXT_READ();
+        }
+        for (; s < KB; s += 2) {
             iteration(s, C0{}, std::true_type{});
             NIMBUS_NEXT_ISSUE();
             NIMBUS_NEXT_READ();
@@ -612,8 +711,6 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // the last pipelined iteration has read a stage that does not exist into the other
     // operand set; nothing may reuse those registers before the reads are back
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    // (the column sum was loaded by hand: its uses must stay behind the loop's waits)
-    asm volatile("" : "+v"(colsum_S));
 
     // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
     const uint32_t col = (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31);
