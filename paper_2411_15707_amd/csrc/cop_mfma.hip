@@ -344,7 +344,19 @@ __device__ __forceinline__ void wait_vmem_loads(int n)
 // FULL: m is a multiple of 128, so every wave has its 32 rows: the code for waves without
 // rows and the row tests around the loads and stores of the epilogue (a compare, an exec
 // update and a branch each) are left out.
-template <int DX, int DQ, bool FULL>
+//
+// MASKLDS: the workgroup's 128 x 64 mask words (64 KB) are brought into LDS by the first
+// iterations of the loop, one direct-to-LDS load per wave and iteration, instead of being
+// read from memory when the loop is over: the 16 B per output that mask and result move
+// would otherwise all fall into the last microseconds of the launch, where they are the
+// only traffic and every workgroup asks at once.  Needs a mask, m a multiple of 128, a
+// pipelined variant, room in the LDS, at least kMaskLdsMinKB k-blocks and a row block whose
+// mask rows span less than 4 GB (host: mask_in_lds()).
+constexpr int kMaskTileBytes = 128 * 64 * 8;
+constexpr int kMaskLoads = kMaskTileBytes / kTileBytes / 8;     // per wave: 8
+constexpr int kMaskPhase = kMaskLoads + 2;                      // iterations that count them
+
+template <int DX, int DQ, bool FULL, bool MASKLDS>
 __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 {
     using P_ = Pipe<DX, DQ>;
@@ -357,7 +369,9 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     constexpr bool PIPELINED = P_::PIPELINED;
     constexpr int AHEAD = P_::AHEAD, LEAD = P_::LEAD, RING = P_::RING;
     constexpr int SETS = PIPELINED ? 2 : 1;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[P_::LDS_BYTES];
+    static_assert(!MASKLDS || (FULL && P_::PIPELINED && P_::LDS_BYTES + kMaskTileBytes <= 160 * 1024),
+                  "mask tile in LDS: full row blocks, pipelined variant, and it must fit");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[P_::LDS_BYTES + (MASKLDS ? kMaskTileBytes : 0)];
     unsigned char *const ldsA = lds;
     unsigned char *const ldsB = lds + RING * P_::A_BYTES;
 
@@ -634,8 +648,28 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     constexpr int NPRE = 4 < NPOS / 3 ? 4 : NPOS / 3;
     // behind the barrier: the loads, then the reads, spread evenly over the remaining positions
     constexpr int NITEMS = P_::MAXU + R0, SPAN = NPOS - NPRE;
-    auto steady_iteration = [&](auto set_c) {
+    // Mask tile (MASKLDS): load j of the tile, 0 <= j < 64, brings rows 2j and 2j+1 of the
+    // row block (lanes 0-31 and 32-63, 16 bytes = two columns each) to LDS bytes
+    // [j KB, j KB + 1 KB) of the tile, which so ends up row-major [128][64].  Wave w issues
+    // load w + 8 i in iteration i < kMaskLoads, ahead of the iteration's stage loads; a
+    // wait for a stage then has one more younger load to allow for in iterations
+    // 1 .. kMaskLoads.  Rows past the end of the mask (none, m being a multiple of 128) would
+    // read as zero: the descriptor ends where the mask ends.
+    __amdgpu_buffer_rsrc_t rsrc_m = rsrc;
+    uint32_t voff_m = 0, soff_m = 0, dst_m = 0;
+    if constexpr (MASKLDS) {
+        const uint64_t first = ((uint64_t)rb * 128u * a.C + (uint64_t)ct2 * 64u) * 8u;
+        const uint64_t left = (uint64_t)a.m * a.C * 8u - first;
+        rsrc_m = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((const unsigned char *)a.mask + first), 0,
+            left > 0xffffffffull ? 0xffffffffu : (uint32_t)left, 0x00027000);
+        voff_m = (uint32_t)(lane >> 5) * a.C * 8u + (uint32_t)(lane & 31) * 16u;
+        soff_m = (uint32_t)wave * 2u * a.C * 8u;
+        dst_m = (uint32_t)P_::LDS_BYTES + (uint32_t)wave * kTileBytes;
+    }
+    auto steady_iteration = [&](auto set_c, auto phase_c, int t) {
         constexpr int SET = decltype(set_c)::value;
+        constexpr bool MASKPHASE = decltype(phase_c)::value;   // iteration t < kMaskPhase
         constexpr int W = LEAD - 1 - AHEAD;
         wait_ops(set_c);
         static_for<0, NPOS>([&](auto i_c) {
@@ -647,9 +681,19 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
                 xa[SET][dx], xb[SET][dq], acc[dx + dq], 0, 0, 0);
             tie_acc(acc[dx + dq]);
             if constexpr (i == NPRE - 1) {
-                wait_vmem_loads<W, P_::MAXU, NMIN>(n_loads);
+                if constexpr (MASKPHASE)
+                    wait_vmem_n(W * n_loads + ((t >= 1 && t <= kMaskLoads) ? 1 : 0));
+                else
+                    wait_vmem_loads<W, P_::MAXU, NMIN>(n_loads);
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
+                if constexpr (MASKPHASE) {
+                    if (t < kMaskLoads) {
+                        dma_tile(rsrc_m, voff_m, soff_m, lds + dst_m);
+                        soff_m += 16u * a.C * 8u;
+                        dst_m += 8u * kTileBytes;
+                    }
+                }
             }
             if constexpr (i >= NPRE) {
                 static_for<0, NITEMS>([&](auto j_c) {
@@ -681,11 +725,22 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     }
     if constexpr (PIPELINED) {
         int s = 0;
+        if constexpr (MASKLDS) {
+            static_assert(kMaskPhase % 2 == 0, "whole pairs of iterations");
+            for (; s < kMaskPhase; s += 2) {        // the host made sure KB - LEAD >= kMaskPhase
+                steady_iteration(C0{}, std::true_type{}, s);
+                NIMBUS_NEXT_ISSUE();
+                NIMBUS_NEXT_READ();
+                steady_iteration(C1{}, std::true_type{}, s + 1);
+                NIMBUS_NEXT_ISSUE();
+                NIMBUS_NEXT_READ();
+            }
+        }
         for (; s + 2 <= KB - LEAD; s += 2) {        // iterations below KB - LEAD are steady
-            steady_iteration(C0{});
+            steady_iteration(C0{}, std::false_type{}, s);
             NIMBUS_NEXT_ISSUE();
             NIMBUS_NEXT_READ();
-            steady_iteration(C1{});
+            steady_iteration(C1{}, std::false_type{}, s + 1);
             NIMBUS_NEXT_ISSUE();
             NIMBUS_NEXT_READ();
         }
@@ -727,7 +782,15 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     const uint64_t *const prev0 = a.prev ? a.prev + lane_elem : nullptr;
     uint64_t *const out0 = a.out + lane_elem;
     uint64_t mk[16];                                // read once: streaming loads
-    if (a.mask) {
+    if constexpr (MASKLDS) {
+        // the tile is in LDS, row-major [128][64]; every load of it landed before a barrier
+        // of the loop that this wave has passed
+        const unsigned char *const tile =
+            lds + P_::LDS_BYTES + (uint32_t)(wr * kTile + 4 * (lane >> 5)) * 512u +
+            (uint32_t)(wc * kTile + (lane & 31)) * 8u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mk[r] = *(const uint64_t *)(tile + roff(r) * 512);
+    } else if (a.mask) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             mk[r] = (FULL || row0 + roff(r) < a.m)
@@ -999,10 +1062,21 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
         a.cst_lo[l] = (uint64_t)c;
     }
     const dim3 grid((CT / 2) * (uint32_t)a.RB);
+    using P_ = Pipe<DX, DQ>;
+    constexpr bool kCanMaskLds = P_::PIPELINED && P_::LDS_BYTES + kMaskTileBytes <= 160 * 1024;
+    // mask tile in LDS: see the kernel; 128 rows of the mask must span less than 4 GB
+    const bool mask_lds = kCanMaskLds && mask != nullptr && p.m % 128 == 0 &&
+                          KB - P_::LEAD >= kMaskPhase && (uint64_t)p.C * 8u * 128u < (1ull << 32);
+    if constexpr (kCanMaskLds) {
+        if (mask_lds) {
+            hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, true, true>), grid, dim3(512), 0, stream, a);
+            return hipGetLastError();
+        }
+    }
     if (p.m % 128 == 0)
-        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, true>), grid, dim3(512), 0, stream, a);
+        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, true, false>), grid, dim3(512), 0, stream, a);
     else
-        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, false>), grid, dim3(512), 0, stream, a);
+        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, false, false>), grid, dim3(512), 0, stream, a);
     return hipGetLastError();
 }
 
