@@ -404,61 +404,51 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     const int KB = a.KB;
 
     // ---- this wave's share of the loads of one stage (sources at k-block 0) ----
-    // X tile t of a stage, t in [0, 4 DX): row tile t / DX (clamped to an existing one;
-    // rows past m are never used), plane t % DX.  Ciphertext tile u in [0, 2 DQ):
-    // column tile u / DQ, plane u % DQ.
-    // (one 64-bit base per operand, 32-bit offsets from it: a row tile or column tile of
-    // planes spans KB * D KiB < 2^23 bytes, and the setup before the first load is all
-    // scalar instructions on the critical path of the launch)
+    // Waves 0-3 (the first wave of each SIMD) load the X tiles, from L2: wave w the DX planes
+    // of row tile w of the row block (clamped to a row tile that exists; rows past m are
+    // never used).  Waves 4-7 (the second of each SIMD) load the ciphertext tiles, from HBM:
+    // waves 4 and 5 the planes of the first column tile (planes 0-3 and 4 .. DQ-1), waves 6
+    // and 7 those of the second.  A load's source is the wave's buffer descriptor (base of
+    // the workgroup's X or ciphertext region), the lane's 16 bytes, and a wave-uniform
+    // offset: the tile's place at k-block 0 plus the carried k-block offset.  (A row tile or
+    // column tile of planes spans KB * D KiB < 2^23 bytes.  Everything up to the first loads
+    // is scalar work on the critical path of the launch: no divisions, and whatever the loads
+    // do not need comes after them.)
     const uint32_t a_tile_bytes = (uint32_t)KB * DX * kTileBytes;     // one row tile, all k-blocks
     const uint32_t b_tile_bytes = (uint32_t)KB * DQ * kTileBytes;     // one column tile
     const unsigned char *const a_base =
         (const unsigned char *)a.xd + (size_t)rb * 4u * a_tile_bytes;
     const unsigned char *const b_base =
         (const unsigned char *)a.planes + (size_t)ct2 * 2u * b_tile_bytes;
-    auto a_off = [&](int t) -> uint32_t {               // byte offset from a_base
-        int r = t / DX;                                 // row tile inside the row block
-        const int last = RT - 1 - (int)rb * 4;          // last one that exists (>= 0)
-        if (r > last) r = last;
-        return (uint32_t)r * a_tile_bytes + (uint32_t)(t % DX) * kTileBytes;
-    };
-    auto b_off = [&](int u) -> uint32_t {               // byte offset from b_base
-        return (uint32_t)(u / DQ) * b_tile_bytes + (uint32_t)(u % DQ) * kTileBytes;
-    };
-    // Waves 0-3 (the first wave of each SIMD) load the X tiles, from L2; waves 4-7 (the
-    // second of each SIMD) the ciphertext tiles, from HBM: load u (u < MAXU) of a wave
-    // moves tile wave % 4 + 4 u of its kind.  A load's source is the wave's buffer
-    // descriptor (base of the workgroup's X or ciphertext region), the lane's 16 bytes, and a
-    // wave-uniform offset: the tile's place at k-block 0 plus the carried k-block offset.
     const bool loads_x = wave < 4;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(loads_x ? a_base : b_base), 0, 0xffffffff, 0x00027000);
     const uint32_t lane16 = (uint32_t)lane * 16u;
+    constexpr int PH = (DQ + 1) / 2;                // planes of a column tile on its first wave
+    static_assert(P_::MAXU == 4 && DX <= 4 && PH <= 4, "four load slots per wave and stage");
     uint32_t toff[P_::MAXU];                        // the tile's byte offset at k-block 0
     uint32_t dst[P_::MAXU];                         // the tile's byte offset in slot 0 of the LDS
-    int n_loads = 0;                                // loads per stage
-#pragma unroll
-    for (int u = 0; u < P_::MAXU; ++u) {
-        const int t = (wave & 3) + 4 * u;
-        if (loads_x ? (t < P_::A_TILES) : (t < P_::B_TILES)) {
-            toff[u] = __builtin_amdgcn_readfirstlane(loads_x ? a_off(t) : b_off(t));
-            dst[u] = (loads_x ? 0u : (uint32_t)(RING * P_::A_BYTES)) + (uint32_t)t * kTileBytes;
-            ++n_loads;
-        } else {
-            toff[u] = 0;
-            dst[u] = 0;
-        }
-    }
-    n_loads = __builtin_amdgcn_readfirstlane(n_loads);
-    // The limb of this wave's 32 columns (they lie in one (polynomial, limb) block of N >= 32
-    // columns), worked out here with a shift and a multiply-high: after the loop it would sit
-    // on the path to the first loads of the epilogue.
-    uint32_t limb;
+    int n_loads;                                    // loads per stage
     {
-        const uint32_t blk = ((ct2 * 2u + (uint32_t)wc) * kTile) >> a.log_n;
-        limb = a.L == 1 ? 0u : blk - (uint32_t)a.L * __umulhi(blk, a.l_magic);
-        limb = __builtin_amdgcn_readfirstlane(limb);
-        asm volatile("" : "+s"(limb));
+        uint32_t first_off, first_tile;             // of the wave's first tile; the others follow it
+        if (loads_x) {
+            int r = wave;
+            const int last = RT - 1 - (int)rb * 4;  // last row tile of the block that exists (>= 0)
+            if (r > last) r = last;
+            first_off = (uint32_t)r * a_tile_bytes;
+            first_tile = (uint32_t)wave * DX;
+            n_loads = DX;
+        } else {
+            const uint32_t c = (uint32_t)(wave >> 1) & 1u, hi = (uint32_t)wave & 1u;
+            first_off = c * b_tile_bytes + hi * (PH * kTileBytes);
+            first_tile = (uint32_t)P_::A_TILES * RING + c * DQ + hi * PH;
+            n_loads = hi ? DQ - PH : PH;
+        }
+#pragma unroll
+        for (int u = 0; u < P_::MAXU; ++u) {
+            toff[u] = first_off + (uint32_t)u * kTileBytes;
+            dst[u] = (first_tile + (uint32_t)u) * kTileBytes;
+        }
     }
     // Stage s of this workgroup is k-block (s + k_start) mod KB: the sum over k does not
     // care about the order, and workgroups that walk their (equally spaced) ciphertext
@@ -491,15 +481,6 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         slot_off = bump(slot_off, slot_step, slot_end);                       \
     } while (0)
 
-    // the column's ciphertext sum is needed after the loop; asked for now (older than every
-    // direct-to-LDS load, so the loop's counted waits have long covered it when it is used)
-    // it costs two registers, not a round trip to memory at the end.  An ordinary load: the
-    // compiler places the wait for it at its first use, and the statements below that
-    // clobber memory keep the load itself up here.
-    const uint64_t colsum_S =
-        a.colsum[(ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31)];
-    asm volatile("" ::: "memory");
-
     // ---- up front: stages 0 .. LEAD-1 ----
     // The accumulators are cleared between the stages: the memory pipeline takes the first
     // loads of a launch slowly (nothing is translated or cached yet), and the moves fill
@@ -519,6 +500,28 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
             for (int r = 0; r < 16; ++r) acc[d][r] = 0;
             tie_acc(acc[d]);
         }
+    }
+
+    // ---- what the first loads did not need ----
+    __builtin_amdgcn_sched_barrier(0);
+    n_loads = __builtin_amdgcn_readfirstlane(n_loads);
+    // The column's ciphertext sum is needed after the loop; asked for now it costs two
+    // registers, not a round trip to memory at the end.  An ordinary load: the compiler places
+    // the wait for it at its first use, and the statements below that clobber memory keep the
+    // load itself up here.  (One more load ahead of the loop's counted waits only makes them
+    // wait for it too; it is the oldest but LEAD stages by then.)
+    const uint64_t colsum_S =
+        a.colsum[(ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31)];
+    asm volatile("" ::: "memory");
+    // The limb of this wave's 32 columns (they lie in one (polynomial, limb) block of N >= 32
+    // columns), worked out here with a shift and a multiply-high: after the loop it would sit
+    // on the path to the first loads of the epilogue.
+    uint32_t limb;
+    {
+        const uint32_t blk = ((ct2 * 2u + (uint32_t)wc) * kTile) >> a.log_n;
+        limb = a.L == 1 ? 0u : blk - (uint32_t)a.L * __umulhi(blk, a.l_magic);
+        limb = __builtin_amdgcn_readfirstlane(limb);
+        asm volatile("" : "+s"(limb));
     }
 
     // Operands come out of LDS through explicit ds_read_b128 instructions: reads the
