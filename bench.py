@@ -135,16 +135,29 @@ def main():
                 nc.nimbus_cop_matmul_prepared(Xs[r], m, k, xb, preps[r], n, N, L, moduli, masks[r],
                                               outs[r], wss[r % S], stream=streams[r % S])
 
+        def timed_two_streams(fn, count):
+            """ms per call of fn(count): events on both streams, the later end minus the earlier start"""
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(S)]
+            torch.cuda.synchronize()
+            for i, st in enumerate(streams):
+                ev[i][0].record(st)
+            fn(count)
+            for i, st in enumerate(streams):
+                ev[i][1].record(st)
+            torch.cuda.synchronize()
+            # both start events are recorded on idle streams within microseconds of each other:
+            # the span is the longest of (start of either -> end of either)
+            return max(ev[i][0].elapsed_time(ev[j][1]) for i in range(S) for j in range(S)) / count
+
         for r in range(S):
             outs[r].zero_()
         torch.cuda.synchronize()
-        run(max(Rs, args.warmup // 2))
+        run(max(Rs, args.warmup // 2, 100))
         torch.cuda.synchronize()
-        steps2 = max(Rs, args.steps // 2)
-        q0 = time.perf_counter()
-        run(steps2)
-        torch.cuda.synchronize()
-        ms2 = (time.perf_counter() - q0) * 1e3 / steps2
+        steps2 = max(Rs, args.steps, 1000)          # enough launches whatever --steps is
+        steps2 -= steps2 % Rs
+        ms2 = timed_two_streams(run, steps2)
         two_streams = {
             "streams": S,
             "steps": steps2,
@@ -248,13 +261,11 @@ def main():
                 nc.nimbus_cop_matmul_staged(staged[r], m, k, xb, preps[r], n, N, L, moduli, masks[r],
                                             outs[r], stream=streams[r % S])
 
-        run_kernel(max(Rs, args.warmup // 2))
+        run_kernel(max(Rs, args.warmup // 2, 100))
         torch.cuda.synchronize()
-        launches2 = max(Rs, args.steps // 2)
-        q0 = time.perf_counter()
-        run_kernel(launches2)
-        torch.cuda.synchronize()
-        k2 = (time.perf_counter() - q0) * 1e3 / launches2
+        launches2 = max(Rs, args.steps, 1000)
+        launches2 -= launches2 % Rs
+        k2 = timed_two_streams(run_kernel, launches2)
         two_streams["kernel_only_ms_per_launch"] = round(k2, 5)
         two_streams["kernel_only_hbm_gbps"] = round(alg_bytes / (k2 * 1e-3) / 1e9, 1)
         two_streams["kernel_only_frac_of_hbm_peak"] = round(alg_bytes / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
@@ -477,6 +488,13 @@ def main():
             c1 = time.perf_counter()
             if c1 - c0 >= 1.5 or reps >= 50:
                 break
+        # one thread, on a slice of the same call (rows 0 .. 7: an eighth of a second or so)
+        rows1 = min(m, 8)
+        cop_oracle.cop_ref(X0[:rows1], ctW0, moduli, n, N, mask0[:rows1], 1)
+        d0 = time.perf_counter()
+        cop_oracle.cop_ref(X0[:rows1], ctW0, moduli, n, N, mask0[:rows1], 1)
+        d1 = time.perf_counter()
+        one_thread = rows1 * k * C / (d1 - d0)
         cpu_baseline = {
             "value": round(reps * cfg.mod_macs / (c1 - c0), 1),
             "unit": "modMAC/s",
@@ -485,6 +503,11 @@ def main():
             "sample": f"{reps} full calls of config {args.config} ({cfg.mod_macs} modular MACs "
                       f"each), {c1 - c0:.2f} s wall = {(c1 - c0) * used:.0f} core-seconds on "
                       f"{used} threads",
+            "one_thread_value": round(one_thread, 1),
+            "one_thread_sample": f"{rows1} rows of the same call ({rows1 * k * C} modular MACs), "
+                                 f"{d1 - d0:.2f} s on one thread",
+            "build": "gcc -O3 -march=x86-64-v2 -fopenmp (the baseline instruction set every box of "
+                     "the pool runs; the oracle is built before the GPU box is known)",
         }
 
     line = {
@@ -496,9 +519,9 @@ def main():
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True,
-        "scaling": "weak",
+        "scaling": "weak",          # one GPU: no scaling run exists (see --gpus)
         "vs_baseline": None,
-        "dtype": "int8",
+        "dtype": "u64 residues mod q_l, exact (int8 matrix-core digit products, int32 sums, one reduction per output)",
         "data": "synthetic",
         "config": {
             "workload": f"config {args.config}: {cfg.name} m={m} k={k} n={n} N={N} L={L} "
