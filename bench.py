@@ -270,17 +270,35 @@ def main():
         two_streams["kernel_only_hbm_gbps"] = round(alg_bytes / (k2 * 1e-3) / 1e9, 1)
         two_streams["kernel_only_frac_of_hbm_peak"] = round(alg_bytes / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
 
-    # ---- the canonical-layout vector-ALU entry point on the same workload, for reference ----
+    # ---- the canonical-layout entry points on the same workload (no setup pass, 8 B residues):
+    # nimbus_cop_matmul (matrix-core kernel that splits the words into byte planes itself) and
+    # nimbus_cop_matmul_valu (vector-ALU kernel, any parameters) ----
     dW0 = dev(first[1])
-    for _ in range(2):
-        nc.nimbus_cop_matmul(Xs[0], m, k, xb, dW0, n, N, L, moduli, masks[0], outs[0])
-    ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ea.record(stream)
-    for _ in range(5):
-        nc.nimbus_cop_matmul(Xs[0], m, k, xb, dW0, n, N, L, moduli, masks[0], outs[0])
-    eb.record(stream)
-    torch.cuda.synchronize()
-    valu_ms = ea.elapsed_time(eb) / 5
+
+    def timed_entry(fn, reps):
+        for _ in range(2):
+            fn(Xs[0], m, k, xb, dW0, n, N, L, moduli, masks[0], outs[0])
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        ea.record(stream)
+        for _ in range(reps):
+            fn(Xs[0], m, k, xb, dW0, n, N, L, moduli, masks[0], outs[0])
+        eb.record(stream)
+        torch.cuda.synchronize()
+        return ea.elapsed_time(eb) / reps
+    canon_ms = timed_entry(nc.nimbus_cop_matmul, 50)
+    valu_ms = timed_entry(nc.nimbus_cop_matmul_valu, 5)
+    canonical = {
+        "entry_point": "nimbus_cop_matmul",
+        "kernel": f"cop_canon_kernel<{DX},{DQ},{'true' if m % 128 == 0 else 'false'}>",
+        "kernel_ms_avg": round(canon_ms, 5),
+        "value": round(cfg.mod_macs / (canon_ms * 1e-3), 1),
+        "algorithmic_bytes_per_launch": alg_bytes,
+        "hbm_gbps_achieved": round(alg_bytes / (canon_ms * 1e-3) / 1e9, 1),
+        "hbm_frac_of_peak": round(alg_bytes / (canon_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "note": "weights from one resident buffer (100 MB, inside the 256 MB last-level cache)",
+        "vector_alu_kernel_ms": round(valu_ms, 4),
+    }
     del dW0
 
     # ---- output packing by right shifts (Algorithm 1 step 3) on this config's output ----
@@ -533,7 +551,7 @@ def main():
         "ms_per_step_hip_graph": None if graph_ms_per_step is None else round(graph_ms_per_step, 5),
         "two_streams": two_streams,
         "hbm_gbps_whole_step": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "canonical_layout_valu_kernel_ms": round(valu_ms, 4),
+        "canonical_layout": canonical,
         "roofline": roofline,
         "pack": pack,
         "server": server,

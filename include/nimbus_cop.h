@@ -77,12 +77,25 @@ extern "C" {
  *   moduli host   [L]
  *   mask   device [m][Ch][2][L][N], or NULL for no mask
  *   out    device [m][Ch][2][L][N]
- * Runs the vector-ALU kernel: any accepted parameter set.
+ * Needs no setup pass and no workspace.  Where the limits of the int8 matrix-core kernel
+ * allow (k <= 16383; k * Ch*2*L*N * 8 bytes and 128 * k * 8 bytes below 4 GB; not 25- to
+ * 32-bit shares together with moduli above 2^55) the 64-bit words of both operands are split
+ * into signed byte planes inside that kernel; everything else runs the vector-ALU kernel.
+ * Same result, bit for bit, either way.
+ *
+ * nimbus_cop_matmul_valu always runs the vector-ALU kernel (two 32 x 32 -> 64-bit
+ * multiply-adds per product, 128-bit sums, one Barrett reduction per output): any accepted
+ * parameter set, and the result the matrix-core kernels are held against.
+ * Additional limit of both (NIMBUS_COP_ERR_UNSUPPORTED beyond it): m <= 1,048,560.
  */
 int nimbus_cop_matmul(const uint64_t *X, int m, int k, int x_bits,
                       const uint64_t *ctW, int n, int N, int L,
                       const uint64_t *moduli,
                       const uint64_t *mask, uint64_t *out, void *stream);
+int nimbus_cop_matmul_valu(const uint64_t *X, int m, int k, int x_bits,
+                           const uint64_t *ctW, int n, int N, int L,
+                           const uint64_t *moduli,
+                           const uint64_t *mask, uint64_t *out, void *stream);
 
 /*
  * Setup phase (Section 3.2: the encrypted weights are static, sent once and

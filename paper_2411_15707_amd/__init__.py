@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     nimbus_cop_matmul,
+    nimbus_cop_matmul_valu,
     nimbus_cop_matmul_prepared,
     nimbus_cop_matmul_prepared_static,
     nimbus_cop_matmul_staged,

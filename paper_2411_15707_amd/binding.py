@@ -16,6 +16,7 @@ NIMBUS_INVALID = -1
 
 EXPORTED_SYMBOLS = (
     "nimbus_cop_matmul",
+    "nimbus_cop_matmul_valu",
     "nimbus_cop_prepared_bytes",
     "nimbus_cop_prepare",
     "nimbus_cop_workspace_bytes",
@@ -79,6 +80,8 @@ def load_library():
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.nimbus_cop_matmul.restype = ci
     lib.nimbus_cop_matmul.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
+    lib.nimbus_cop_matmul_valu.restype = ci
+    lib.nimbus_cop_matmul_valu.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.nimbus_cop_prepared_bytes.restype = sz
     lib.nimbus_cop_prepared_bytes.argtypes = [ci, ci, ci, ci, vp]
     lib.nimbus_cop_prepare.restype = ci
@@ -178,7 +181,7 @@ def nimbus_cop_version() -> int:
     return int(load_library().nimbus_cop_version())
 
 
-def nimbus_cop_matmul(X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, stream=None):
+def _canonical(entry, X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, stream):
     lib = load_library()
     C = _columns(n, N, L)
     _words(X, "X", m * k)
@@ -186,11 +189,19 @@ def nimbus_cop_matmul(X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, stream=N
     _words(out, "out", m * C)
     if mask is not None:
         _words(mask, "mask", m * C)
-    rc = lib.nimbus_cop_matmul(_dev_ptr(X, "X"), m, k, x_bits, _dev_ptr(ctW, "ctW"), n, N, L,
-                               _moduli(moduli), _dev_ptr(mask, "mask", True),
-                               _dev_ptr(out, "out"), _stream(stream))
+    rc = getattr(lib, entry)(_dev_ptr(X, "X"), m, k, x_bits, _dev_ptr(ctW, "ctW"), n, N, L,
+                             _moduli(moduli), _dev_ptr(mask, "mask", True),
+                             _dev_ptr(out, "out"), _stream(stream))
     if rc != 0:
-        raise NimbusCopError(rc, "nimbus_cop_matmul")
+        raise NimbusCopError(rc, entry)
+
+
+def nimbus_cop_matmul(X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, stream=None):
+    _canonical("nimbus_cop_matmul", X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, stream)
+
+
+def nimbus_cop_matmul_valu(X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, stream=None):
+    _canonical("nimbus_cop_matmul_valu", X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, stream)
 
 
 def nimbus_cop_prepared_bytes(k, n, N, L, moduli) -> int:

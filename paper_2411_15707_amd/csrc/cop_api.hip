@@ -162,21 +162,47 @@ using namespace nimbus;
 
 extern "C" {
 
+// checks shared by the two entry points on the canonical layout
+static int canonical_problem(const uint64_t *X, int m, int k, int x_bits, const uint64_t *ctW,
+                             int n, int N, int L, const uint64_t *moduli, const uint64_t *mask,
+                             uint64_t *out, Problem *p)
+{
+    if (!X || !ctW || !out) return NIMBUS_COP_ERR_INVALID_ARG;
+    const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, p);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if (x_bits > 32) return NIMBUS_COP_ERR_UNSUPPORTED;    // wide shares: prepared path only
+    if ((m + 15) / 16 > 65535) return NIMBUS_COP_ERR_UNSUPPORTED;   // grid of the vector-ALU kernel
+    const size_t out_bytes = (size_t)m * p->C * sizeof(uint64_t);
+    if (overlaps(out, out_bytes, X, (size_t)m * (size_t)k * sizeof(uint64_t)) ||
+        overlaps(out, out_bytes, ctW, (size_t)k * p->C * sizeof(uint64_t)) ||
+        overlaps(out, out_bytes, mask, out_bytes))
+        return NIMBUS_COP_ERR_INVALID_ARG;
+    return NIMBUS_COP_OK;
+}
+
 int nimbus_cop_matmul(const uint64_t *X, int m, int k, int x_bits,
                       const uint64_t *ctW, int n, int N, int L,
                       const uint64_t *moduli,
                       const uint64_t *mask, uint64_t *out, void *stream)
 {
-    if (!X || !ctW || !out) return NIMBUS_COP_ERR_INVALID_ARG;
     Problem p;
-    const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
+    const int rc = canonical_problem(X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, &p);
     if (rc != NIMBUS_COP_OK) return rc;
-    if (x_bits > 32) return NIMBUS_COP_ERR_UNSUPPORTED;    // wide shares: prepared path only
-    const size_t out_bytes = (size_t)m * p.C * sizeof(uint64_t);
-    if (overlaps(out, out_bytes, X, (size_t)m * (size_t)k * sizeof(uint64_t)) ||
-        overlaps(out, out_bytes, ctW, (size_t)k * p.C * sizeof(uint64_t)) ||
-        overlaps(out, out_bytes, mask, out_bytes))
-        return NIMBUS_COP_ERR_INVALID_ARG;
+    // the matrix-core kernel where its limits allow, the vector-ALU kernel for everything else
+    const hipError_t e = canon_supported(p)
+                             ? launch_cop_canon(p, X, ctW, mask, out, (hipStream_t)stream)
+                             : launch_cop_valu(p, X, ctW, mask, out, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+int nimbus_cop_matmul_valu(const uint64_t *X, int m, int k, int x_bits,
+                           const uint64_t *ctW, int n, int N, int L,
+                           const uint64_t *moduli,
+                           const uint64_t *mask, uint64_t *out, void *stream)
+{
+    Problem p;
+    const int rc = canonical_problem(X, m, k, x_bits, ctW, n, N, L, moduli, mask, out, &p);
+    if (rc != NIMBUS_COP_OK) return rc;
     const hipError_t e = launch_cop_valu(p, X, ctW, mask, out, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }

@@ -67,6 +67,10 @@ hipError_t launch_cop_mfma(const Problem &p, const void *staged, const void *pre
                            const uint64_t *mask, const uint64_t *prev, uint64_t *out,
                            hipStream_t stream);
 bool mfma_supported(const Problem &p);
+// matrix-core kernel on the canonical layout (cop_canon.hip)
+bool canon_supported(const Problem &p);
+hipError_t launch_cop_canon(const Problem &p, const uint64_t *X, const uint64_t *ctW,
+                            const uint64_t *mask, uint64_t *out, hipStream_t stream);
 hipError_t launch_cop_check(const Problem &p, const uint64_t *X, const uint64_t *ctW,
                             const uint64_t *mask, uint64_t *violations, hipStream_t stream);
 hipError_t launch_cop_pack(const Problem &p, const uint64_t *rows, const uint64_t *mask,

@@ -14,16 +14,27 @@ def host(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy().view(np.uint64)
 
 
-def run_valu(X, ctW, moduli, n, N, x_bits, mask=None):
+def _run_canonical(entry, X, ctW, moduli, n, N, x_bits, mask=None):
     m, k = X.shape
     L = len(moduli)
     Ch = -(-n // N)
     dX, dW = dev(X), dev(ctW)
     dM = dev(mask) if mask is not None else None
     out = torch.full((m, Ch, 2, L, N), -1, dtype=torch.int64, device="cuda")
-    nc.nimbus_cop_matmul(dX, m, k, x_bits, dW, n, N, L, moduli, dM, out)
+    entry(dX, m, k, x_bits, dW, n, N, L, moduli, dM, out)
     torch.cuda.synchronize()
     return host(out)
+
+
+def run_valu(X, ctW, moduli, n, N, x_bits, mask=None):
+    """the vector-ALU kernel on the canonical layout"""
+    return _run_canonical(nc.nimbus_cop_matmul_valu, X, ctW, moduli, n, N, x_bits, mask)
+
+
+def run_canon(X, ctW, moduli, n, N, x_bits, mask=None):
+    """nimbus_cop_matmul: the matrix-core kernel on the canonical layout where its limits
+    allow, the vector-ALU kernel otherwise"""
+    return _run_canonical(nc.nimbus_cop_matmul, X, ctW, moduli, n, N, x_bits, mask)
 
 
 def prepare(ctW, moduli, n, N):

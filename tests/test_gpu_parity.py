@@ -35,6 +35,9 @@ def _check_both(oracle, X, ctW, moduli, n, N, x_bits, mask, label):
     _say(f"[parity] {label}: matrix-core kernel")
     got = gu.run_mfma(X, ctW, moduli, n, N, x_bits, mask)
     assert np.array_equal(got, want), "mfma: " + gu.first_mismatch(got, want)
+    _say(f"[parity] {label}: canonical-layout entry point")
+    got = gu.run_canon(X, ctW, moduli, n, N, x_bits, mask)
+    assert np.array_equal(got, want), "canonical: " + gu.first_mismatch(got, want)
     return want
 
 
@@ -113,7 +116,7 @@ def test_special_cases_on_gpu(oracle):
     moduli = ci.limb_primes(54, t_bits, L)
     _, ctW, mask = _inputs(5, m, k, n, N, moduli, t_bits)
     qv = np.array(moduli, dtype=np.uint64).reshape(1, 1, 1, L, 1)
-    for run in (gu.run_valu, gu.run_mfma):
+    for run in (gu.run_valu, gu.run_mfma, gu.run_canon):
         out = run(np.zeros((m, k), np.uint64), ctW, moduli, n, N, t_bits, mask)
         assert np.array_equal(out, mask)                         # X = 0: the mask
         out = run(np.eye(m, dtype=np.uint64), ctW, moduli, n, N, t_bits, mask)
@@ -141,7 +144,7 @@ def test_config1_real_encryption_and_decrypt_invariant(oracle):
     mask = np.stack([oracle.share_mask(R[j], cfg.moduli, cfg.t_bits)[None] for j in range(cfg.m)])
     want, _ = oracle.cop_ref(X, ctW, cfg.moduli, cfg.n, cfg.N, mask)
     XW = X.astype(object) @ W.astype(object)
-    for run in (gu.run_valu, gu.run_mfma):
+    for run in (gu.run_valu, gu.run_mfma, gu.run_canon):
         out = run(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask)
         assert np.array_equal(out, want)
         for j in range(cfg.m):
@@ -253,8 +256,11 @@ def test_config5_layer_stack_on_one_stream(oracle):
     want_last = held[-1][4]
     del held
     _say("[parity] config 5: canonical-layout entry point, last call")
-    got = gu.run_valu(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask)
+    got = gu.run_canon(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask)
     assert np.array_equal(got, want_last), "canonical: " + gu.first_mismatch(got, want_last)
+    _say("[parity] config 5: vector-ALU kernel, last call")
+    got = gu.run_valu(X, ctW, cfg.moduli, cfg.n, cfg.N, cfg.t_bits, mask)
+    assert np.array_equal(got, want_last), "valu: " + gu.first_mismatch(got, want_last)
 
 
 def test_repeat_runs_are_identical(oracle):
