@@ -1,15 +1,17 @@
 """Compile the HIP sources under csrc/ into paper_2411_15707_amd/libnimbus_cop.so (gfx950)."""
+import concurrent.futures
 import glob
 import os
 import subprocess
 import sys
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnimbus_cop.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
@@ -20,9 +22,17 @@ def sources():
 
 
 def build(extra_flags=()) -> str:
+    """one object per source, compiled side by side, then one link"""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-o", LIB] + sources()
-    subprocess.run(cmd, check=True)
+    srcs = sources()
+    with tempfile.TemporaryDirectory(prefix="nimbus_cop_build_") as tmp:
+        def compile_one(src):
+            obj = os.path.join(tmp, os.path.basename(src) + ".o")
+            subprocess.run([hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-c", "-o", obj, src], check=True)
+            return obj
+        with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+            objs = list(pool.map(compile_one, srcs))
+        subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, check=True)
     return LIB
 
 

@@ -63,7 +63,10 @@ __device__ __forceinline__ void transpose4(uint32_t a, uint32_t b, uint32_t c, u
     t[3] = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x07060302u);
 }
 
-template <int DX, int DQ, bool FULL>
+// FULL: m is a multiple of 128.  SHARED: several row blocks per column tile (m > 128); they
+// start at the same k-block and load the ciphertext without the streaming hint, so that the
+// tile is found in the L2 of their XCD by all but the first.
+template <int DX, int DQ, bool FULL, bool SHARED>
 __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
 {
     const MfmaArgs &a = ca.e;
@@ -90,17 +93,19 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
     uint32_t ct2, rb;
     {
         const uint32_t id = blockIdx.x;
-        const uint32_t CT2 = a.CT >> 1;
-        if (a.RB == 1) {
+        const uint32_t RB = (uint32_t)a.RB;
+        const uint32_t CT2a = (a.CT >> 1) & ~7u;
+        if (!SHARED) {
             rb = 0;
             ct2 = id;
-        } else if ((CT2 & 7u) == 0) {
+        } else if (id < CT2a * RB) {
             const uint32_t xcd = id & 7u, slot = id >> 3;
-            rb = slot % (uint32_t)a.RB;
-            ct2 = (slot / (uint32_t)a.RB) * 8u + xcd;
+            rb = slot % RB;
+            ct2 = (slot / RB) * 8u + xcd;
         } else {
-            rb = id % (uint32_t)a.RB;
-            ct2 = id / (uint32_t)a.RB;
+            const uint32_t t = id - CT2a * RB;
+            rb = t % RB;
+            ct2 = CT2a + t / RB;
         }
     }
     const int RT = (a.m + kTile - 1) / kTile;
@@ -170,8 +175,8 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
                    (kq & 3u) * 4u;
     }
 
-    // stage s is k-block (s + k_start) mod KB (workgroups start at different k-blocks)
-    uint32_t k_start = blockIdx.x - __umulhi(blockIdx.x, a.kb_magic) * (uint32_t)KB;
+    // stage s is k-block (s + k_start) mod KB (column tiles start at different k-blocks)
+    uint32_t k_start = ct2 - __umulhi(ct2, a.kb_magic) * (uint32_t)KB;
     if (k_start >= (uint32_t)KB) k_start -= (uint32_t)KB;
     uint32_t kb_issue = k_start;                    // k-block of the next stage whose loads go out
     auto next_kb = [&](uint32_t kb) -> uint32_t { return kb + 1 == (uint32_t)KB ? 0u : kb + 1; };
@@ -183,7 +188,7 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
             // check of the descriptor looks at, and rows past k must read as zero)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rsrc_ct, (NIMBUS_AS3 void *)(lds + (ct_dst[i] + raw_issue * RAW_SLOT)), 16,
-                voff_ct + (ct_src[i] + kb_issue * 32u * row_bytes), 0, 0, 2);
+                voff_ct + (ct_src[i] + kb_issue * 32u * row_bytes), 0, 0, SHARED ? 0 : 2);
         kb_issue = next_kb(kb_issue);
         raw_issue = raw_issue + 1 == RAW_RING ? 0u : raw_issue + 1;
     };
@@ -397,10 +402,15 @@ static hipError_t canon_impl(const Problem &p, const uint64_t *X, const uint64_t
     ca.k = p.k;
     ca.limbs = p.limbs;
     const dim3 grid((ca.e.CT / 2) * (uint32_t)ca.e.RB);
-    if (p.m % 128 == 0)
-        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, true>), grid, dim3(512), 0, stream, ca);
+    const bool full = p.m % 128 == 0, shared = ca.e.RB > 1;
+    if (full && shared)
+        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, true, true>), grid, dim3(512), 0, stream, ca);
+    else if (full)
+        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, true, false>), grid, dim3(512), 0, stream, ca);
+    else if (shared)
+        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, false, true>), grid, dim3(512), 0, stream, ca);
     else
-        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, false>), grid, dim3(512), 0, stream, ca);
+        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, false, false>), grid, dim3(512), 0, stream, ca);
     return hipGetLastError();
 }
 

@@ -197,11 +197,15 @@ struct Pipe {
 // only traffic and every workgroup asks at once.  Needs a mask, m a multiple of 128, a
 // pipelined variant, room in the LDS, at least kMaskLdsMinKB k-blocks and a row block whose
 // mask rows span less than 4 GB (host: mask_in_lds()).
+//
+// SHARED: the launch has several row blocks per column tile (m > 128).  They run on one XCD
+// at the same time, start at the same k-block and load without the streaming hint, so the
+// ciphertext tile comes over the fabric once and the other row blocks find it in the L2.
 constexpr int kMaskTileBytes = 128 * 64 * 8;
 constexpr int kMaskLoads = kMaskTileBytes / kTileBytes / 8;     // per wave: 8
 constexpr int kMaskPhase = kMaskLoads + 2;                      // iterations that count them
 
-template <int DX, int DQ, bool FULL, bool MASKLDS>
+template <int DX, int DQ, bool FULL, bool MASKLDS, bool SHARED>
 __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 {
     using P_ = Pipe<DX, DQ>;
@@ -217,8 +221,6 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     static_assert(!MASKLDS || (FULL && P_::PIPELINED && P_::LDS_BYTES + kMaskTileBytes <= 160 * 1024),
                   "mask tile in LDS: full row blocks, pipelined variant, and it must fit");
     __shared__ __attribute__((aligned(1024))) unsigned char lds[P_::LDS_BYTES + (MASKLDS ? kMaskTileBytes : 0)];
-    unsigned char *const ldsA = lds;
-    unsigned char *const ldsB = lds + RING * P_::A_BYTES;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // 0..7
@@ -226,21 +228,24 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
 
     // workgroup -> (64-column tile, row block).  Workgroups are dealt round-robin to
     // the 8 XCDs; the RB row blocks that share a column tile are kept on one XCD
-    // and adjacent in launch order so that tile is fetched from HBM once.
+    // and adjacent in launch order so that tile is fetched from HBM once.  (The
+    // column tiles past the last multiple of 8, if any, are not worth the trouble.)
     uint32_t ct2, rb;
     {
         const uint32_t id = blockIdx.x;
-        const uint32_t CT2 = a.CT >> 1;
-        if (a.RB == 1) {                            // one row block: no division
+        const uint32_t RB = (uint32_t)a.RB;
+        const uint32_t CT2a = (a.CT >> 1) & ~7u;
+        if (!SHARED) {                              // one row block: no division
             rb = 0;
             ct2 = id;
-        } else if ((CT2 & 7u) == 0) {
+        } else if (id < CT2a * RB) {
             const uint32_t xcd = id & 7u, slot = id >> 3;
-            rb = slot % (uint32_t)a.RB;
-            ct2 = (slot / (uint32_t)a.RB) * 8u + xcd;
+            rb = slot % RB;
+            ct2 = (slot / RB) * 8u + xcd;
         } else {
-            rb = id % (uint32_t)a.RB;
-            ct2 = id / (uint32_t)a.RB;
+            const uint32_t t = id - CT2a * RB;
+            rb = t % RB;
+            ct2 = CT2a + t / RB;
         }
     }
     const int RT = (a.m + kTile - 1) / kTile;       // row tiles that exist in the workspace
@@ -298,8 +303,9 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // Stage s of this workgroup is k-block (s + k_start) mod KB: the sum over k does not
     // care about the order, and workgroups that walk their (equally spaced) ciphertext
     // regions in lockstep would otherwise ask the same memory channels for data at the
-    // same moment.
-    uint32_t k_start = blockIdx.x - __umulhi(blockIdx.x, a.kb_magic) * (uint32_t)KB;   // id mod KB
+    // same moment.  The start depends on the column tile alone: row blocks that share a
+    // column tile walk it together.
+    uint32_t k_start = ct2 - __umulhi(ct2, a.kb_magic) * (uint32_t)KB;   // ct2 mod KB
     if (k_start >= (uint32_t)KB) k_start -= (uint32_t)KB;
     // Wave-uniform state of the issue side, for the next stage to issue: byte offset of
     // its k-block in the source, byte offset of its slot in the ring.  Carried and
@@ -318,7 +324,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     auto issue_one = [&](auto u_c) {
         constexpr int u = decltype(u_c)::value;
         unsigned char *const d = lds + (dst[u] + slot_off);
-        dma_tile(rsrc, lane16, toff[u] + src_off, d);
+        dma_tile<!SHARED>(rsrc, lane16, toff[u] + src_off, d);
     };
 #define NIMBUS_NEXT_ISSUE()                                                   \
     do {                                                                      \
@@ -537,7 +543,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
                 asm volatile("" ::: "memory");
                 if constexpr (MASKPHASE) {
                     if (t < kMaskLoads) {
-                        dma_tile(rsrc_m, voff_m, soff_m, lds + dst_m);
+                        dma_tile<true>(rsrc_m, voff_m, soff_m, lds + dst_m);
                         soff_m += 16u * a.C * 8u;
                         dst_m += 8u * kTileBytes;
                     }
@@ -549,7 +555,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
                     if constexpr (NPRE + j * SPAN / NITEMS == i) {
                         if constexpr (j < P_::MAXU) {
                             if (j < NMIN || j < n_loads)
-                                dma_tile(rsrc, lane16, toff[j] + src_off,
+                                dma_tile<!SHARED>(rsrc, lane16, toff[j] + src_off,
                                                 lds + (dst[j] + slot_off));
                         } else {
                             read_one(std::integral_constant<int, 1 - SET>{},
@@ -710,17 +716,20 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
     // mask tile in LDS: see the kernel; 128 rows of the mask must span less than 4 GB
     const bool mask_lds = kCanMaskLds && mask != nullptr && p.m % 128 == 0 &&
                           KB - P_::LEAD >= kMaskPhase && (uint64_t)p.C * 8u * 128u < (1ull << 32);
+    const bool full = p.m % 128 == 0;
+    auto launch = [&](auto full_c, auto masklds_c, auto shared_c) {
+        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, decltype(full_c)::value, decltype(masklds_c)::value,
+                                            decltype(shared_c)::value>),
+                           grid, dim3(512), 0, stream, a);
+        return hipGetLastError();
+    };
+    using T = std::true_type;
+    using F = std::false_type;
     if constexpr (kCanMaskLds) {
-        if (mask_lds) {
-            hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, true, true>), grid, dim3(512), 0, stream, a);
-            return hipGetLastError();
-        }
+        if (mask_lds) return a.RB > 1 ? launch(T{}, T{}, T{}) : launch(T{}, T{}, F{});
     }
-    if (p.m % 128 == 0)
-        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, true, false>), grid, dim3(512), 0, stream, a);
-    else
-        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, false, false>), grid, dim3(512), 0, stream, a);
-    return hipGetLastError();
+    if (a.RB > 1) return full ? launch(T{}, F{}, T{}) : launch(F{}, F{}, T{});
+    return full ? launch(T{}, F{}, F{}) : launch(F{}, F{}, F{});
 }
 
 hipError_t launch_cop_mfma(const Problem &p, const void *staged, const void *prepared,

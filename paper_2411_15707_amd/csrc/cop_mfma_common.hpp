@@ -144,15 +144,18 @@ __device__ __forceinline__ void wait_vmem()
 // one wave copies 64 x 16 B (a whole operand tile) from global memory straight into LDS;
 // lane l's bytes land at dst + l*16.  The source is a buffer descriptor (wave-uniform base)
 // plus a per-lane offset plus a wave-uniform offset: the address needs no vector arithmetic.
-// Every tile carries the streaming hint: the ciphertext planes are read once and should not
-// push the X planes out of L2, and for the X planes, which all workgroups of an XCD read
-// within a few microseconds of each other, the hint makes no measurable difference; one kind
-// of load lets all eight waves run the same instructions.
+// STREAM puts the streaming hint on the load.  With one row block per column tile every
+// ciphertext byte is read once and should not push the X planes out of L2 (for the X
+// planes, which all workgroups of an XCD read within a few microseconds of each other, the
+// hint makes no measurable difference, and one kind of load lets all eight waves run the
+// same instructions).  With several row blocks per column tile the hint is left off: the
+// tile has to stay in the XCD's L2 until the last of them has read it.
+template <bool STREAM>
 __device__ __forceinline__ void dma_tile(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_off,
                                          uint32_t uniform_off, void *dst_wave)
 {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (NIMBUS_AS3 void *)dst_wave, 16, lane_off,
-                                             uniform_off, 0, 2);
+                                             uniform_off, 0, STREAM ? 2 : 0);
 }
 
 // Wait until at most n of this wave's loads are pending, 0 <= n <= 63, n wave-uniform.
