@@ -1,10 +1,12 @@
 /*
  * nimbus_calib.h: calibration launches used by the benchmark, exported by the same shared
- * library as nimbus_cop.h.  They measure what the chip sustains on the two resources the
- * COP kernel is bounded by, so that its time can be set against measured ceilings as well
- * as against the published peaks.  Not part of the COP path; for callers that benchmark.
+ * library as nimbus_cop.h.  They measure what the chip sustains on the resources the
+ * kernels are bounded by (matrix cores and memory reads for the COP kernel, 64-bit integer
+ * arithmetic for the server-side transforms), so that their times can be set against
+ * measured ceilings as well as against the published peaks.  Not part of the COP path; for
+ * callers that benchmark.
  *
- * Both only enqueue one kernel on `stream` (a hipStream_t, NULL = default) and return at
+ * Each only enqueues one kernel on `stream` (a hipStream_t, NULL = default) and return at
  * once; the caller times them.  Pointers are DEVICE pointers owned by the caller.
  * Return value: the amount of work enqueued, or -1 for invalid arguments / a refused launch.
  */
@@ -33,6 +35,17 @@ long long nimbus_calib_mfma_i8(int workgroups, int iters, int random_operands, v
  * sink: at least 4 bytes.  Returns the number of bytes read.
  */
 long long nimbus_calib_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+
+/*
+ * Register-only loop of the transform butterfly of the server side (Algorithm 1 steps 1
+ * and 5 multiply polynomials in the number-theoretic-transform domain, Appendix B.1): every
+ * thread of `workgroups` workgroups of 256 runs `iters` rounds of 12 lazy butterflies
+ * (three stages over eight values) modulo the odd q < 2^62, with no memory access in the
+ * loop.  sink: at least workgroups * 2048 bytes, written once.
+ * Returns the number of butterflies enqueued.
+ */
+long long nimbus_calib_butterflies(int workgroups, int iters, unsigned long long q, void *sink,
+                                   size_t sink_bytes, void *stream);
 
 #ifdef __cplusplus
 }

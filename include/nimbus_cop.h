@@ -41,8 +41,22 @@
  * residues of ctW and mask < q_l.
  *
  * Errors: every function returning int gives NIMBUS_COP_OK (0) or a negative
- * code; on any error nothing was enqueued and `out` is untouched.  No C++
+ * code.  Every code but NIMBUS_COP_ERR_LAUNCH is found on the host before
+ * anything is enqueued: `out` is untouched.  NIMBUS_COP_ERR_LAUNCH means that
+ * the HIP runtime refused a kernel launch; an entry point that launches more
+ * than one kernel (nimbus_cop_matmul_prepared and its _static variant,
+ * nimbus_cop_prepare, nimbus_cop_check_inputs, and the staged entry points
+ * for shares of more than 32 bits) may then already have enqueued the earlier
+ * ones, and what its outputs and workspace hold is unspecified.  No C++
  * exception crosses this boundary.
+ *
+ * Loading: the library links the HIP runtime (libamdhip64) by name.  A process
+ * must map ONE copy of that runtime: device pointers and streams made by one
+ * copy mean nothing to another, and the first launch fails.  A host program
+ * that brings its own copy (PyTorch loads the one in its wheel by path) has to
+ * load it BEFORE this library, so that the dynamic linker resolves this
+ * library's dependency to the copy already mapped; the Python binding imports
+ * torch first for that reason.
  *
  * Accepted parameters: m, k, n >= 1; N a power of two in [32, 65536];
  * L in [1, 4]; x_bits in [1, 32] with every q_l odd and 2^x_bits < q_l < 2^62;
@@ -191,6 +205,11 @@ int nimbus_cop_matmul_prepared_static(const uint64_t *X, int m, int k, int x_bit
  *           < q_l, or NULL for no mask
  *   packed  device [T][2][L][N], canonical residues; must not alias rows
  *   nimbus_cop_packed_count  T = ceil(m / floor(N/n)); 0 for invalid arguments or n > N
+ * For N/2 < n <= N there is one row per ciphertext (P = 1, T = m) and nothing to merge: a
+ * caller then passes the mask to the matmul entry point, whose epilogue adds it, and does
+ * not call nimbus_cop_pack at all.  (The call is still accepted; it then is a masked copy.)
+ * A caller who does pack (P >= 2) passes mask = NULL to the matmul and the mask to
+ * nimbus_cop_pack: Algorithm 1 masks once, after the packing.
  * Errors: NIMBUS_COP_ERR_INVALID_ARG as for the other entry points;
  * NIMBUS_COP_ERR_UNSUPPORTED for n > N (several chunks: there is nothing to pack) and
  * for more than 65535 packed ciphertexts.  On error nothing is enqueued.

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     nimbus_cop_workspace_bytes,
     EXPORTED_SYMBOLS,
     CALIBRATION_SYMBOLS,
+    nimbus_calib_butterflies,
     nimbus_calib_mfma_i8,
     nimbus_calib_stream_read,
     LOADER_SYMBOLS,

@@ -32,7 +32,8 @@ EXPORTED_SYMBOLS = (
 )
 
 
-CALIBRATION_SYMBOLS = ("nimbus_calib_mfma_i8", "nimbus_calib_stream_read")
+CALIBRATION_SYMBOLS = ("nimbus_calib_mfma_i8", "nimbus_calib_stream_read",
+                       "nimbus_calib_butterflies")
 
 LOADER_SYMBOLS = (
     "nimbus_loader_create",
@@ -106,6 +107,8 @@ def load_library():
     lib.nimbus_calib_mfma_i8.argtypes = [ci, ci, ci, vp, sz, vp]
     lib.nimbus_calib_stream_read.restype = ctypes.c_longlong
     lib.nimbus_calib_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.nimbus_calib_butterflies.restype = ctypes.c_longlong
+    lib.nimbus_calib_butterflies.argtypes = [ci, ci, ctypes.c_ulonglong, vp, sz, vp]
     lib.nimbus_rlwe_tables_bytes.restype = sz
     lib.nimbus_rlwe_tables_bytes.argtypes = [ci, ci]
     lib.nimbus_rlwe_setup.restype = ci
@@ -324,6 +327,15 @@ def nimbus_calib_mfma_i8(workgroups, iters, random_operands, sink, stream=None) 
     if ops < 0:
         raise NimbusCopError(NIMBUS_INVALID, "nimbus_calib_mfma_i8")
     return int(ops)
+
+
+def nimbus_calib_butterflies(workgroups, iters, q, sink, stream=None) -> int:
+    """enqueue the register-only transform-butterfly loop; returns the butterflies enqueued"""
+    n = load_library().nimbus_calib_butterflies(workgroups, iters, int(q), _dev_ptr(sink, "sink"),
+                                                sink.numel() * sink.element_size(), _stream(stream))
+    if n < 0:
+        raise NimbusCopError(NIMBUS_INVALID, "nimbus_calib_butterflies")
+    return int(n)
 
 
 def nimbus_calib_stream_read(src, sink, stream=None) -> int:

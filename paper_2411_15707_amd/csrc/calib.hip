@@ -7,8 +7,13 @@
 //    digit products), with zero or with random operand bytes.  The sustained rate depends
 //    on the operand values (the chip lowers its clock under load), so both are measured.
 //  * HBM read rate: a grid-stride read of a buffer with 16-byte loads.
+//  * butterfly rate: a register-only loop of the number-theoretic transform's butterfly as
+//    the server-side kernels compute it (Appendix B.1: ciphertext polynomials are multiplied
+//    in the transform domain), eight values and three stages per thread: what the vector
+//    ALUs sustain on that mix of 64-bit integer work when no memory is involved.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "cop_common.hpp"
 #include "../../include/nimbus_calib.h"
 
 namespace {
@@ -60,6 +65,46 @@ __global__ __launch_bounds__(256) void calib_read_kernel(const u32x4 *__restrict
     if (acc == 0x9e3779b9u) sink[0] = acc;      // keeps the loads alive, (almost) never taken
 }
 
+// Harvey-style lazy butterfly on values < 4q, q < 2^62: w a table value, ws = floor(w 2^64 / q).
+// The same arithmetic as the transform kernels, written out here so that the calibration
+// stands on its own.
+__device__ __forceinline__ void butterfly(uint64_t &a, uint64_t &b, uint64_t w, uint64_t ws,
+                                          uint64_t q, uint64_t two_q)
+{
+    const uint64_t u = a >= two_q ? a - two_q : a;
+    const uint64_t v = b * w - __umul64hi(b, ws) * q;
+    a = u + v;
+    b = u - v + two_q;
+}
+
+__global__ __launch_bounds__(256) void calib_butterfly_kernel(int iters, uint64_t q, uint64_t *sink)
+{
+    const uint32_t seed = blockIdx.x * 256u + threadIdx.x;
+    uint64_t x[8], w[7], ws[7];
+    for (int i = 0; i < 8; ++i) x[i] = (((uint64_t)mix32(seed * 8u + i) << 32) | mix32(seed + 77u * i)) % q;
+    for (int i = 0; i < 7; ++i) {
+        w[i] = (((uint64_t)mix32(seed * 7u + i + 100u) << 32) | mix32(seed + 13u * i)) % q;
+        ws[i] = (uint64_t)(((unsigned __int128)w[i] << 64) / q);
+    }
+    const uint64_t two_q = 2 * q;
+    for (int it = 0; it < iters; ++it) {
+        // stages of distance 4, 2, 1 over the thread's eight values: 12 butterflies
+#pragma unroll
+        for (int st = 0; st < 3; ++st) {
+            const int half = 4 >> st;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                if (r & half) continue;
+                const int t = (1 << st) - 1 + (r >> (3 - st));
+                butterfly(x[r], x[r + half], w[t], ws[t], q, two_q);
+            }
+        }
+    }
+    uint64_t s = 0;
+    for (int i = 0; i < 8; ++i) s ^= x[i];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace
 
 extern "C" {
@@ -69,9 +114,9 @@ long long nimbus_calib_mfma_i8(int workgroups, int iters, int random_operands, v
 {
     if (workgroups < 1 || workgroups > 65535 || iters < 1 || !sink) return -1;
     if (sink_bytes < (size_t)workgroups * 256u * sizeof(int)) return -1;
-    hipLaunchKernelGGL(calib_mfma_kernel, dim3((uint32_t)workgroups), dim3(256), 0,
-                       (hipStream_t)stream, iters, random_operands, (int *)sink);
-    if (hipGetLastError() != hipSuccess) return -1;
+    if (nimbus::launch(calib_mfma_kernel, dim3((uint32_t)workgroups), dim3(256), (hipStream_t)stream,
+                       iters, random_operands, (int *)sink) != hipSuccess)
+        return -1;
     // int8 operations issued: 4 waves x iters x 21 instructions x 2 * 32*32*32 each
     return (long long)workgroups * 4ll * iters * 21ll * 65536ll;
 }
@@ -80,10 +125,22 @@ long long nimbus_calib_stream_read(const void *src, size_t bytes, void *sink, vo
 {
     if (!src || !sink || bytes < 16 || ((uintptr_t)src & 15u) != 0) return -1;
     const size_t n16 = bytes / 16;
-    hipLaunchKernelGGL(calib_read_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream,
-                       (const u32x4 *)src, n16, (uint32_t *)sink);
-    if (hipGetLastError() != hipSuccess) return -1;
+    if (nimbus::launch(calib_read_kernel, dim3(256 * 16), dim3(256), (hipStream_t)stream,
+                       (const u32x4 *)src, n16, (uint32_t *)sink) != hipSuccess)
+        return -1;
     return (long long)(n16 * 16);
+}
+
+long long nimbus_calib_butterflies(int workgroups, int iters, unsigned long long q, void *sink,
+                                   size_t sink_bytes, void *stream)
+{
+    if (workgroups < 1 || workgroups > 65535 || iters < 1 || !sink) return -1;
+    if (q < 3 || (q & 1u) == 0 || q >= (1ull << 62)) return -1;
+    if (sink_bytes < (size_t)workgroups * 256u * sizeof(uint64_t)) return -1;
+    if (nimbus::launch(calib_butterfly_kernel, dim3((uint32_t)workgroups), dim3(256), (hipStream_t)stream,
+                       iters, (uint64_t)q, (uint64_t *)sink) != hipSuccess)
+        return -1;
+    return (long long)workgroups * 256ll * iters * 12ll;
 }
 
 }  // extern "C"

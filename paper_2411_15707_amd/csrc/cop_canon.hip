@@ -404,14 +404,10 @@ static hipError_t canon_impl(const Problem &p, const uint64_t *X, const uint64_t
     const dim3 grid((ca.e.CT / 2) * (uint32_t)ca.e.RB);
     const bool full = p.m % 128 == 0, shared = ca.e.RB > 1;
     if (full && shared)
-        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, true, true>), grid, dim3(512), 0, stream, ca);
-    else if (full)
-        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, true, false>), grid, dim3(512), 0, stream, ca);
-    else if (shared)
-        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, false, true>), grid, dim3(512), 0, stream, ca);
-    else
-        hipLaunchKernelGGL((cop_canon_kernel<DX, DQ, false, false>), grid, dim3(512), 0, stream, ca);
-    return hipGetLastError();
+        return launch(cop_canon_kernel<DX, DQ, true, true>, grid, dim3(512), stream, ca);
+    if (full) return launch(cop_canon_kernel<DX, DQ, true, false>, grid, dim3(512), stream, ca);
+    if (shared) return launch(cop_canon_kernel<DX, DQ, false, true>, grid, dim3(512), stream, ca);
+    return launch(cop_canon_kernel<DX, DQ, false, false>, grid, dim3(512), stream, ca);
 }
 
 hipError_t launch_cop_canon(const Problem &p, const uint64_t *X, const uint64_t *ctW,

@@ -53,19 +53,21 @@ hipError_t launch_cop_check(const Problem &p, const uint64_t *X, const uint64_t 
     int log_n = 0;
     while ((1 << log_n) < p.N) ++log_n;
     // (a fill kernel, not a memset: callers may record this into a graph)
-    hipLaunchKernelGGL(check_clear_kernel, dim3(1), dim3(64), 0, stream, v);
+    hipError_t e = launch(check_clear_kernel, dim3(1), dim3(64), stream, v);
+    if (e != hipSuccess) return e;
     const uint64_t nx = (uint64_t)p.m * (uint64_t)p.k;
-    hipLaunchKernelGGL(check_shares_kernel, dim3(blocks_for(nx)), dim3(256), 0, stream, X, nx,
-                       p.x_bits, v + 0);
+    e = launch(check_shares_kernel, dim3(blocks_for(nx)), dim3(256), stream, X, nx, p.x_bits, v + 0);
+    if (e != hipSuccess) return e;
     const uint64_t nw = (uint64_t)p.k * p.C;
-    hipLaunchKernelGGL(check_residues_kernel, dim3(blocks_for(nw)), dim3(256), 0, stream, ctW, nw,
-                       (uint32_t)p.C, log_n, p.L, p.limbs, v + 1);
+    e = launch(check_residues_kernel, dim3(blocks_for(nw)), dim3(256), stream, ctW, nw,
+               (uint32_t)p.C, log_n, p.L, p.limbs, v + 1);
+    if (e != hipSuccess) return e;
     if (mask) {
         const uint64_t nm = (uint64_t)p.m * p.C;
-        hipLaunchKernelGGL(check_residues_kernel, dim3(blocks_for(nm)), dim3(256), 0, stream, mask,
-                           nm, (uint32_t)p.C, log_n, p.L, p.limbs, v + 2);
+        e = launch(check_residues_kernel, dim3(blocks_for(nm)), dim3(256), stream, mask, nm,
+                   (uint32_t)p.C, log_n, p.L, p.limbs, v + 2);
     }
-    return hipGetLastError();
+    return e;
 }
 
 }  // namespace nimbus

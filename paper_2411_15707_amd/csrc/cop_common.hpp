@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <type_traits>
 
 namespace nimbus {
 
@@ -75,5 +76,16 @@ hipError_t launch_cop_check(const Problem &p, const uint64_t *X, const uint64_t 
                             const uint64_t *mask, uint64_t *violations, hipStream_t stream);
 hipError_t launch_cop_pack(const Problem &p, const uint64_t *rows, const uint64_t *mask,
                            uint64_t *packed, hipStream_t stream);
+
+// Launches a kernel and returns the status of this launch alone.  (The status the runtime
+// keeps per thread would also hand out, and clear, an error that an unrelated earlier call
+// left behind.)
+template <typename... KArgs>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream,
+                         std::common_type_t<KArgs>... args)
+{
+    void *ptrs[] = {(void *)&args...};
+    return hipLaunchKernel((const void *)kernel, grid, block, ptrs, 0, stream);
+}
 
 }  // namespace nimbus

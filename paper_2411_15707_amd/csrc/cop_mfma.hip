@@ -657,13 +657,12 @@ static hipError_t prepare_impl(const Problem &p, const uint64_t *ctW, void *prep
     const uint64_t total = (uint64_t)CT * KB * 64;
     uint4 *planes = (uint4 *)prepared;
     uint64_t *colsum = (uint64_t *)((char *)prepared + (size_t)CT * KB * DQ * kTileBytes);
-    hipLaunchKernelGGL(prepare_planes_kernel<DQ>, dim3((unsigned)((total + 255) / 256)), dim3(256),
-                       0, stream, ctW, p.k, (uint32_t)p.C, p.N, p.L, p.limbs, KB, total, planes);
-    hipError_t e = hipGetLastError();
+    const hipError_t e =
+        launch(prepare_planes_kernel<DQ>, dim3((unsigned)((total + 255) / 256)), dim3(256), stream,
+               ctW, p.k, (uint32_t)p.C, p.N, p.L, p.limbs, KB, total, planes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(column_sums_kernel, dim3((unsigned)((p.C + 255) / 256)), dim3(256), 0,
-                       stream, ctW, p.k, (uint32_t)p.C, p.N, p.L, p.limbs, colsum);
-    return hipGetLastError();
+    return launch(column_sums_kernel, dim3((unsigned)((p.C + 255) / 256)), dim3(256), stream,
+                  ctW, p.k, (uint32_t)p.C, p.N, p.L, p.limbs, colsum);
 }
 
 hipError_t launch_prepare(const Problem &p, const uint64_t *ctW, void *prepared,
@@ -680,10 +679,9 @@ static hipError_t stage_impl(const Problem &p, const uint64_t *X, int half_shift
     const int KB = kblocks(p.k);
     const int RT = (p.m + kTile - 1) / kTile;
     const uint32_t xtotal = (uint32_t)RT * KB * 256;
-    hipLaunchKernelGGL(x_planes_kernel<DX>, dim3((xtotal + 255) / 256), dim3(256), 0, stream,
-                       X, p.m, p.k, KB, xtotal, share_offset(p.x_bits, DX), half_shift,
-                       (uint32_t *)workspace);
-    return hipGetLastError();
+    return launch(x_planes_kernel<DX>, dim3((xtotal + 255) / 256), dim3(256), stream,
+                  X, p.m, p.k, KB, xtotal, share_offset(p.x_bits, DX), half_shift,
+                  (uint32_t *)workspace);
 }
 
 // p.x_bits (<= 32) is the width of the half that is staged; half_shift is 0 or 32
@@ -718,10 +716,9 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
                           KB - P_::LEAD >= kMaskPhase && (uint64_t)p.C * 8u * 128u < (1ull << 32);
     const bool full = p.m % 128 == 0;
     auto launch = [&](auto full_c, auto masklds_c, auto shared_c) {
-        hipLaunchKernelGGL((cop_mfma_kernel<DX, DQ, decltype(full_c)::value, decltype(masklds_c)::value,
-                                            decltype(shared_c)::value>),
-                           grid, dim3(512), 0, stream, a);
-        return hipGetLastError();
+        return nimbus::launch(cop_mfma_kernel<DX, DQ, decltype(full_c)::value,
+                                              decltype(masklds_c)::value, decltype(shared_c)::value>,
+                              grid, dim3(512), stream, a);
     };
     using T = std::true_type;
     using F = std::false_type;

@@ -64,9 +64,7 @@ hipError_t launch_cop_pack(const Problem &p, const uint64_t *rows, const uint64_
     a.T = (p.m + a.P - 1) / a.P;
     for (int l = 0; l < p.L; ++l) a.q[l] = p.limbs.limb[l].q;
     const uint32_t words = 2u * (uint32_t)p.L * (uint32_t)p.N;
-    hipLaunchKernelGGL(cop_pack_kernel, dim3((words + 255) / 256, (uint32_t)a.T), dim3(256), 0,
-                       stream, a);
-    return hipGetLastError();
+    return launch(cop_pack_kernel, dim3((words + 255) / 256, (uint32_t)a.T), dim3(256), stream, a);
 }
 
 }  // namespace nimbus

@@ -86,9 +86,8 @@ hipError_t launch_cop_valu(const Problem &p, const uint64_t *X, const uint64_t *
     const int sh = 32 - p.x_bits;                   // x_bits in [1, 32]
     const int kblk = 1 << (sh > 30 ? 30 : sh);
     dim3 grid((unsigned)((p.C + 255) / 256), (unsigned)((p.m + RT - 1) / RT));
-    hipLaunchKernelGGL(cop_valu_kernel<RT>, grid, dim3(256), 0, stream,
-                       X, p.m, p.k, kblk, ctW, (uint32_t)p.C, p.N, p.L, p.limbs, mask, out);
-    return hipGetLastError();
+    return launch(cop_valu_kernel<RT>, grid, dim3(256), stream,
+                  X, p.m, p.k, kblk, ctW, (uint32_t)p.C, p.N, p.L, p.limbs, mask, out);
 }
 
 }  // namespace nimbus

@@ -879,16 +879,16 @@ static int scaling(int L, const uint64_t *moduli, int t_bits, Scaling *out)
 
 #define NIMBUS_RLWE_DISPATCH(logN, CALL)                                          \
     switch (logN) {                                                               \
-    case 5: { constexpr int LOGN = 5; CALL; break; }                              \
-    case 6: { constexpr int LOGN = 6; CALL; break; }                              \
-    case 7: { constexpr int LOGN = 7; CALL; break; }                              \
-    case 8: { constexpr int LOGN = 8; CALL; break; }                              \
-    case 9: { constexpr int LOGN = 9; CALL; break; }                              \
-    case 10: { constexpr int LOGN = 10; CALL; break; }                            \
-    case 11: { constexpr int LOGN = 11; CALL; break; }                            \
-    case 12: { constexpr int LOGN = 12; CALL; break; }                            \
-    case 13: { constexpr int LOGN = 13; CALL; break; }                            \
-    case 14: { constexpr int LOGN = 14; CALL; break; }                            \
+    case 5: { constexpr int LOGN = 5; return CALL; }                              \
+    case 6: { constexpr int LOGN = 6; return CALL; }                              \
+    case 7: { constexpr int LOGN = 7; return CALL; }                              \
+    case 8: { constexpr int LOGN = 8; return CALL; }                              \
+    case 9: { constexpr int LOGN = 9; return CALL; }                              \
+    case 10: { constexpr int LOGN = 10; return CALL; }                            \
+    case 11: { constexpr int LOGN = 11; return CALL; }                            \
+    case 12: { constexpr int LOGN = 12; return CALL; }                            \
+    case 13: { constexpr int LOGN = 13; return CALL; }                            \
+    case 14: { constexpr int LOGN = 14; return CALL; }                            \
     default: return hipErrorInvalidValue;                                         \
     }
 
@@ -896,36 +896,30 @@ static hipError_t launch_secret(const RlweArgs &a, int logN, int L, const int8_t
                                 Twiddle *tables, hipStream_t stream)
 {
     if (logN == 15) {
-        hipLaunchKernelGGL((rlwe_secret_kernel<15, 1>), dim3(2u * (unsigned)L),
-                           dim3(threads_for(14, 4)), 0, stream, a, s, tables);
-        return hipGetLastError();
+        return launch(rlwe_secret_kernel<15, 1>, dim3(2u * (unsigned)L), dim3(threads_for(14, 4)),
+                      stream, a, s, tables);
     }
-    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL((rlwe_secret_kernel<LOGN, 0>), dim3((unsigned)L),
-                                                  dim3(threads_for(LOGN, 4)), 0, stream, a, s, tables));
-    return hipGetLastError();
+    NIMBUS_RLWE_DISPATCH(logN, launch(rlwe_secret_kernel<LOGN, 0>, dim3((unsigned)L),
+                                      dim3(threads_for(LOGN, 4)), stream, a, s, tables));
 }
 
 template <bool ENCRYPT, int MAXS>
 static hipError_t launch_poly_with(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
 {
-    NIMBUS_RLWE_DISPATCH(logN, hipLaunchKernelGGL((rlwe_poly_kernel<LOGN, 0, MAXS, ENCRYPT>),
-                                                  dim3((unsigned)polys),
-                                                  dim3(threads_for(LOGN, MAXS)), 0, stream, a));
-    return hipGetLastError();
+    NIMBUS_RLWE_DISPATCH(logN, launch(rlwe_poly_kernel<LOGN, 0, MAXS, ENCRYPT>, dim3((unsigned)polys),
+                                      dim3(threads_for(LOGN, MAXS)), stream, a));
 }
 
 // ring of 2^15 coefficients: two workgroups per polynomial, then the joining pass
 template <bool ENCRYPT>
 static hipError_t launch_poly_in_parts(const PolyArgs &a, size_t polys, hipStream_t stream)
 {
-    hipLaunchKernelGGL((rlwe_poly_kernel<15, 1, 4, ENCRYPT>), dim3(2u * (unsigned)polys),
-                       dim3(threads_for(14, 4)), 0, stream, a);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT>, dim3(2u * (unsigned)polys),
+                                dim3(threads_for(14, 4)), stream, a);
     if (e != hipSuccess) return e;
     const uint64_t pairs = (uint64_t)polys << 14;
-    hipLaunchKernelGGL(rlwe_join_kernel<ENCRYPT>, dim3((unsigned)((pairs + 255u) / 256u)), dim3(256), 0,
-                       stream, a, 15, pairs);
-    return hipGetLastError();
+    return launch(rlwe_join_kernel<ENCRYPT>, dim3((unsigned)((pairs + 255u) / 256u)), dim3(256),
+                  stream, a, 15, pairs);
 }
 
 // Stages per round by ring degree and batch size (one workgroup per polynomial, 256 compute
@@ -937,14 +931,10 @@ template <bool ENCRYPT>
 static hipError_t launch_poly(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
 {
     if (logN == 15) return launch_poly_in_parts<ENCRYPT>(a, polys, stream);
-#ifdef NIMBUS_RLWE_FORCE_MAXS
-    return launch_poly_with<ENCRYPT, NIMBUS_RLWE_FORCE_MAXS>(a, logN, polys, stream);
-#else
     const int maxs = polys >= 1024 ? stages_large_batch(logN) : stages_small_batch(logN);
     if (maxs == 4) return launch_poly_with<ENCRYPT, 4>(a, logN, polys, stream);
     if (maxs == 3) return launch_poly_with<ENCRYPT, 3>(a, logN, polys, stream);
     return launch_poly_with<ENCRYPT, 2>(a, logN, polys, stream);
-#endif
 }
 
 }  // namespace nimbus
@@ -979,9 +969,9 @@ int nimbus_rlwe_setup(int N, int L, const uint64_t *moduli, const int8_t *s,
     }
     const int logN = log2_exact(N);
     const unsigned total = (unsigned)N * (unsigned)L;
-    hipLaunchKernelGGL(rlwe_powers_kernel, dim3((total + 255u) / 256u), dim3(256), 0,
-                       (hipStream_t)stream, a, logN, L, (Twiddle *)tables);
-    if (hipGetLastError() != hipSuccess) return NIMBUS_COP_ERR_LAUNCH;
+    if (launch(rlwe_powers_kernel, dim3((total + 255u) / 256u), dim3(256), (hipStream_t)stream,
+               a, logN, L, (Twiddle *)tables) != hipSuccess)
+        return NIMBUS_COP_ERR_LAUNCH;
     const hipError_t e = launch_secret(a, logN, L, s, (Twiddle *)tables, (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
@@ -1031,6 +1021,7 @@ int nimbus_rlwe_decode(const uint64_t *phi, int T, int N, int L, const uint64_t 
     if (ranges_overlap(m_hat, (size_t)total * sizeof(uint64_t), phi, (size_t)total * (size_t)L * sizeof(uint64_t)))
         return NIMBUS_COP_ERR_INVALID_ARG;
     const dim3 grid((unsigned)((total + 255u) / 256u));
+    hipError_t e;
     if (L <= 2) {
         DecodeArgs a{};
         a.phi = phi;
@@ -1049,7 +1040,7 @@ int nimbus_rlwe_decode(const uint64_t *phi, int T, int N, int L, const uint64_t 
         a.half_lo = sc.half.w[0];
         a.delta_inv = sc.delta_inv;
         a.t_mask = (1ull << t_bits) - 1;
-        hipLaunchKernelGGL(rlwe_decode_kernel, grid, dim3(256), 0, (hipStream_t)stream, a);
+        e = launch(rlwe_decode_kernel, grid, dim3(256), (hipStream_t)stream, a);
     } else {
         DecodeWideArgs a{};
         a.phi = phi;
@@ -1066,9 +1057,9 @@ int nimbus_rlwe_decode(const uint64_t *phi, int T, int N, int L, const uint64_t 
         }
         a.delta_inv = sc.delta_inv;
         a.t_mask = (1ull << t_bits) - 1;
-        hipLaunchKernelGGL(rlwe_decode_wide_kernel, grid, dim3(256), 0, (hipStream_t)stream, a);
+        e = launch(rlwe_decode_wide_kernel, grid, dim3(256), (hipStream_t)stream, a);
     }
-    return hipGetLastError() == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 
 int nimbus_rlwe_decrypt(const uint64_t *ct, int T, int N, int L, const uint64_t *moduli,

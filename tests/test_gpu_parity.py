@@ -420,6 +420,12 @@ def test_calibration_launches_run():
     torch.cuda.synchronize()
     with pytest.raises(nc.NimbusCopError):
         nc.nimbus_calib_mfma_i8(8, 3, 1, sink[:16])        # sink too small: refused on the host
+    bsink = torch.zeros(8 * 256, dtype=torch.int64, device="cuda")
+    assert nc.nimbus_calib_butterflies(8, 5, (1 << 54) - 33, bsink) == 8 * 256 * 5 * 12
+    torch.cuda.synchronize()
+    assert int((bsink != 0).sum()) > 8 * 256 // 2          # the loop ran and wrote its values
+    with pytest.raises(nc.NimbusCopError):
+        nc.nimbus_calib_butterflies(8, 5, 1 << 54, bsink)  # even modulus: refused on the host
 
 
 @pytest.mark.parametrize("t_bits,q_bits", [(32, 62), (20, 54), (16, 50)])
