@@ -231,7 +231,13 @@ def main():
     # configs 1-4, slightly before the matrix cores; the matrix cores for config 5, m = 512)
     t_hbm = alg_bytes / (HBM_PEAK_GBPS * 1e9)
     t_mfma = i8_ops / (INT8_PEAK_TOPS * 1e12)
-    roofline = {"kernel": f"cop_mfma_kernel<{DX},{DQ},{'true' if m % 128 == 0 else 'false'}>"}
+    # the instance the library launches for this shape (share planes, ciphertext planes, m a
+    # multiple of 128, mask tile through LDS, several row blocks per column tile)
+    full = m % 128 == 0
+    pipelined = (DX + DQ - 1) * 16 + 2 * (DX + DQ) * 4 + 12 <= 256
+    mask_lds = full and pipelined and -(-k // 32) - 3 >= 10 and C * 8 * 128 < (1 << 32)
+    flags = ",".join("true" if f else "false" for f in (full, mask_lds, m > 128))
+    roofline = {"kernel": f"cop_mfma_kernel<{DX},{DQ},{flags}>"}
     if t_hbm >= t_mfma:
         roofline.update({"bound": "hbm", "achieved": round(achieved_gbps, 1), "peak": HBM_PEAK_GBPS,
                          "unit": "GB/s", "frac": round(achieved_gbps / HBM_PEAK_GBPS, 4)})
@@ -290,7 +296,7 @@ def main():
     valu_ms = timed_entry(nc.nimbus_cop_matmul_valu, 5)
     canonical = {
         "entry_point": "nimbus_cop_matmul",
-        "kernel": f"cop_canon_kernel<{DX},{DQ},{'true' if m % 128 == 0 else 'false'}>",
+        "kernel": f"cop_canon_kernel<{DX},{DQ},{'true' if m % 128 == 0 else 'false'},{'true' if m > 128 else 'false'}>",
         "kernel_ms_avg": round(canon_ms, 5),
         "value": round(cfg.mod_macs / (canon_ms * 1e-3), 1),
         "algorithmic_bytes_per_launch": alg_bytes,

@@ -139,28 +139,35 @@ __global__ __launch_bounds__(256) void x_planes_kernel(
 // and 2*DQ operand tiles of ciphertext planes (14 KB for DQ = 7), each in an LDS ring of
 // its own.  Both are filled by direct-to-LDS loads of whole tiles (64 lanes x 16 B; the
 // texture address unit spends the same time on narrower loads); nothing passes through
-// registers on the way in.  The X tiles of a stage are dealt to waves 0-3, the ciphertext
-// tiles to waves 4-7 (one wave of each kind per SIMD).  A wave knows how many loads it
-// issues per stage, so "stage s has landed" is a wait on the number of its younger loads,
-// then the barrier.
+// registers on the way in.  Wave w < 4 loads the DX planes of row tile w, waves 4 and 5
+// the two halves of the planes of the first column tile, waves 6 and 7 those of the
+// second (one wave of each kind per SIMD, at most four loads per wave and stage).  A load
+// is a buffer load: descriptor with the workgroup's base, the lane's 16 bytes, and one
+// wave-uniform offset that is carried from stage to stage, so issuing it costs no vector
+// arithmetic.  A wave knows how many loads it issues per stage, so "stage s has landed"
+// is a wait on the number of its younger loads, then the barrier.
 //
 // Inside a wave the loop is software pipelined: the LDS reads of stage s+1 are issued
 // between the matrix-core instructions of stage s, into the other of two operand sets.
+// The steady state is one branch-free body that every wave runs: loads and reads sit at
+// fixed places between the matrix-core instructions, the first few products of an
+// iteration (whose operands were read during the iteration before) run in front of its
+// barrier, and only the first and the last iterations are peeled.
 //
 // What the loop is bound by (measured).  Its duration follows the operand values: the
-// chip lowers its clock under the combined matrix-core and memory load, and a k-block
-// costs the matrix-core time of its 42 instructions per SIMD at the rate a register-only
-// loop reaches on random bytes, plus a memory-side term; the two add up instead of
-// overlapping.  Within that, what the schedule has to respect: enough bytes in flight per
-// CU (a streaming read reaches 3.9 TB/s chip-wide with 8 KB in flight per CU, 6.5 with 16 KB,
-// 7.0 from 32 KB on, direct-to-LDS and register loads alike; two to three stages of 26 KB
-// are in flight here), the ciphertext loads spread over the iteration, where the other
-// wave of the SIMD can fill a gap with its own matrix-core instructions, and
-// instruction issue (a wave issues an instruction every four or five
-// cycles at best and all eight waves run in lockstep between barriers, so every scalar
-// instruction costs: one stage issued per iteration from the first iteration on,
-// ring offsets carried and wrapped instead of recomputed, and the wait for "at most n
-// loads pending", an immediate of the instruction, done by a computed jump).
+// chip lowers its clock under the combined matrix-core and memory load (1.5 to 1.8 GHz
+// here against the 2.4 GHz of the data sheet), and a k-block costs the matrix-core time
+// of its 42 instructions per SIMD, 1344 cycles, plus about a tenth.  Fewer cycles do
+// not translate one to one: the chip answers a denser loop with a lower clock.  What the
+// schedule has to respect: enough bytes in flight per CU (a streaming read reaches
+// 3.9 TB/s chip-wide with 8 KB in flight per CU, 6.5 with 16 KB, 7.0 from 32 KB on,
+// direct-to-LDS and register loads alike; three stages of 26 KB are in flight here), the
+// ciphertext loads spread over the iteration, where the other wave of the SIMD can fill a
+// gap with its own matrix-core instructions, and instruction issue (all eight waves run
+// in lockstep between barriers, so every scalar instruction costs: ring offsets carried
+// and wrapped instead of recomputed, and the wait for "at most n loads pending", an
+// immediate of the instruction, done by a compare chain over the two or three counts
+// that can occur).
 
 template <int DX, int DQ>
 struct Pipe {
@@ -179,7 +186,7 @@ struct Pipe {
     static constexpr int LEAD = 3;
     static constexpr int RING = LEAD + 1 - AHEAD;
     static_assert(LEAD >= 1 + AHEAD, "the stage read next must have been issued");
-    // X tile t goes to wave t % 4 as its load t / 4, ciphertext tile t to wave 4 + t % 4
+    // load slots per wave and stage: a row tile's DX planes, or half of a column tile's DQ
     static constexpr int MAXU = ((A_TILES > B_TILES ? A_TILES : B_TILES) + 3) / 4;
     static_assert((LEAD - 1) * MAXU <= 63, "pending-load count must fit the wait counter");
     static constexpr int LDS_BYTES = RING * (A_BYTES + B_BYTES);
