@@ -68,6 +68,17 @@ SMALL = [
     (128, 65, 64, 64, 2, 24, 62),       # 3 x 8
     (128, 64, 32, 32, 1, 32, 62),       # 4 x 8, smallest ring
     (256, 100, 64, 64, 2, 20, 54),      # two full row blocks
+    # the mask tile through LDS (m a multiple of 128, at least 13 k-blocks) for the plane counts
+    # the BERT-shaped configs do not reach, alone and with several row blocks per column tile
+    (128, 512, 64, 64, 1, 16, 50),      # 2 x 7
+    (128, 448, 64, 64, 1, 16, 62),      # 2 x 8
+    (256, 480, 64, 64, 1, 16, 50),      # 2 x 7, two row blocks
+    (256, 417, 64, 64, 1, 16, 62),      # 2 x 8, two row blocks, ragged k
+    (384, 512, 128, 128, 2, 20, 54),    # 3 x 7, three row blocks
+    # row blocks dealt to the XCDs: 8 and 12 column-tile pairs (a whole round, a round and a tail)
+    (256, 100, 256, 256, 1, 20, 54),
+    (384, 70, 128, 128, 3, 20, 54),
+    (200, 500, 256, 256, 1, 16, 50),    # ragged m with two row blocks, 16 k-blocks
     # the ends of the accepted ranges
     (6, 50, 64, 64, 4, 20, 54),         # four limbs
     (3, 33, 32768, 32768, 2, 20, 54),   # the paper's largest ring degree
@@ -88,6 +99,20 @@ def test_small_and_ragged_shapes(oracle, m, k, n, N, L, t_bits, q_bits):
         mask[0, 0, :, l, :4] = q - 1
     _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, f"small m={m} k={k} n={n} N={N} L={L}")
     _check_both(oracle, X, ctW, moduli, n, N, t_bits, None, f"small/no-mask m={m} k={k}")
+
+
+@pytest.mark.parametrize("k", [20, 40, 80])
+@pytest.mark.parametrize("t_bits,q_bits", [(16, 50), (20, 54), (32, 54), (16, 62), (24, 62), (32, 62)])
+def test_one_to_three_k_blocks_per_plane_count(oracle, t_bits, q_bits, k):
+    """every plane count with one, two and three k-blocks: the loop's prologue is all there is,
+    its first wait covers the load of the column sums, and with shares of t-1 the term
+    OFFX * S that needs them is as large as it gets"""
+    m, n, N, L = 8, 32, 32, 1
+    moduli = ci.limb_primes(q_bits, t_bits, L)
+    X, ctW, mask = _inputs(2000 + k + t_bits + q_bits, m, k, n, N, moduli, t_bits)
+    X[0, :] = (1 << t_bits) - 1
+    X[1, :] = 0
+    _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, f"k={k} t={t_bits} q={q_bits}")
 
 
 def test_all_maximal_operands(oracle):
