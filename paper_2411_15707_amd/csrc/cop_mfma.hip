@@ -29,6 +29,7 @@
 // use the same lane/byte -> k mapping, so any fixed assignment of k-slots to
 // actual k indices gives the same sum as long as both sides share it.
 #include "cop_mfma_common.hpp"
+#include <atomic>
 
 namespace nimbus {
 
@@ -233,13 +234,13 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // 0..7
     const int wr = wave >> 1, wc = wave & 1;
 
-    // workgroup -> (64-column tile, row block).  Workgroups are dealt round-robin to
-    // the 8 XCDs; the RB row blocks that share a column tile are kept on one XCD
-    // and adjacent in launch order so that tile is fetched from HBM once.  (The
-    // column tiles past the last multiple of 8, if any, are not worth the trouble.)
-    uint32_t ct2, rb;
-    {
-        const uint32_t id = blockIdx.x;
+    // tile id -> (64-column tile, row block).  A workgroup takes the tiles blockIdx.x,
+    // blockIdx.x + gridDim.x, ... (the host launches one workgroup per compute unit when there
+    // are more tiles than that).  Workgroups are dealt round-robin to the 8 XCDs, and with a
+    // grid that is a multiple of 8 so are the tile ids; the RB row blocks that share a column
+    // tile are kept on one XCD and adjacent in that order so that tile is fetched from HBM
+    // once.  (The column tiles past the last multiple of 8, if any, are not worth the trouble.)
+    auto map_tile = [&](uint32_t id, uint32_t &ct2, uint32_t &rb) {
         const uint32_t RB = (uint32_t)a.RB;
         const uint32_t CT2a = (a.CT >> 1) & ~7u;
         if (!SHARED) {                              // one row block: no division
@@ -254,10 +255,8 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
             rb = t % RB;
             ct2 = CT2a + t / RB;
         }
-    }
+    };
     const int RT = (a.m + kTile - 1) / kTile;       // row tiles that exist in the workspace
-    const int rt = (int)rb * 4 + wr;                // this wave's row tile
-    const bool active = FULL || rt < RT;            // wave-uniform
     const int KB = a.KB;
 
     // ---- this wave's share of the loads of one stage (sources at k-block 0) ----
@@ -266,63 +265,71 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // never used).  Waves 4-7 (the second of each SIMD) load the ciphertext tiles, from HBM:
     // waves 4 and 5 the planes of the first column tile (planes 0-3 and 4 .. DQ-1), waves 6
     // and 7 those of the second.  A load's source is the wave's buffer descriptor (base of
-    // the workgroup's X or ciphertext region), the lane's 16 bytes, and a wave-uniform
-    // offset: the tile's place at k-block 0 plus the carried k-block offset.  (A row tile or
-    // column tile of planes spans KB * D KiB < 2^23 bytes.  Everything up to the first loads
-    // is scalar work on the critical path of the launch: no divisions, and whatever the loads
-    // do not need comes after them.)
+    // the tile's X or ciphertext region), the lane's 16 bytes, and a wave-uniform
+    // offset: the operand tile's place at k-block 0 plus the carried k-block offset.  (A row
+    // tile or column tile of planes spans KB * D KiB < 2^23 bytes.  Everything up to the first
+    // loads is scalar work on the critical path of the launch: no divisions, and whatever the
+    // loads do not need comes after them.)
     const uint32_t a_tile_bytes = (uint32_t)KB * DX * kTileBytes;     // one row tile, all k-blocks
     const uint32_t b_tile_bytes = (uint32_t)KB * DQ * kTileBytes;     // one column tile
-    const unsigned char *const a_base =
-        (const unsigned char *)a.xd + (size_t)rb * 4u * a_tile_bytes;
-    const unsigned char *const b_base =
-        (const unsigned char *)a.planes + (size_t)ct2 * 2u * b_tile_bytes;
     const bool loads_x = wave < 4;
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(loads_x ? a_base : b_base), 0, 0xffffffff, 0x00027000);
     const uint32_t lane16 = (uint32_t)lane * 16u;
     constexpr int PH = (DQ + 1) / 2;                // planes of a column tile on its first wave
     static_assert(P_::MAXU == 4 && DX <= 4 && PH <= 4, "four load slots per wave and stage");
-    uint32_t toff[P_::MAXU];                        // the tile's byte offset at k-block 0
-    uint32_t dst[P_::MAXU];                         // the tile's byte offset in slot 0 of the LDS
+    const uint32_t src_step = (uint32_t)(loads_x ? DX : DQ) * kTileBytes;   // per k-block
+    const uint32_t src_end = (uint32_t)KB * src_step;
+    const uint32_t slot_step = loads_x ? P_::A_BYTES : P_::B_BYTES;
+    const uint32_t slot_end = RING * slot_step;
+    uint32_t dst[P_::MAXU];                         // the operand tile's byte offset in slot 0 of the LDS
     int n_loads;                                    // loads per stage
     {
-        uint32_t first_off, first_tile;             // of the wave's first tile; the others follow it
+        uint32_t first_tile;
+        if (loads_x) {
+            first_tile = (uint32_t)wave * DX;
+            n_loads = DX;
+        } else {
+            const uint32_t c = (uint32_t)(wave >> 1) & 1u, hi = (uint32_t)wave & 1u;
+            first_tile = (uint32_t)P_::A_TILES * RING + c * DQ + hi * PH;
+            n_loads = hi ? DQ - PH : PH;
+        }
+#pragma unroll
+        for (int u = 0; u < P_::MAXU; ++u) dst[u] = (first_tile + (uint32_t)u) * kTileBytes;
+    }
+    // Issue side of a tile: descriptor, the operand tiles' offsets at k-block 0, and the
+    // wave-uniform state for the next stage to issue (byte offset of its k-block in the
+    // source, byte offset of its slot in the ring; carried and wrapped, never recomputed).
+    // Stage s of a tile is k-block (s + k_start) mod KB: the sum over k does not care about
+    // the order, and workgroups that walk their (equally spaced) ciphertext regions in
+    // lockstep would otherwise ask the same memory channels for data at the same moment.
+    // The start depends on the column tile alone: row blocks that share a column tile walk
+    // it together.
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t toff[P_::MAXU];                        // the operand tile's byte offset at k-block 0
+    uint32_t src_off, slot_off;
+    auto begin_tile = [&](uint32_t ct2, uint32_t rb) {
+        const unsigned char *const a_base =
+            (const unsigned char *)a.xd + (size_t)rb * 4u * a_tile_bytes;
+        const unsigned char *const b_base =
+            (const unsigned char *)a.planes + (size_t)ct2 * 2u * b_tile_bytes;
+        rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(loads_x ? a_base : b_base), 0, 0xffffffff,
+                                                 0x00027000);
+        uint32_t first_off;
         if (loads_x) {
             int r = wave;
             const int last = RT - 1 - (int)rb * 4;  // last row tile of the block that exists (>= 0)
             if (r > last) r = last;
             first_off = (uint32_t)r * a_tile_bytes;
-            first_tile = (uint32_t)wave * DX;
-            n_loads = DX;
         } else {
             const uint32_t c = (uint32_t)(wave >> 1) & 1u, hi = (uint32_t)wave & 1u;
             first_off = c * b_tile_bytes + hi * (PH * kTileBytes);
-            first_tile = (uint32_t)P_::A_TILES * RING + c * DQ + hi * PH;
-            n_loads = hi ? DQ - PH : PH;
         }
 #pragma unroll
-        for (int u = 0; u < P_::MAXU; ++u) {
-            toff[u] = first_off + (uint32_t)u * kTileBytes;
-            dst[u] = (first_tile + (uint32_t)u) * kTileBytes;
-        }
-    }
-    // Stage s of this workgroup is k-block (s + k_start) mod KB: the sum over k does not
-    // care about the order, and workgroups that walk their (equally spaced) ciphertext
-    // regions in lockstep would otherwise ask the same memory channels for data at the
-    // same moment.  The start depends on the column tile alone: row blocks that share a
-    // column tile walk it together.
-    uint32_t k_start = ct2 - __umulhi(ct2, a.kb_magic) * (uint32_t)KB;   // ct2 mod KB
-    if (k_start >= (uint32_t)KB) k_start -= (uint32_t)KB;
-    // Wave-uniform state of the issue side, for the next stage to issue: byte offset of
-    // its k-block in the source, byte offset of its slot in the ring.  Carried and
-    // wrapped, never recomputed.
-    const uint32_t src_step = (uint32_t)(loads_x ? DX : DQ) * kTileBytes;   // per k-block
-    const uint32_t src_end = (uint32_t)KB * src_step;
-    const uint32_t slot_step = loads_x ? P_::A_BYTES : P_::B_BYTES;
-    const uint32_t slot_end = RING * slot_step;
-    uint32_t src_off = k_start * src_step;
-    uint32_t slot_off = 0;
+        for (int u = 0; u < P_::MAXU; ++u) toff[u] = first_off + (uint32_t)u * kTileBytes;
+        uint32_t k_start = ct2 - __umulhi(ct2, a.kb_magic) * (uint32_t)KB;   // ct2 mod KB
+        if (k_start >= (uint32_t)KB) k_start -= (uint32_t)KB;
+        src_off = k_start * src_step;
+        slot_off = 0;
+    };
     auto bump = [](uint32_t v, uint32_t step, uint32_t end) -> uint32_t {
         v += step;
         return v == end ? 0u : v;
@@ -339,30 +346,52 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         slot_off = bump(slot_off, slot_step, slot_end);                       \
     } while (0)
 
-    // ---- up front: stages 0 .. LEAD-1 ----
-    // The accumulators are cleared between the stages: the memory pipeline takes the first
-    // loads of a launch slowly (nothing is translated or cached yet), and the moves fill
-    // the time the wave would spend waiting for it to accept the next one.
+    uint32_t tile = blockIdx.x, ct2, rb;
+    map_tile(tile, ct2, rb);
+    begin_tile(ct2, rb);
+    n_loads = __builtin_amdgcn_readfirstlane(n_loads);
+
+    // One pass of this loop per tile.  The first stages of a tile other than the first are
+    // in flight when its pass begins: they were issued in front of the epilogue of the tile
+    // before it.
+    for (bool first = true;; first = false) {
     v16i acc[ND];
+    if (first) {
+        // ---- up front: stages 0 .. LEAD-1 of the first tile ----
+        // The accumulators are cleared between the stages: the memory pipeline takes the first
+        // loads of a launch slowly (nothing is translated or cached yet), and the moves fill
+        // the time the wave would spend waiting for it to accept the next one.
 #pragma unroll
-    for (int st = 0; st < LEAD; ++st) {
-        if (st < KB) {
-            static_for<0, P_::MAXU>([&](auto u_c) {
-                if (decltype(u_c)::value < n_loads) issue_one(u_c);
-            });
-            NIMBUS_NEXT_ISSUE();
+        for (int st = 0; st < LEAD; ++st) {
+            if (st < KB) {
+                static_for<0, P_::MAXU>([&](auto u_c) {
+                    if (decltype(u_c)::value < n_loads) issue_one(u_c);
+                });
+                NIMBUS_NEXT_ISSUE();
+            }
+#pragma unroll
+            for (int d = st; d < ND; d += LEAD) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[d][r] = 0;
+                tie_acc(acc[d]);
+            }
         }
+    } else {
 #pragma unroll
-        for (int d = st; d < ND; d += LEAD) {
+        for (int d = 0; d < ND; ++d) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[d][r] = 0;
             tie_acc(acc[d]);
         }
     }
-
-    // ---- what the first loads did not need ----
     __builtin_amdgcn_sched_barrier(0);
-    n_loads = __builtin_amdgcn_readfirstlane(n_loads);
+    // ---- what the first loads did not need ----
+    const int rt = (int)rb * 4 + wr;                // this wave's row tile
+    const bool active = FULL || rt < RT;            // wave-uniform
+    // Loads and stores complete in the order they were issued, so the counted waits of the
+    // loop would still be right with the epilogue's stores among the younger ones; waiting
+    // for everything once (the loads have had the whole epilogue to land) keeps them simple.
+    if (!first) wait_vmem<0>();
     // The column's ciphertext sum is needed after the loop; asked for now it costs two
     // registers, not a round trip to memory at the end.  An ordinary load: the compiler places
     // the wait for it at its first use, and the statements below that clobber memory keep the
@@ -582,9 +611,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
             iteration(s, C0{}, std::false_type{});
             NIMBUS_NEXT_ISSUE();
         }
-        return;
-    }
-    if constexpr (PIPELINED) {
+    } else if constexpr (PIPELINED) {
         int s = 0;
         if constexpr (MASKLDS) {
             static_assert(kMaskPhase % 2 == 0, "whole pairs of iterations");
@@ -622,23 +649,72 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
             NIMBUS_NEXT_READ();
         }
     }
-#undef NIMBUS_NEXT_ISSUE
 #undef NIMBUS_NEXT_READ
     // the last pipelined iteration has read a stage that does not exist into the other
     // operand set; nothing may reuse those registers before the reads are back
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
+    // ---- the next tile's first stages, issued in front of this tile's epilogue ----
+    // Every wave has the last stage in registers once all have passed the last barrier
+    // (pipelined variants: the reads are waited for in front of it; the others read behind
+    // it, so they meet once more here): the rings are free, and the loads have the whole
+    // epilogue, which uses neither the rings nor the memory pipeline much, to land.
+    const uint32_t next = tile + gridDim.x;
+    const bool more = next < a.tiles;
+    uint32_t next_ct2 = 0, next_rb = 0;
+    if (more) {
+        if constexpr (!PIPELINED) __builtin_amdgcn_s_barrier();
+        map_tile(next, next_ct2, next_rb);
+        begin_tile(next_ct2, next_rb);
+#pragma unroll
+        for (int st = 0; st < LEAD; ++st) {
+            if (st < KB) {
+                static_for<0, P_::MAXU>([&](auto u_c) {
+                    if (decltype(u_c)::value < n_loads) issue_one(u_c);
+                });
+                NIMBUS_NEXT_ISSUE();
+            }
+        }
+    }
+    asm volatile("" ::: "memory");
+
     // ---- epilogue: rebuild, add the constant and the mask, reduce, store ----
-    cop_epilogue<ND, FULL, MASKLDS>(
-        acc, a, limb, colsum_S, rt * kTile + 4 * (lane >> 5),
-        (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31),
-        lds + (MASKLDS ? P_::LDS_BYTES : 0) + (uint32_t)(wr * kTile + 4 * (lane >> 5)) * 512u +
-            (uint32_t)(wc * kTile + (lane & 31)) * 8u);
+    // (the lane number goes through an opaque copy: what the epilogue derives from it would
+    // otherwise be computed once in front of all tiles and held in registers through the loop)
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    if (active)
+        cop_epilogue<ND, FULL, MASKLDS>(
+            acc, a, limb, colsum_S, rt * kTile + 4 * (lane_e >> 5),
+            (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane_e & 31),
+            lds + (MASKLDS ? P_::LDS_BYTES : 0) + (uint32_t)(wr * kTile + 4 * (lane_e >> 5)) * 512u +
+                (uint32_t)(wc * kTile + (lane_e & 31)) * 8u);
+    if (!more) break;
+    tile = next;
+    ct2 = next_ct2;
+    rb = next_rb;
+    }   // tiles
+#undef NIMBUS_NEXT_ISSUE
 }
 
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
+// compute units of the current device (asked once per device)
+static int compute_units()
+{
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
 bool mfma_supported(const Problem &p)
 {
     const int DX = planes_x(p.x_bits), DQ = planes_q(p.q_bits_max);
@@ -715,7 +791,12 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
     a.xd = (const uint4 *)staged;
     a.planes = (const uint4 *)prepared;
     a.colsum = (const uint64_t *)((const char *)prepared + (size_t)CT * KB * DQ * kTileBytes);
-    const dim3 grid((CT / 2) * (uint32_t)a.RB);
+    // One workgroup per compute unit at most (a compute unit holds one at a time anyway);
+    // each walks the tiles id, id + grid, ...  A grid that is a multiple of 8 keeps a tile id's
+    // XCD the same on every pass.
+    uint32_t cus = (uint32_t)compute_units();
+    if (cus >= 8) cus &= ~7u;
+    const dim3 grid(a.tiles < cus ? a.tiles : cus);
     using P_ = Pipe<DX, DQ>;
     constexpr bool kCanMaskLds = P_::PIPELINED && P_::LDS_BYTES + kMaskTileBytes <= 160 * 1024;
     // mask tile in LDS: see the kernel; 128 rows of the mask must span less than 4 GB

@@ -30,6 +30,7 @@ struct MfmaArgs {
     uint64_t *out;            // [m][C]
     int m, KB, RB, N, L;
     uint32_t C, CT;
+    uint32_t tiles;           // 128 x 64 output tiles: (CT / 2) * RB
     uint32_t kb_magic;        // floor(2^32 / KB): x / KB = umulhi(x, kb_magic) or one more
     uint32_t log_n;           // N = 2^log_n
     uint32_t l_magic;         // ceil(2^32 / L) for L >= 2: x / L = umulhi(x, l_magic) for x < 2^31
@@ -81,6 +82,7 @@ static inline void fill_common_args(const Problem &p, int DX, const uint64_t *ma
     a->L = p.L;
     a->C = (uint32_t)p.C;
     a->CT = (uint32_t)(p.C / kTile);
+    a->tiles = (a->CT / 2u) * (uint32_t)a->RB;
     a->offx = share_offset(p.x_bits, DX);
     a->kb_magic = (uint32_t)((1ull << 32) / (uint64_t)KB);   // KB = 1: 2^32 does not fit, see below
     if (KB == 1) a->kb_magic = 0xffffffffu;
@@ -347,7 +349,12 @@ __device__ __forceinline__ void cop_epilogue(v16i (&acc)[ND], const MfmaArgs &a,
 #pragma unroll
     for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(mk[r]));
     // wave-uniform constants of the quotient estimate, kept in vector registers
-    double qinv_v = qinv, magic_c = 1688849860263936.0 - 0.5;      // 3 * 2^49 - 1/2
+    // (the constant starts out in scalar registers behind an opaque statement: a caller that
+    // runs this epilogue in a loop would otherwise have it built once in front of the loop
+    // and carried, or spilled, through all of it)
+    uint64_t magic_bits = 0x4317fffffffffffeull;                   // 3 * 2^49 - 1/2 as a double
+    asm volatile("" : "+s"(magic_bits));
+    double qinv_v = qinv, magic_c = __builtin_bit_cast(double, magic_bits);
     // (the subtract-with-borrow reads vcc, which leaves no room for a second scalar operand)
     uint32_t q_hi_v = q_hi;
     asm volatile("" : "+v"(qinv_v), "+v"(magic_c), "+v"(q_hi_v));

@@ -79,6 +79,12 @@ SMALL = [
     (256, 100, 256, 256, 1, 20, 54),
     (384, 70, 128, 128, 3, 20, 54),
     (200, 500, 256, 256, 1, 16, 50),    # ragged m with two row blocks, 16 k-blocks
+    # more output tiles than compute units: a workgroup walks several tiles, the first stages of
+    # the next one in flight under the epilogue of the one before
+    (128, 512, 8192, 8192, 3, 20, 54),  # 768 tiles, mask tile through LDS
+    (70, 100, 8192, 8192, 3, 20, 54),   # 768 tiles, a wave without rows in every tile
+    (200, 70, 4096, 4096, 2, 20, 54),   # 512 tiles in two row blocks, the second ragged
+    (128, 96, 16384, 16384, 1, 32, 62), # 512 tiles, 4 x 8 planes (operands read after the barrier)
     # the ends of the accepted ranges
     (6, 50, 64, 64, 4, 20, 54),         # four limbs
     (3, 33, 32768, 32768, 2, 20, 54),   # the paper's largest ring degree
