@@ -18,12 +18,14 @@ def _say(msg):
 
 
 # m, k, n, N, L, t_bits, q_bits
-@pytest.mark.parametrize("m,k,n,N,L,t_bits,q_bits", [
-    (33, 100, 40, 128, 2, 20, 54),        # ragged rows and k, three rows per packed ciphertext
-    (8, 64, 64, 1024, 1, 16, 50),         # config 1
-    (128, 256, 3072, 4096, 2, 20, 54),    # BERT-base FFN width, shortened inner dimension
+@pytest.mark.parametrize("m,k,n,N,L,t_bits,q_bits,static", [
+    (33, 100, 40, 128, 2, 20, 54, False),     # ragged rows and k, three rows per packed ciphertext
+    (8, 64, 64, 1024, 1, 16, 50, False),      # config 1
+    (128, 256, 3072, 4096, 2, 20, 54, False), # BERT-base FFN width, shortened inner dimension
+    # the entry point for callers that cannot allocate: share planes in the library's own buffer
+    (40, 96, 64, 128, 2, 20, 54, True),
 ])
-def test_layer_recorded_in_a_graph_replays_exactly(oracle, m, k, n, N, L, t_bits, q_bits):
+def test_layer_recorded_in_a_graph_replays_exactly(oracle, m, k, n, N, L, t_bits, q_bits, static):
     import torch
     import gpu_util as gu
     import paper_2411_15707_amd as nc
@@ -48,7 +50,10 @@ def test_layer_recorded_in_a_graph_replays_exactly(oracle, m, k, n, N, L, t_bits
     with_decrypt = L <= 2
 
     def layer():
-        nc.nimbus_cop_matmul_prepared(dX, m, k, t_bits, prepared, n, N, L, moduli, dmask, out, ws)
+        if static:
+            nc.nimbus_cop_matmul_prepared_static(dX, m, k, t_bits, prepared, n, N, L, moduli, dmask, out)
+        else:
+            nc.nimbus_cop_matmul_prepared(dX, m, k, t_bits, prepared, n, N, L, moduli, dmask, out, ws)
         nc.nimbus_cop_pack(out, m, n, N, L, moduli, dpmask, packed)
         if with_decrypt:
             nc.nimbus_rlwe_decrypt(packed, T, N, L, moduli, t_bits, tables, phi, m_hat)
