@@ -5,9 +5,11 @@
 //
 //   ciphertext words  ctW[k][C]: a 32 x 64 tile per k-block (16 KB) comes into a ring of raw
 //       tiles in LDS by direct-to-LDS loads, three k-blocks ahead; one k-block ahead of its use
-//       every thread takes four words of one column (four consecutive k), centres them
-//       (c' = c or c - q), recodes them into signed bytes and writes one 32-bit word (four
-//       k-slots) into each of the DQ operand tiles of that column tile;
+//       every thread takes four words of one column (four consecutive k), recodes them into
+//       signed bytes (digits of the residue c itself: unlike the setup pass of the other
+//       kernel it does not centre first, which would cost five vector instructions a word)
+//       and writes one 32-bit word (four k-slots) into each of the DQ operand tiles of that
+//       column tile;
 //   shares  X[m][k]: a 128 x 32 tile per k-block comes from L2 into registers, one k-block
 //       ahead; every thread turns 2 x 4 consecutive k of one row into one word per plane.
 //
@@ -66,7 +68,11 @@ __device__ __forceinline__ void transpose4(uint32_t a, uint32_t b, uint32_t c, u
 // FULL: m is a multiple of 128.  SHARED: several row blocks per column tile (m > 128); they
 // start at the same k-block and load the ciphertext without the streaming hint, so that the
 // tile is found in the L2 of their XCD by all but the first.
-template <int DX, int DQ, bool FULL, bool SHARED>
+// CENTRE: the ciphertext digits are those of the centred residue (c or c - q) instead of the
+// residue itself.  Needed when a residue can exceed what DQ signed digits express,
+// 127 (256^DQ - 1) / 255 (moduli within half a percent of 2^(8 DQ - 1)); costs five vector
+// instructions a word.
+template <int DX, int DQ, bool FULL, bool SHARED, bool CENTRE>
 __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
 {
     const MfmaArgs &a = ca.e;
@@ -142,8 +148,8 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
     const uint32_t cv_out = lds0 + (uint32_t)A_BYTES + (cv_c >> 5) * (DQ * kTileBytes) +
                             ((cv_c & 31u) + 32u * (cv_g >> 2)) * 16u + (cv_g & 3u) * 4u;
     // modulus of the item's column (16 aligned columns lie in one limb: N >= 32)
-    uint64_t cv_q;
-    {
+    uint64_t cv_q = 0;
+    if constexpr (CENTRE) {
         const uint32_t blk = ((ct2 * 2u + (((uint32_t)wave & 3u) >> 1)) * kTile) >> a.log_n;
         uint32_t l = a.L == 1 ? 0u : blk - (uint32_t)a.L * __umulhi(blk, a.l_magic);
         l = __builtin_amdgcn_readfirstlane(l);
@@ -153,8 +159,9 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
     uint64_t bias = 0;                              // 0x80 in each of the DQ low bytes
 #pragma unroll
     for (int d = 0; d < DQ; ++d) bias |= (uint64_t)0x80 << (8 * d);
-    uint64_t sum_lo = 0;                            // sum of the words this thread converts
-    uint32_t sum_hi = 0;
+    // sums of the lower and of the upper halves of the words this thread converts (one
+    // 32 x 32 + 64-bit multiply-add by one each: k / 8 words of 32 bits cannot overflow 64)
+    uint64_t sum_lo = 0, sum_hi = 0;
 
     // ---- share side: two items per thread, item i: 16 rows x 4 k-quads per wave ----
     // item t = 2 wave + i: rows 16 (t % 8) + lane / 4, k-quad 4 (t / 8) + lane % 4 (k = 4 kq .. +3)
@@ -219,11 +226,13 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
         for (int j = 0; j < 4; ++j) {
             tie64(cw[j]);
             const uint64_t c = cw[j];
-            const uint64_t s = sum_lo + c;
-            sum_hi += s < sum_lo ? 1u : 0u;
-            sum_lo = s;
-            const uint64_t cc = c > cv_half ? c - cv_q : c;        // two's complement of c'
-            cw[j] = (cc + bias) ^ bias;                             // bytes: the signed digits
+            asm("v_mad_u64_u32 %0, vcc, %1, 1, %0" : "+v"(sum_lo) : "v"((uint32_t)c) : "vcc");
+            asm("v_mad_u64_u32 %0, vcc, %1, 1, %0" : "+v"(sum_hi) : "v"((uint32_t)(c >> 32)) : "vcc");
+            // signed base-256 digits of the residue, centred first where it has to be:
+            // c' + 0x80..80 has the bytes digit + 128, and flipping bit 7 of each gives the
+            // digits as signed bytes
+            const uint64_t cc = CENTRE && c > cv_half ? c - cv_q : c;  // two's complement of c'
+            cw[j] = (cc + bias) ^ bias;
         }
     };
     auto ct_write = [&](uint32_t ob) {
@@ -344,7 +353,7 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
     __builtin_amdgcn_s_barrier();
     {
         const uint32_t at = lds0 + (uint32_t)RAW0 + (cv_c * 8u + cv_g) * 16u;
-        asm volatile("ds_write_b64 %0, %1\n\tds_write_b32 %0, %2 offset:8"
+        asm volatile("ds_write_b64 %0, %1\n\tds_write_b64 %0, %2 offset:8"
                      ::"v"(at), "v"(sum_lo), "v"(sum_hi) : "memory");
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -359,16 +368,18 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
     uint64_t colsum_S;
     {
         const uint32_t at = lds0 + (uint32_t)RAW0 + ((uint32_t)(wc * kTile + (lane & 31)) * 8u) * 16u;
-        uint64_t lo = 0, hi = 0;
+        uint64_t lows = 0, highs = 0;               // each below 2^32 k
         static_for<0, 8>([&](auto g_c) {
             constexpr int g = decltype(g_c)::value;
-            uint64_t plo;
-            uint32_t phi;
-            asm volatile("ds_read_b64 %0, %2 offset:%3\n\tds_read_b32 %1, %2 offset:%4\n\t"
+            uint64_t plo, phi;
+            asm volatile("ds_read_b64 %0, %2 offset:%3\n\tds_read_b64 %1, %2 offset:%4\n\t"
                          "s_waitcnt lgkmcnt(0)"
                          : "=&v"(plo), "=&v"(phi) : "v"(at), "n"(g * 16), "n"(g * 16 + 8) : "memory");
-            add128(hi, lo, (uint64_t)phi, plo);
+            lows += plo;
+            highs += phi;
         });
+        uint64_t lo = lows, hi = 0;                 // lows + 2^32 highs in 128 bits
+        add128(hi, lo, highs >> 32, highs << 32);
         colsum_S = barrett128(hi, lo, ca.limbs.limb[limb]);      // k * q < 2^(b+63)
     }
     cop_epilogue<ND, FULL, false>(acc, a, limb, colsum_S, rt * kTile + 4 * (lane >> 5),
@@ -378,9 +389,24 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
+// DQ signed digits express the values up to 127 (256^DQ - 1) / 255: is there a limb whose
+// residues can be larger?
+static bool needs_centring(const Problem &p, int DQ)
+{
+    uint64_t top = 0;
+    for (int d = 0; d < DQ; ++d) top = top * 256u + 127u;
+    for (int l = 0; l < p.L; ++l)
+        if (p.limbs.limb[l].q - 1 > top) return true;
+    return false;
+}
+
 bool canon_supported(const Problem &p)
 {
     if (p.x_bits > 32 || !mfma_supported(p)) return false;
+    // where the digits stand for the residues themselves, not the centred ones, the sums are
+    // twice as large and the multiple of q that makes them non-negative is one bit longer; the
+    // value reduced in the epilogue must stay below 2^47 q all the same
+    if (!needs_centring(p, planes_q(p.q_bits_max)) && bias_shift(p) + 3 > 47) return false;
     // four share planes times eight ciphertext planes: eleven accumulator tiles and the
     // conversion's registers do not fit one wave
     if (planes_x(p.x_bits) == 4 && planes_q(p.q_bits_max) == 8) return false;
@@ -396,18 +422,27 @@ static hipError_t canon_impl(const Problem &p, const uint64_t *X, const uint64_t
                              const uint64_t *mask, uint64_t *out, hipStream_t stream)
 {
     CanonArgs ca{};
-    fill_common_args(p, DX, mask, nullptr, out, &ca.e);
+    const bool centre = needs_centring(p, DQ);
+    fill_common_args(p, DX, mask, nullptr, out, &ca.e, centre ? 0 : 1);
     ca.X = X;
     ca.ctW = ctW;
     ca.k = p.k;
     ca.limbs = p.limbs;
     const dim3 grid((ca.e.CT / 2) * (uint32_t)ca.e.RB);
     const bool full = p.m % 128 == 0, shared = ca.e.RB > 1;
-    if (full && shared)
-        return launch(cop_canon_kernel<DX, DQ, true, true>, grid, dim3(512), stream, ca);
-    if (full) return launch(cop_canon_kernel<DX, DQ, true, false>, grid, dim3(512), stream, ca);
-    if (shared) return launch(cop_canon_kernel<DX, DQ, false, true>, grid, dim3(512), stream, ca);
-    return launch(cop_canon_kernel<DX, DQ, false, false>, grid, dim3(512), stream, ca);
+    auto go = [&](auto full_c, auto shared_c, auto centre_c) {
+        return launch(cop_canon_kernel<DX, DQ, decltype(full_c)::value, decltype(shared_c)::value,
+                                       decltype(centre_c)::value>,
+                      grid, dim3(512), stream, ca);
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    if (centre) {
+        if (full) return shared ? go(T{}, T{}, T{}) : go(T{}, F{}, T{});
+        return shared ? go(F{}, T{}, T{}) : go(F{}, F{}, T{});
+    }
+    if (full) return shared ? go(T{}, T{}, F{}) : go(T{}, F{}, F{});
+    return shared ? go(F{}, T{}, F{}) : go(F{}, F{}, F{});
 }
 
 hipError_t launch_cop_canon(const Problem &p, const uint64_t *X, const uint64_t *ctW,

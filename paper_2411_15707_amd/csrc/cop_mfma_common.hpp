@@ -68,8 +68,11 @@ static inline int bias_shift(const Problem &p)
 
 // everything of the argument block that follows from the problem alone: sizes, the constants
 // of the tile mapping, OFFX, and per limb the modulus, its reciprocal and q << sh
+// (extra_shift: one more bit of q * 2^sh for a kernel whose ciphertext digits stand for the
+// residue c itself, |c'| < q, instead of the centred one, |c'| <= q / 2)
 static inline void fill_common_args(const Problem &p, int DX, const uint64_t *mask,
-                                    const uint64_t *prev, uint64_t *out, MfmaArgs *a)
+                                    const uint64_t *prev, uint64_t *out, MfmaArgs *a,
+                                    int extra_shift = 0)
 {
     const int KB = kblocks(p.k);
     a->mask = mask;
@@ -89,7 +92,7 @@ static inline void fill_common_args(const Problem &p, int DX, const uint64_t *ma
     a->log_n = 0;
     while ((1 << a->log_n) < p.N) ++a->log_n;
     a->l_magic = p.L >= 2 ? (uint32_t)(((1ull << 32) + (uint64_t)p.L - 1) / (uint64_t)p.L) : 0u;
-    const int sh = bias_shift(p);
+    const int sh = bias_shift(p) + extra_shift;
     for (int l = 0; l < p.L; ++l) {
         const uint64_t q = p.limbs.limb[l].q;
         const unsigned __int128 c = (unsigned __int128)q << sh;

@@ -139,6 +139,39 @@ def test_all_maximal_operands(oracle):
     _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, "zero shares")
 
 
+@pytest.mark.parametrize("q_bits,t_bits", [(54, 24), (62, 16), (50, 20)])
+def test_all_maximal_operands_uncentred_digits(oracle, q_bits, t_bits):
+    """the same extremes for moduli whose residues the canonical-layout kernel splits into
+    digits without centring them first: sums twice as large as with centred digits"""
+    m, k, n, N, L = 32, 512, 64, 64, 2
+    moduli = ci.limb_primes(q_bits, t_bits, L)
+    qv = np.array(moduli, dtype=np.uint64).reshape(1, 1, 1, L, 1)
+    X = np.full((m, k), (1 << t_bits) - 1, dtype=np.uint64)
+    ctW = np.broadcast_to(qv - np.uint64(1), (k, 1, 2, L, N)).copy()
+    mask = np.broadcast_to(qv - np.uint64(1), (m, 1, 2, L, N)).copy()
+    _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, f"maximal {q_bits}")
+    X[::2] = 0
+    ctW[1::2] = 0
+    _check_both(oracle, X, ctW, moduli, n, N, t_bits, None, f"maximal and zero {q_bits}")
+
+
+@pytest.mark.parametrize("q", [0x7F7F7F7F7F7F7F, 0x7F7F7F7F7F7F81, 0x7F7F7F7F7F7F7D])
+def test_moduli_at_the_edge_of_seven_signed_digits(oracle, q):
+    """Seven signed base-256 digits express the values up to 0x7F7F7F7F7F7F7F.  A modulus whose
+    residues stay below that is split into digits as it is, one above is centred first; the
+    residues next to the edge are the ones whose top digit is 127 after the carries.  (The
+    client side only needs odd moduli above 2^x_bits.)"""
+    m, k, n, N, L, t_bits = 16, 96, 32, 32, 1, 20
+    moduli = (q,)
+    X, ctW, mask = _inputs(4242, m, k, n, N, moduli, t_bits)
+    edge = np.array([q - 1, q - 2, 0x7F7F7F7F7F7F7E, 0x7F7F7F7F7F7F00, 0x7F7F7F7F7F0080, 0x7F80, 0x80, 0x7F, 0],
+                    dtype=np.uint64) % np.uint64(q)
+    ctW.reshape(k, -1)[:, :edge.size] = edge
+    ctW.reshape(k, -1)[::3, edge.size:2 * edge.size] = edge[::-1]
+    X[0, :] = (1 << t_bits) - 1
+    _check_both(oracle, X, ctW, moduli, n, N, t_bits, mask, f"edge modulus {q:#x}")
+
+
 def test_special_cases_on_gpu(oracle):
     import gpu_util as gu
     m = k = 48
