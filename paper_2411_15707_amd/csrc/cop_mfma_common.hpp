@@ -295,6 +295,8 @@ __device__ __forceinline__ void cop_epilogue(v16i (&acc)[ND], const MfmaArgs &a,
     // (wave-uniform: the limb follows from the wave's column tile)
     const uint32_t q_lo = __builtin_amdgcn_readfirstlane((uint32_t)q);
     const uint32_t q_hi = __builtin_amdgcn_readfirstlane((uint32_t)(q >> 32));
+    const uint32_t nq_lo = __builtin_amdgcn_readfirstlane((uint32_t)(0 - q));           // 2^64 - q
+    const uint32_t nq_hi = __builtin_amdgcn_readfirstlane((uint32_t)((0 - q) >> 32));
     // First everything that does not need the mask words (their loads are in flight), then,
     // per element, mask, quotient, remainder, store.
     // (the powers of 256 are kept opaque so that each term is one multiply-add instead of a
@@ -381,10 +383,12 @@ __device__ __forceinline__ void cop_epilogue(v16i (&acc)[ND], const MfmaArgs &a,
         const uint32_t m_hi = (uint32_t)(mbits >> 32);
         const uint32_t ql = (uint32_t)(mbits >> 2);
         const uint32_t qh = (uint32_t)__builtin_amdgcn_sbfe((int32_t)m_hi, 2, 17);
-        // remainder modulo 2^64: lo - (qh 2^32 + ql) q, in [0, 2q); then one correction
-        const uint64_t t = (((uint64_t)lo_hi << 32) | lo_lo) - (uint64_t)ql * q_lo;
+        // remainder modulo 2^64: lo - (qh 2^32 + ql) q = lo + (qh 2^32 + ql) (2^64 - q), in
+        // [0, 2q); then one correction.  (With the negated modulus the lower product goes into
+        // one multiply-add on top of lo, and nothing has to be subtracted with borrow.)
+        const uint64_t t = (uint64_t)ql * nq_lo + (((uint64_t)lo_hi << 32) | lo_lo);
         const uint32_t t_lo = (uint32_t)t;
-        const uint32_t t_hi = (uint32_t)(t >> 32) - (ql * q_hi + qh * q_lo);   // upper word only
+        const uint32_t t_hi = (uint32_t)(t >> 32) + (ql * nq_hi + qh * nq_lo);   // upper word only
         // res = t - q if that does not borrow, else t (subtract with borrow, then select on
         // the borrow; a value written to vcc may be read two wait states later)
         uint32_t r_lo, r_hi;
