@@ -279,33 +279,41 @@ def main():
     # ---- the canonical-layout entry points on the same workload (no setup pass, 8 B residues):
     # nimbus_cop_matmul (matrix-core kernel that splits the words into byte planes itself) and
     # nimbus_cop_matmul_valu (vector-ALU kernel, any parameters) ----
-    dW0 = dev(first[1])
+    # (weights rotated over enough canonical buffers of uniform residues to defeat the 256 MB
+    # last-level cache, as for the prepared path; the output check of buffer 0 is further down)
+    canon_bytes = k * C * 8
+    Rc = max(2, -(-(1 << 30) // canon_bytes))
+    dWs = [dev(first[1])] + [torch.randint(0, min(moduli), (k, C), dtype=torch.int64, device="cuda")
+                             for _ in range(Rc - 1)]
 
     def timed_entry(fn, reps):
-        for _ in range(2):
-            fn(Xs[0], m, k, xb, dW0, n, N, L, moduli, masks[0], outs[0])
+        for s_ in range(min(reps, 20)):
+            fn(Xs[0], m, k, xb, dWs[s_ % Rc], n, N, L, moduli, masks[0], outs[0])
         ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         ea.record(stream)
-        for _ in range(reps):
-            fn(Xs[0], m, k, xb, dW0, n, N, L, moduli, masks[0], outs[0])
+        for s_ in range(reps):
+            fn(Xs[0], m, k, xb, dWs[s_ % Rc], n, N, L, moduli, masks[0], outs[0])
         eb.record(stream)
         torch.cuda.synchronize()
         return ea.elapsed_time(eb) / reps
-    canon_ms = timed_entry(nc.nimbus_cop_matmul, 50)
-    valu_ms = timed_entry(nc.nimbus_cop_matmul_valu, 5)
+    canon_ms = timed_entry(nc.nimbus_cop_matmul, max(100, min(args.steps, 1000)))
+    valu_ms = timed_entry(nc.nimbus_cop_matmul_valu, 10)
+    # digits of the centred residue only where seven or eight signed digits cannot express q - 1
+    centre = any(q - 1 > int("7f" * DQ, 16) for q in moduli)
     canonical = {
         "entry_point": "nimbus_cop_matmul",
-        "kernel": f"cop_canon_kernel<{DX},{DQ},{'true' if m % 128 == 0 else 'false'},{'true' if m > 128 else 'false'}>",
+        "kernel": "cop_canon_kernel<%d,%d,%s>" % (DX, DQ, ",".join(
+            "true" if f else "false" for f in (m % 128 == 0, m > 128, centre))),
         "kernel_ms_avg": round(canon_ms, 5),
         "value": round(cfg.mod_macs / (canon_ms * 1e-3), 1),
         "algorithmic_bytes_per_launch": alg_bytes,
         "hbm_gbps_achieved": round(alg_bytes / (canon_ms * 1e-3) / 1e9, 1),
         "hbm_frac_of_peak": round(alg_bytes / (canon_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-        "note": "weights from one resident buffer (100 MB, inside the 256 MB last-level cache)",
+        "weight_buffers_rotated": Rc,
         "vector_alu_kernel_ms": round(valu_ms, 4),
     }
-    del dW0
+    del dWs
 
     # ---- output packing by right shifts (Algorithm 1 step 3) on this config's output ----
     # rows: the unmasked outputs of the step above; P = floor(N/n) rows per packed ciphertext
