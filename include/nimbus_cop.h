@@ -187,6 +187,29 @@ int nimbus_cop_matmul_prepared_static(const uint64_t *X, int m, int k, int x_bit
                                       void *stream);
 
 /*
+ * Several calls of nimbus_cop_matmul_staged in ONE launch (Algorithm 1 steps 2 and 4 for
+ * `count` independent share matrices and weight matrices of the same shape: the layers of a
+ * stack whose shares are all known, the requests of a batch).  Problem i uses
+ * staged_shares[i], prepared[i], masks[i] (masks = NULL, or every masks[i] = NULL: no mask;
+ * otherwise a mask for every problem) and writes outs[i]; the four arrays are HOST arrays of
+ * device pointers, read during the call.  Results are those of `count` separate calls, bit
+ * for bit.  The kernel walks the output tiles of all problems with one workgroup per compute
+ * unit and loads the first stages of a tile under the epilogue of the one before, so the
+ * launch gaps and the cold start of every call but the first go away.
+ * count is at most NIMBUS_COP_MAX_BATCH; shares of more than 32 bits (two passes per problem)
+ * are answered NIMBUS_COP_ERR_UNSUPPORTED.  No output may overlap any buffer of the batch.
+ */
+#define NIMBUS_COP_MAX_BATCH 16
+/* nimbus_cop_stage_shares for `count` share matrices of the same shape in one launch: X and
+ * workspaces are HOST arrays of device pointers; every workspace holds workspace_bytes. */
+int nimbus_cop_stage_shares_batch(int count, const uint64_t *const *X, int m, int k, int x_bits,
+                                  void *const *workspaces, size_t workspace_bytes, void *stream);
+int nimbus_cop_matmul_staged_batch(int count, const void *const *staged_shares, int m, int k,
+                                   int x_bits, const void *const *prepared, int n, int N, int L,
+                                   const uint64_t *moduli, const uint64_t *const *masks,
+                                   uint64_t *const *outs, void *stream);
+
+/*
  * Output packing (Algorithm 1 step 3; Appendix B.1 "Right Shift"; Section 3.2 "Output
  * Communication"): when n <= N/2 the payload of an output ciphertext fills only its
  * first n slots, so P = floor(N/n) of them are merged into one by negacyclic right

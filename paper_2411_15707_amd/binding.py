@@ -22,6 +22,8 @@ EXPORTED_SYMBOLS = (
     "nimbus_cop_workspace_bytes",
     "nimbus_cop_stage_shares",
     "nimbus_cop_matmul_staged",
+    "nimbus_cop_stage_shares_batch",
+    "nimbus_cop_matmul_staged_batch",
     "nimbus_cop_matmul_prepared",
     "nimbus_cop_matmul_prepared_static",
     "nimbus_cop_packed_count",
@@ -93,6 +95,10 @@ def load_library():
     lib.nimbus_cop_stage_shares.argtypes = [vp, ci, ci, ci, vp, sz, vp]
     lib.nimbus_cop_matmul_staged.restype = ci
     lib.nimbus_cop_matmul_staged.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
+    lib.nimbus_cop_stage_shares_batch.restype = ci
+    lib.nimbus_cop_stage_shares_batch.argtypes = [ci, vp, ci, ci, ci, vp, sz, vp]
+    lib.nimbus_cop_matmul_staged_batch.restype = ci
+    lib.nimbus_cop_matmul_staged_batch.argtypes = [ci, vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.nimbus_cop_matmul_prepared.restype = ci
     lib.nimbus_cop_matmul_prepared.argtypes = [vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
     lib.nimbus_cop_matmul_prepared_static.restype = ci
@@ -249,6 +255,50 @@ def nimbus_cop_matmul_staged(staged, m, k, x_bits, prepared, n, N, L, moduli, ma
         _moduli(moduli), _dev_ptr(mask, "mask", True), _dev_ptr(out, "out"), _stream(stream))
     if rc != 0:
         raise NimbusCopError(rc, "nimbus_cop_matmul_staged")
+
+
+def nimbus_cop_stage_shares_batch(Xs, m, k, x_bits, workspaces, stream=None):
+    """nimbus_cop_stage_shares for several share matrices of one shape in one launch"""
+    lib = load_library()
+    count = len(Xs)
+    if len(workspaces) != count:
+        raise ValueError("one workspace per share matrix")
+    for X in Xs:
+        _words(X, "X", m * k)
+    size = min(w.numel() * w.element_size() for w in workspaces)
+    ptrs = ctypes.c_void_p * count
+    rc = lib.nimbus_cop_stage_shares_batch(count, ptrs(*[_dev_ptr(X, "X") for X in Xs]), m, k, x_bits,
+                                           ptrs(*[_dev_ptr(w, "workspace") for w in workspaces]),
+                                           size, _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_stage_shares_batch")
+
+
+def nimbus_cop_matmul_staged_batch(staged, m, k, x_bits, prepared, n, N, L, moduli, masks, outs,
+                                   stream=None):
+    """`len(outs)` calls of nimbus_cop_matmul_staged in one launch; staged, prepared, masks (or
+    None) and outs are sequences of tensors, one per problem"""
+    lib = load_library()
+    count = len(outs)
+    if len(staged) != count or len(prepared) != count or (masks is not None and len(masks) != count):
+        raise ValueError("one staged buffer, one prepared buffer and one mask (or none) per output")
+    C = _columns(n, N, L)
+    need = nimbus_cop_workspace_bytes(m, k, x_bits)
+    for i in range(count):
+        _words(outs[i], "out", m * C)
+        if masks is not None and masks[i] is not None:
+            _words(masks[i], "mask", m * C)
+        if staged[i].numel() * staged[i].element_size() < need:
+            raise ValueError("staged shares buffer is smaller than nimbus_cop_workspace_bytes")
+    ptrs = ctypes.c_void_p * count
+    a_staged = ptrs(*[_dev_ptr(t, "staged") for t in staged])
+    a_prep = ptrs(*[_dev_ptr(t, "prepared") for t in prepared])
+    a_out = ptrs(*[_dev_ptr(t, "out") for t in outs])
+    a_mask = None if masks is None else ptrs(*[_dev_ptr(t, "mask", True) for t in masks])
+    rc = lib.nimbus_cop_matmul_staged_batch(count, a_staged, m, k, x_bits, a_prep, n, N, L,
+                                            _moduli(moduli), a_mask, a_out, _stream(stream))
+    if rc != 0:
+        raise NimbusCopError(rc, "nimbus_cop_matmul_staged_batch")
 
 
 def nimbus_cop_matmul_prepared(X, m, k, x_bits, prepared, n, N, L, moduli, mask, out,

@@ -254,6 +254,33 @@ int nimbus_cop_stage_shares(const uint64_t *X, int m, int k, int x_bits,
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 
+int nimbus_cop_stage_shares_batch(int count, const uint64_t *const *X, int m, int k, int x_bits,
+                                  void *const *workspaces, size_t workspace_bytes, void *stream)
+{
+    if (count < 1 || count > NIMBUS_COP_MAX_BATCH || !X || !workspaces)
+        return NIMBUS_COP_ERR_INVALID_ARG;
+    if (m < 1 || m > kMaxRows || k < 1 || k >= (1 << 24) || x_bits < 1 || x_bits > 64)
+        return NIMBUS_COP_ERR_INVALID_ARG;
+    if (x_bits > 32) return NIMBUS_COP_ERR_UNSUPPORTED;      // wide shares: two halves per problem
+    if (!staging_fits(m, k)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    const size_t need = workspace_bytes_of(m, k, x_bits), x_bytes = (size_t)m * (size_t)k * sizeof(uint64_t);
+    if (workspace_bytes < need) return NIMBUS_COP_ERR_BUFFER_SIZE;
+    for (int i = 0; i < count; ++i)
+        if (!X[i] || !workspaces[i] || ((uintptr_t)workspaces[i] & 15u) != 0)
+            return NIMBUS_COP_ERR_INVALID_ARG;
+    for (int i = 0; i < count; ++i)
+        for (int j = 0; j < count; ++j)
+            if (overlaps(workspaces[i], need, X[j], x_bytes) ||
+                (i != j && overlaps(workspaces[i], need, workspaces[j], need)))
+                return NIMBUS_COP_ERR_INVALID_ARG;
+    Problem p{};
+    p.m = m;
+    p.k = k;
+    p.x_bits = x_bits;
+    const hipError_t e = launch_stage_shares_batch(p, count, X, 0, workspaces, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
 int nimbus_cop_matmul_staged(const void *staged_shares, int m, int k, int x_bits,
                              const void *prepared, int n, int N, int L,
                              const uint64_t *moduli,
@@ -272,6 +299,46 @@ int nimbus_cop_matmul_staged(const void *staged_shares, int m, int k, int x_bits
         overlaps(out, out_bytes, mask, out_bytes))
         return NIMBUS_COP_ERR_INVALID_ARG;
     const hipError_t e = matmul_all(p, staged_shares, prepared, mask, out, (hipStream_t)stream);
+    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+}
+
+int nimbus_cop_matmul_staged_batch(int count, const void *const *staged_shares, int m, int k,
+                                   int x_bits, const void *const *prepared, int n, int N, int L,
+                                   const uint64_t *moduli, const uint64_t *const *masks,
+                                   uint64_t *const *outs, void *stream)
+{
+    if (count < 1 || count > NIMBUS_COP_MAX_BATCH || !staged_shares || !prepared || !outs)
+        return NIMBUS_COP_ERR_INVALID_ARG;
+    if (x_bits > 32) return NIMBUS_COP_ERR_UNSUPPORTED;      // wide shares: two passes per problem
+    Problem p;
+    const int rc = make_problem(m, k, x_bits, n, N, L, moduli, true, &p);
+    if (rc != NIMBUS_COP_OK) return rc;
+    if (!prepared_path_supported(p)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    // tile ids of the whole launch are 32-bit
+    const uint64_t tiles = (uint64_t)(p.C / 64) * (uint64_t)((m + 127) / 128) * (uint64_t)count;
+    if (tiles >= (1ull << 31)) return NIMBUS_COP_ERR_UNSUPPORTED;
+    const size_t out_bytes = (size_t)m * p.C * sizeof(uint64_t);
+    const size_t ws_bytes = workspace_bytes_of(m, k, x_bits), prep_bytes = prepared_bytes_of(p);
+    const uint64_t *no_masks[NIMBUS_COP_MAX_BATCH] = {};
+    for (int i = 0; i < count; ++i) {
+        if (!staged_shares[i] || !prepared[i] || !outs[i]) return NIMBUS_COP_ERR_INVALID_ARG;
+        if ((((uintptr_t)prepared[i] | (uintptr_t)staged_shares[i]) & 15u) != 0)
+            return NIMBUS_COP_ERR_INVALID_ARG;
+        if (masks && (masks[i] == nullptr) != (masks[0] == nullptr))
+            return NIMBUS_COP_ERR_INVALID_ARG;                // a mask for every problem or for none
+    }
+    // no output may overlap anything another problem (or its own) reads or writes
+    for (int i = 0; i < count; ++i)
+        for (int j = 0; j < count; ++j) {
+            if (overlaps(outs[i], out_bytes, staged_shares[j], ws_bytes) ||
+                overlaps(outs[i], out_bytes, prepared[j], prep_bytes) ||
+                (masks && overlaps(outs[i], out_bytes, masks[j], out_bytes)) ||
+                (i != j && overlaps(outs[i], out_bytes, outs[j], out_bytes)))
+                return NIMBUS_COP_ERR_INVALID_ARG;
+        }
+    const hipError_t e = launch_cop_mfma_batch(p, count, staged_shares, prepared,
+                                               masks ? masks : no_masks, nullptr, outs,
+                                               (hipStream_t)stream);
     return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
 }
 

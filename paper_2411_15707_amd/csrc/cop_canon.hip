@@ -382,7 +382,7 @@ __global__ __launch_bounds__(512, 1) void cop_canon_kernel(const CanonArgs ca)
         add128(hi, lo, highs >> 32, highs << 32);
         colsum_S = barrett128(hi, lo, ca.limbs.limb[limb]);      // k * q < 2^(b+63)
     }
-    cop_epilogue<ND, FULL, false>(acc, a, limb, colsum_S, rt * kTile + 4 * (lane >> 5),
+    cop_epilogue<ND, FULL, false>(acc, a, a.mask, nullptr, a.out, limb, colsum_S, rt * kTile + 4 * (lane >> 5),
                                   (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31), nullptr);
 }
 

@@ -64,6 +64,11 @@ hipError_t launch_prepare(const Problem &p, const uint64_t *ctW, void *prepared,
                           hipStream_t stream);
 hipError_t launch_stage_shares(const Problem &p, const uint64_t *X, int half_shift,
                                void *workspace, hipStream_t stream);
+hipError_t launch_stage_shares_batch(const Problem &p, int count, const uint64_t *const *X,
+                                     int half_shift, void *const *workspace, hipStream_t stream);
+hipError_t launch_cop_mfma_batch(const Problem &p, int count, const void *const *staged,
+                                 const void *const *prepared, const uint64_t *const *masks,
+                                 const uint64_t *prev, uint64_t *const *outs, hipStream_t stream);
 hipError_t launch_cop_mfma(const Problem &p, const void *staged, const void *prepared,
                            const uint64_t *mask, const uint64_t *prev, uint64_t *out,
                            hipStream_t stream);

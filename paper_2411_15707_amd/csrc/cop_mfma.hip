@@ -95,11 +95,18 @@ __global__ __launch_bounds__(256) void column_sums_kernel(
 // ---------------------------------------------------------------------------
 // per call: X -> DX signed byte planes in A-operand tile order
 // ---------------------------------------------------------------------------
+// (blockIdx.y: the problem, when the shares of several calls are staged in one launch)
+struct StagePtrs {
+    const uint64_t *X[kMaxBatch];
+    uint32_t *xd[kMaxBatch];
+};
+
 template <int DX>
 __global__ __launch_bounds__(256) void x_planes_kernel(
-    const uint64_t *__restrict__ X, int m, int k, int KB, uint32_t total, uint32_t offx,
-    int half_shift, uint32_t *__restrict__ xd)
+    const StagePtrs sp, int m, int k, int KB, uint32_t total, uint32_t offx, int half_shift)
 {
+    const uint64_t *__restrict__ const X = sp.X[blockIdx.y];
+    uint32_t *__restrict__ const xd = sp.xd[blockIdx.y];
     // one thread = four consecutive k of one row: one 32-bit word in each of the DX planes
     const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
     if (gid >= total) return;
@@ -214,13 +221,14 @@ constexpr int kMaskLoads = kMaskTileBytes / kTileBytes / 8;     // per wave: 8
 constexpr int kMaskPhase = kMaskLoads + 2;                      // iterations that count them
 
 template <int DX, int DQ, bool FULL, bool MASKLDS, bool SHARED>
-__global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
+__global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a, const BatchPtrs b)
 {
     using P_ = Pipe<DX, DQ>;
     // Every scalar argument the setup needs, asked for in one batch: left to the compiler the
     // loads sit next to their first uses, and the setup waits for the constant cache once
     // per group of them instead of once.
-    asm volatile("" ::"s"(a.xd), "s"(a.planes), "s"(a.colsum), "s"(a.m), "s"(a.KB), "s"(a.RB),
+    asm volatile("" ::"s"(b.prob[0].xd), "s"(b.prob[0].planes), "s"(b.prob[0].colsum),
+                 "s"(b.prob[0].mask), "s"(b.prob[0].out), "s"(b.count), "s"(a.m), "s"(a.KB), "s"(a.RB),
                  "s"(a.L), "s"(a.CT), "s"(a.kb_magic), "s"(a.log_n), "s"(a.l_magic));
     constexpr int ND = P_::ND;
     constexpr bool PIPELINED = P_::PIPELINED;
@@ -240,7 +248,19 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // grid that is a multiple of 8 so are the tile ids; the RB row blocks that share a column
     // tile are kept on one XCD and adjacent in that order so that tile is fetched from HBM
     // once.  (The column tiles past the last multiple of 8, if any, are not worth the trouble.)
-    auto map_tile = [&](uint32_t id, uint32_t &ct2, uint32_t &rb) {
+    // (the pointers of a single call are asked for with the first batch of scalar loads: an
+    // indexed load would sit on the path to the first loads of the launch)
+    const bool single = b.count == 1;
+    // (a launch may hold several problems of the same shape: tile ids run through the first
+    // problem's tiles, then the second's, ...; p is the problem)
+    auto map_tile = [&](uint32_t id, uint32_t &p, uint32_t &ct2, uint32_t &rb) {
+        p = 0;
+        if (!single) {
+            while (id >= b.tiles_each) {            // at most kMaxBatch - 1 rounds, scalar
+                id -= b.tiles_each;
+                ++p;
+            }
+        }
         const uint32_t RB = (uint32_t)a.RB;
         const uint32_t CT2a = (a.CT >> 1) & ~7u;
         if (!SHARED) {                              // one row block: no division
@@ -306,11 +326,16 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     __amdgpu_buffer_rsrc_t rsrc;
     uint32_t toff[P_::MAXU];                        // the operand tile's byte offset at k-block 0
     uint32_t src_off, slot_off;
-    auto begin_tile = [&](uint32_t ct2, uint32_t rb) {
+    auto begin_tile = [&](uint32_t p, uint32_t ct2, uint32_t rb) {
+        const uint4 *xd_p = b.prob[0].xd, *planes_p = b.prob[0].planes;
+        if (!single) {
+            xd_p = b.prob[p].xd;
+            planes_p = b.prob[p].planes;
+        }
         const unsigned char *const a_base =
-            (const unsigned char *)a.xd + (size_t)rb * 4u * a_tile_bytes;
+            (const unsigned char *)xd_p + (size_t)rb * 4u * a_tile_bytes;
         const unsigned char *const b_base =
-            (const unsigned char *)a.planes + (size_t)ct2 * 2u * b_tile_bytes;
+            (const unsigned char *)planes_p + (size_t)ct2 * 2u * b_tile_bytes;
         rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(loads_x ? a_base : b_base), 0, 0xffffffff,
                                                  0x00027000);
         uint32_t first_off;
@@ -346,9 +371,9 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         slot_off = bump(slot_off, slot_step, slot_end);                       \
     } while (0)
 
-    uint32_t tile = blockIdx.x, ct2, rb;
-    map_tile(tile, ct2, rb);
-    begin_tile(ct2, rb);
+    uint32_t tile = blockIdx.x, prob, ct2, rb;
+    map_tile(tile, prob, ct2, rb);
+    begin_tile(prob, ct2, rb);
     n_loads = __builtin_amdgcn_readfirstlane(n_loads);
 
     // One pass of this loop per tile.  The first stages of a tile other than the first are
@@ -397,8 +422,16 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // the wait for it at its first use, and the statements below that clobber memory keep the
     // load itself up here.  (One more load ahead of the loop's counted waits only makes them
     // wait for it too; it is the oldest but LEAD stages by then.)
+    const uint64_t *colsum_p = b.prob[0].colsum;
+    const uint64_t *mask_p = b.prob[0].mask;
+    uint64_t *out_p = b.prob[0].out;
+    if (!single) {
+        colsum_p = b.prob[prob].colsum;
+        mask_p = b.prob[prob].mask;
+        out_p = b.prob[prob].out;
+    }
     const uint64_t colsum_S =
-        a.colsum[(ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31)];
+        colsum_p[(ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane & 31)];
     asm volatile("" ::: "memory");
     // The limb of this wave's 32 columns (they lie in one (polynomial, limb) block of N >= 32
     // columns), worked out here with a shift and a multiply-high: after the loop it would sit
@@ -551,7 +584,7 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
         const uint64_t first = ((uint64_t)rb * 128u * a.C + (uint64_t)ct2 * 64u) * 8u;
         const uint64_t left = (uint64_t)a.m * a.C * 8u - first;
         rsrc_m = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)((const unsigned char *)a.mask + first), 0,
+            (void *)((const unsigned char *)mask_p + first), 0,
             left > 0xffffffffull ? 0xffffffffu : (uint32_t)left, 0x00027000);
         voff_m = (uint32_t)(lane >> 5) * a.C * 8u + (uint32_t)(lane & 31) * 16u;
         soff_m = (uint32_t)wave * 2u * a.C * 8u;
@@ -661,11 +694,11 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     // epilogue, which uses neither the rings nor the memory pipeline much, to land.
     const uint32_t next = tile + gridDim.x;
     const bool more = next < a.tiles;
-    uint32_t next_ct2 = 0, next_rb = 0;
+    uint32_t next_prob = 0, next_ct2 = 0, next_rb = 0;
     if (more) {
         if constexpr (!PIPELINED) __builtin_amdgcn_s_barrier();
-        map_tile(next, next_ct2, next_rb);
-        begin_tile(next_ct2, next_rb);
+        map_tile(next, next_prob, next_ct2, next_rb);
+        begin_tile(next_prob, next_ct2, next_rb);
 #pragma unroll
         for (int st = 0; st < LEAD; ++st) {
             if (st < KB) {
@@ -685,12 +718,13 @@ __global__ __launch_bounds__(512, 1) void cop_mfma_kernel(const MfmaArgs a)
     asm volatile("" : "+v"(lane_e));
     if (active)
         cop_epilogue<ND, FULL, MASKLDS>(
-            acc, a, limb, colsum_S, rt * kTile + 4 * (lane_e >> 5),
+            acc, a, mask_p, a.prev, out_p, limb, colsum_S, rt * kTile + 4 * (lane_e >> 5),
             (ct2 * 2u + (uint32_t)wc) * kTile + (uint32_t)(lane_e & 31),
             lds + (MASKLDS ? P_::LDS_BYTES : 0) + (uint32_t)(wr * kTile + 4 * (lane_e >> 5)) * 512u +
                 (uint32_t)(wc * kTile + (lane_e & 31)) * 8u);
     if (!more) break;
     tile = next;
+    prob = next_prob;
     ct2 = next_ct2;
     rb = next_rb;
     }   // tiles
@@ -756,41 +790,64 @@ hipError_t launch_prepare(const Problem &p, const uint64_t *ctW, void *prepared,
 }
 
 template <int DX>
-static hipError_t stage_impl(const Problem &p, const uint64_t *X, int half_shift, void *workspace,
-                             hipStream_t stream)
+static hipError_t stage_impl(const Problem &p, int count, const uint64_t *const *X, int half_shift,
+                             void *const *workspace, hipStream_t stream)
 {
     const int KB = kblocks(p.k);
     const int RT = (p.m + kTile - 1) / kTile;
     const uint32_t xtotal = (uint32_t)RT * KB * 256;
-    return launch(x_planes_kernel<DX>, dim3((xtotal + 255) / 256), dim3(256), stream,
-                  X, p.m, p.k, KB, xtotal, share_offset(p.x_bits, DX), half_shift,
-                  (uint32_t *)workspace);
+    StagePtrs sp{};
+    for (int i = 0; i < count; ++i) {
+        sp.X[i] = X[i];
+        sp.xd[i] = (uint32_t *)workspace[i];
+    }
+    return launch(x_planes_kernel<DX>, dim3((xtotal + 255) / 256, (uint32_t)count), dim3(256), stream,
+                  sp, p.m, p.k, KB, xtotal, share_offset(p.x_bits, DX), half_shift);
 }
 
 // p.x_bits (<= 32) is the width of the half that is staged; half_shift is 0 or 32
 hipError_t launch_stage_shares(const Problem &p, const uint64_t *X, int half_shift,
                                void *workspace, hipStream_t stream)
 {
+    return launch_stage_shares_batch(p, 1, &X, half_shift, &workspace, stream);
+}
+
+// the shares of count calls of the same shape in one launch
+hipError_t launch_stage_shares_batch(const Problem &p, int count, const uint64_t *const *X,
+                                     int half_shift, void *const *workspace, hipStream_t stream)
+{
+    if (count < 1 || count > kMaxBatch) return hipErrorInvalidValue;
     switch (planes_x(p.x_bits)) {
-    case 2: return stage_impl<2>(p, X, half_shift, workspace, stream);
-    case 3: return stage_impl<3>(p, X, half_shift, workspace, stream);
-    default: return stage_impl<4>(p, X, half_shift, workspace, stream);
+    case 2: return stage_impl<2>(p, count, X, half_shift, workspace, stream);
+    case 3: return stage_impl<3>(p, count, X, half_shift, workspace, stream);
+    default: return stage_impl<4>(p, count, X, half_shift, workspace, stream);
     }
 }
 
+// count problems of the same shape in one launch (count = 1: the ordinary call); the masks are
+// all there or all null; prev only with count = 1
 template <int DX, int DQ>
-static hipError_t mfma_impl(const Problem &p, const void *staged, const void *prepared,
-                            const uint64_t *mask, const uint64_t *prev, uint64_t *out,
-                            hipStream_t stream)
+static hipError_t mfma_impl(const Problem &p, int count, const void *const *staged,
+                            const void *const *prepared, const uint64_t *const *masks,
+                            const uint64_t *prev, uint64_t *const *outs, hipStream_t stream)
 {
     const int KB = kblocks(p.k);
     const uint32_t CT = (uint32_t)(p.C / kTile);
+    const uint64_t *const mask = masks[0];
 
     MfmaArgs a{};
-    fill_common_args(p, DX, mask, prev, out, &a);
-    a.xd = (const uint4 *)staged;
-    a.planes = (const uint4 *)prepared;
-    a.colsum = (const uint64_t *)((const char *)prepared + (size_t)CT * KB * DQ * kTileBytes);
+    fill_common_args(p, DX, mask, prev, outs[0], &a);
+    BatchPtrs b{};
+    for (int i = 0; i < count; ++i) {
+        b.prob[i].xd = (const uint4 *)staged[i];
+        b.prob[i].planes = (const uint4 *)prepared[i];
+        b.prob[i].colsum = (const uint64_t *)((const char *)prepared[i] + (size_t)CT * KB * DQ * kTileBytes);
+        b.prob[i].mask = masks[i];
+        b.prob[i].out = outs[i];
+    }
+    b.count = (uint32_t)count;
+    b.tiles_each = a.tiles;
+    a.tiles *= (uint32_t)count;
     // One workgroup per compute unit at most (a compute unit holds one at a time anyway);
     // each walks the tiles id, id + grid, ...  A grid that is a multiple of 8 keeps a tile id's
     // XCD the same on every pass.
@@ -806,7 +863,7 @@ static hipError_t mfma_impl(const Problem &p, const void *staged, const void *pr
     auto launch = [&](auto full_c, auto masklds_c, auto shared_c) {
         return nimbus::launch(cop_mfma_kernel<DX, DQ, decltype(full_c)::value,
                                               decltype(masklds_c)::value, decltype(shared_c)::value>,
-                              grid, dim3(512), stream, a);
+                              grid, dim3(512), stream, a, b);
     };
     using T = std::true_type;
     using F = std::false_type;
@@ -821,9 +878,18 @@ hipError_t launch_cop_mfma(const Problem &p, const void *staged, const void *pre
                            const uint64_t *mask, const uint64_t *prev, uint64_t *out,
                            hipStream_t stream)
 {
+    return launch_cop_mfma_batch(p, 1, &staged, &prepared, &mask, prev, &out, stream);
+}
+
+hipError_t launch_cop_mfma_batch(const Problem &p, int count, const void *const *staged,
+                                 const void *const *prepared, const uint64_t *const *masks,
+                                 const uint64_t *prev, uint64_t *const *outs, hipStream_t stream)
+{
+    if (count < 1 || count > kMaxBatch) return hipErrorInvalidValue;
     const int DX = planes_x(p.x_bits), DQ = planes_q(p.q_bits_max);
 #define NIMBUS_CASE(dx, dq) \
-    if (DX == dx && DQ == dq) return mfma_impl<dx, dq>(p, staged, prepared, mask, prev, out, stream);
+    if (DX == dx && DQ == dq) \
+        return mfma_impl<dx, dq>(p, count, staged, prepared, masks, prev, outs, stream);
     NIMBUS_CASE(2, 7)
     NIMBUS_CASE(3, 7)
     NIMBUS_CASE(4, 7)

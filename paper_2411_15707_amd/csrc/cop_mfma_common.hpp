@@ -41,6 +41,22 @@ struct MfmaArgs {
     uint64_t cst_hi[kMaxLimbs], cst_lo[kMaxLimbs];
 };
 
+// The problems of one launch: same sizes and moduli, their own shares, weights, mask and
+// output.  A single call is a batch of one.
+constexpr int kMaxBatch = 16;
+struct ProblemPtrs {
+    const uint4 *xd;            // staged shares
+    const uint4 *planes;        // prepared weights
+    const uint64_t *colsum;     // their column sums
+    const uint64_t *mask;       // or null (all problems or none)
+    uint64_t *out;
+};
+struct BatchPtrs {
+    uint32_t count;
+    uint32_t tiles_each;        // output tiles of one problem
+    ProblemPtrs prob[kMaxBatch];    // (problem 0 first: one cache line with the two words above)
+};
+
 // ---- host side: constants of the argument block ----
 static inline int ceil_log2(unsigned v)
 {
@@ -230,6 +246,8 @@ __device__ __forceinline__ void wait_vmem_loads(int n)
 
 // ---------------------------------------------------------------------------
 // epilogue: rebuild the sums from the diagonals, add the constant and the mask, reduce, store
+//   mask, prev, out  the problem's mask (or null), the result of the pass over the upper share
+//              halves (or null) and its output, [m][C] each
 //   acc        the wave's ND = DX + DQ - 1 accumulator tiles (32 x 32 outputs: element r of
 //              the lane is row row0 + 8 (r / 4) + r % 4, column col)
 //   limb       limb of the wave's 32 columns;  colsum_S  sum of the column's residues mod q
@@ -237,9 +255,10 @@ __device__ __forceinline__ void wait_vmem_loads(int n)
 //   mask_tile  MASKLDS: the lane's word of row0 in the workgroup's mask tile in LDS
 // ---------------------------------------------------------------------------
 template <int ND, bool FULL, bool MASKLDS>
-__device__ __forceinline__ void cop_epilogue(v16i (&acc)[ND], const MfmaArgs &a, uint32_t limb,
-                                             uint64_t colsum_S, int row0, uint32_t col,
-                                             const unsigned char *mask_tile)
+__device__ __forceinline__ void cop_epilogue(v16i (&acc)[ND], const MfmaArgs &a,
+                                             const uint64_t *mask, const uint64_t *prev,
+                                             uint64_t *out, uint32_t limb, uint64_t colsum_S,
+                                             int row0, uint32_t col, const unsigned char *mask_tile)
 {
     const uint64_t q = a.q[limb];
     const double qinv = a.qinv[limb];
@@ -249,15 +268,15 @@ __device__ __forceinline__ void cop_epilogue(v16i (&acc)[ND], const MfmaArgs &a,
     // row0 plus a wave-uniform multiple of the row length
     auto roff = [](int r) -> int { return 8 * (r >> 2) + (r & 3); };
     const size_t lane_elem = (size_t)row0 * a.C + col;
-    const uint64_t *const mask0 = a.mask ? a.mask + lane_elem : nullptr;
-    const uint64_t *const prev0 = a.prev ? a.prev + lane_elem : nullptr;
-    uint64_t *const out0 = a.out + lane_elem;
+    const uint64_t *const mask0 = mask ? mask + lane_elem : nullptr;
+    const uint64_t *const prev0 = prev ? prev + lane_elem : nullptr;
+    uint64_t *const out0 = out + lane_elem;
     uint64_t mk[16];                                // read once: streaming loads
     if constexpr (MASKLDS) {
         // the tile is in LDS, row-major [128][64] words; mask_tile is the lane's word of row0
 #pragma unroll
         for (int r = 0; r < 16; ++r) mk[r] = *(const uint64_t *)(mask_tile + roff(r) * 512);
-    } else if (a.mask) {
+    } else if (mask) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             mk[r] = (FULL || row0 + roff(r) < a.m)
@@ -337,7 +356,7 @@ __device__ __forceinline__ void cop_epilogue(v16i (&acc)[ND], const MfmaArgs &a,
     // the same lane, and every read comes before the first write).  2^32 prev < 2^32 q keeps
     // V below 2^47 q.  (A block of its own behind one wave-uniform branch: the narrow path
     // does not execute any of it.)
-    if (a.prev) {
+    if (prev) {
         uint64_t pv[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r)

@@ -110,6 +110,50 @@ def test_static_workspace_limit_is_checked_on_the_host():
     assert rc == -2
 
 
+def test_batch_entry_points_check_their_arguments_on_the_host():
+    """the entry points that take several problems in one launch: count, the pointer arrays, a
+    mask for every problem or for none, no output on top of another buffer of the batch"""
+    lib = _raw()
+    mod = (ctypes.c_uint64 * 1)(*ci.limb_primes(54, 20, 1))
+    vp = ctypes.c_void_p
+    m, k, n, N, L, xb = 4, 64, 32, 32, 1, 20
+    out_bytes = m * 2 * L * N * 8
+
+    def arr(*v):
+        return (vp * len(v))(*v)
+    good = dict(staged=arr(0x100000, 0x200000), prep=arr(0x300000, 0x400000),
+                masks=arr(0x500000, 0x600000), outs=arr(0x700000, 0x800000))
+
+    def call(count=2, **kw):
+        a = dict(good, **kw)
+        return lib.nimbus_cop_matmul_staged_batch(count, a["staged"], m, k, xb, a["prep"], n, N, L, mod,
+                                                  a["masks"], a["outs"], None)
+    assert call(count=0) == -1
+    assert call(count=17) == -1
+    assert call(staged=None) == -1
+    assert call(outs=arr(0x700000, None)) == -1
+    assert call(prep=arr(0x300000, 0x400008)) == -1                      # misaligned
+    assert call(masks=arr(0x500000, None)) == -1                         # a mask for one problem only
+    assert call(outs=arr(0x700000, 0x700000 + out_bytes // 2)) == -1     # outputs on top of each other
+    assert call(outs=arr(0x700000, 0x500000)) == -1                      # output on another problem's mask
+    assert call(outs=arr(0x700000, 0x300000)) == -1                      # output on prepared weights
+    assert lib.nimbus_cop_matmul_staged_batch(2, good["staged"], m, k, 40, good["prep"], n, N, L, mod,
+                                              None, good["outs"], None) == -2      # wide shares
+    assert lib.nimbus_cop_matmul_staged_batch(2, good["staged"], m, 50000, xb, good["prep"], n, N, L, mod,
+                                              None, good["outs"], None) == -2      # k beyond the bound
+    # staging
+    ws = nc.nimbus_cop_workspace_bytes(m, k, xb)
+    X = arr(0x100000, 0x200000)
+    W = arr(0x300000, 0x400000)
+    assert lib.nimbus_cop_stage_shares_batch(0, X, m, k, xb, W, ws, None) == -1
+    assert lib.nimbus_cop_stage_shares_batch(17, X, m, k, xb, W, ws, None) == -1
+    assert lib.nimbus_cop_stage_shares_batch(2, X, m, k, xb, W, ws - 1, None) == -4
+    assert lib.nimbus_cop_stage_shares_batch(2, X, m, k, 40, W, ws, None) == -2
+    assert lib.nimbus_cop_stage_shares_batch(2, X, m, k, xb, arr(0x300000, 0x300008), ws, None) == -1
+    assert lib.nimbus_cop_stage_shares_batch(2, X, m, k, xb, arr(0x300000, 0x300000 + 16), ws, None) == -1
+    assert lib.nimbus_cop_stage_shares_batch(2, X, m, k, xb, arr(0x300000, 0x100000), ws, None) == -1
+
+
 def test_prepared_path_limits_and_buffer_sizes():
     lib = _raw()
     mod = (ctypes.c_uint64 * 1)(*ci.limb_primes(54, 20, 1))

@@ -470,6 +470,46 @@ def test_wide_shares_two_pass_path(oracle, m, k, n, N, L, x_bits, q_bits):
         assert np.array_equal(got, want), gu.first_mismatch(got, want)
 
 
+# m, k, n, N, L, t_bits, q_bits, problems, with masks
+BATCHES = [
+    (128, 416, 64, 64, 2, 20, 54, 5, True),       # mask tile through LDS, 13 k-blocks
+    (33, 100, 40, 64, 2, 20, 54, 3, True),        # ragged rows and k
+    (256, 100, 256, 256, 1, 20, 54, 3, True),     # two row blocks per column tile
+    (128, 96, 8192, 8192, 3, 20, 54, 2, False),   # 768 tiles each: more tiles than compute units
+    (64, 70, 64, 64, 1, 32, 62, 4, True),         # 4 x 8 planes (operands read after the barrier)
+    (8, 64, 64, 1024, 1, 16, 50, 16, True),       # the largest batch, config 1's shape
+    (40, 96, 128, 128, 3, 24, 55, 1, True),       # a batch of one
+]
+
+
+@pytest.mark.parametrize("m,k,n,N,L,t_bits,q_bits,count,with_mask", BATCHES)
+def test_several_problems_in_one_launch(oracle, m, k, n, N, L, t_bits, q_bits, count, with_mask):
+    """nimbus_cop_stage_shares_batch + nimbus_cop_matmul_staged_batch: independent share
+    matrices, weights, masks and outputs of one shape in one launch each, every output equal
+    to the oracle's (and so to separate calls)"""
+    import torch
+    import gpu_util as gu
+    import paper_2411_15707_amd as nc
+    moduli = ci.limb_primes(q_bits, t_bits, L)
+    Ch = -(-n // N)
+    probs = [_inputs(9000 + 17 * i + m, m, k, n, N, moduli, t_bits, with_mask) for i in range(count)]
+    probs[0][0][0, :] = (1 << t_bits) - 1
+    _say(f"[parity] batch of {count}: m={m} k={k} n={n} N={N} L={L}")
+    dXs = [gu.dev(X) for X, _, _ in probs]
+    preps = [gu.prepare(ctW, moduli, n, N) for _, ctW, _ in probs]
+    masks = [gu.dev(mk) for _, _, mk in probs] if with_mask else None
+    wss = [torch.empty(nc.nimbus_cop_workspace_bytes(m, k, t_bits), dtype=torch.uint8, device="cuda")
+           for _ in range(count)]
+    outs = [torch.full((m, Ch, 2, L, N), -1, dtype=torch.int64, device="cuda") for _ in range(count)]
+    nc.nimbus_cop_stage_shares_batch(dXs, m, k, t_bits, wss)
+    nc.nimbus_cop_matmul_staged_batch(wss, m, k, t_bits, preps, n, N, L, moduli, masks, outs)
+    torch.cuda.synchronize()
+    for i, (X, ctW, mk) in enumerate(probs):
+        want, _ = oracle.cop_ref(X, ctW, moduli, n, N, mk)
+        got = gu.host(outs[i])
+        assert np.array_equal(got, want), f"problem {i}: " + gu.first_mismatch(got, want)
+
+
 def test_calibration_launches_run():
     """the benchmark's calibration kernels enqueue and report the work they were asked for"""
     import torch
