@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefetch", action="store_true", help="skip the weight-loading stack")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the steps")
+    ap.add_argument("--no-batched", action="store_true",
+                    help="skip the run with several steps per launch")
     ap.add_argument("--no-two-streams", action="store_true",
                     help="skip the run with two batches in flight on two streams")
     args = ap.parse_args()
@@ -275,6 +277,58 @@ def main():
         two_streams["kernel_only_ms_per_launch"] = round(k2, 5)
         two_streams["kernel_only_hbm_gbps"] = round(alg_bytes / (k2 * 1e-3) / 1e9, 1)
         two_streams["kernel_only_frac_of_hbm_peak"] = round(alg_bytes / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+
+    # ---- several steps in one launch (nimbus_cop_stage_shares_batch + nimbus_cop_matmul_staged_batch):
+    # what a caller pays per step who has the shares of several layers or requests at hand.
+    # Same problems, same buffers, same outputs as the timed steps above. ----
+    batched = None
+    if not args.no_batched and R >= 2 and xb <= 32:
+        Bn = min(12, R)
+        bws = [torch.empty_like(ws) for _ in range(Bn)]
+        want = []
+        for r in range(Bn):
+            step(r)
+        torch.cuda.synchronize()
+        want = [outs[r].clone() for r in range(Bn)]
+        for r in range(Bn):
+            outs[r].zero_()
+
+        def batch_step():
+            nc.nimbus_cop_stage_shares_batch(Xs[:Bn], m, k, xb, bws)
+            nc.nimbus_cop_matmul_staged_batch(bws, m, k, xb, preps[:Bn], n, N, L, moduli, masks[:Bn], outs[:Bn])
+
+        def batch_kernel():
+            nc.nimbus_cop_matmul_staged_batch(bws, m, k, xb, preps[:Bn], n, N, L, moduli, masks[:Bn], outs[:Bn])
+        batch_step()
+        torch.cuda.synchronize()
+        same = all(bool(torch.equal(outs[r], want[r])) for r in range(Bn))
+        del want
+        reps_b = max(10, min(args.steps, 2000) // Bn)
+
+        def timed_b(fn):
+            for _ in range(max(3, reps_b // 10)):
+                fn()
+            eb0, eb1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            eb0.record(stream)
+            for _ in range(reps_b):
+                fn()
+            eb1.record(stream)
+            torch.cuda.synchronize()
+            return eb0.elapsed_time(eb1) / reps_b / Bn
+        bstep_ms, bkern_ms = timed_b(batch_step), timed_b(batch_kernel)
+        batched = {
+            "problems_per_launch": Bn,
+            "launches_timed": reps_b,
+            "ms_per_step": round(bstep_ms, 5),
+            "value": round(cfg.mod_macs / (bstep_ms * 1e-3), 1),
+            "kernel_ms_per_problem": round(bkern_ms, 5),
+            "kernel_hbm_gbps": round(alg_bytes / (bkern_ms * 1e-3) / 1e9, 1),
+            "kernel_frac_of_hbm_peak": round(alg_bytes / (bkern_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "outputs_equal_separate_calls": same,
+            "note": "one staging launch and one matmul launch for all the problems; per problem",
+        }
+        del bws
 
     # ---- the canonical-layout entry points on the same workload (no setup pass, 8 B residues):
     # nimbus_cop_matmul (matrix-core kernel that splits the words into byte planes itself) and
@@ -602,6 +656,7 @@ def main():
         },
         "ms_per_step_hip_graph": None if graph_ms_per_step is None else round(graph_ms_per_step, 5),
         "two_streams": two_streams,
+        "batched": batched,
         "hbm_gbps_whole_step": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "canonical_layout": canonical,
         "roofline": roofline,
