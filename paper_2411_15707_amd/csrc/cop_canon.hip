@@ -437,9 +437,11 @@ static hipError_t canon_impl(const Problem &p, const uint64_t *X, const uint64_t
     };
     using T = std::true_type;
     using F = std::false_type;
-    if (centre) {
-        if (full) return shared ? go(T{}, T{}, T{}) : go(T{}, F{}, T{});
-        return shared ? go(F{}, T{}, T{}) : go(F{}, F{}, T{});
+    if constexpr (DQ == 7) {                        // (eight digits express every q < 2^62)
+        if (centre) {
+            if (full) return shared ? go(T{}, T{}, T{}) : go(T{}, F{}, T{});
+            return shared ? go(F{}, T{}, T{}) : go(F{}, F{}, T{});
+        }
     }
     if (full) return shared ? go(T{}, T{}, F{}) : go(T{}, F{}, F{});
     return shared ? go(F{}, T{}, F{}) : go(F{}, F{}, F{});
