@@ -105,7 +105,37 @@ def main():
         nc.nimbus_cop_matmul_prepared(Xs[r], m, k, xb, preps[r], n, N, L, moduli, masks[r],
                                       outs[r], ws)
 
+    # A chip that has been idle, even for ten milliseconds of host work, takes some 25 ms of
+    # load (700 launches of this kernel) to settle its clocks, and runs up to a quarter slower
+    # meanwhile.  Every timed region below therefore follows directly on about 50 ms of untimed
+    # launches of the same work, whatever W and K are.
+    def settle(fn, seconds=0.05):
+        """untimed calls fn(0), fn(1), ... for `seconds` of wall-clock, never far ahead of the GPU"""
+        c0, i = time.perf_counter(), 0
+        while time.perf_counter() - c0 < seconds:
+            fn(i)
+            i += 1
+            if i % 64 == 0:
+                torch.cuda.synchronize()
+
+    def event_timed(fn, count, record_on=None):
+        """ms per call of fn(i), i < count: settle, then one event pair around all the calls, on the
+        stream they are launched on"""
+        st = record_on if record_on is not None else torch.cuda.current_stream()
+        settle(fn)
+        a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a_.record(st)
+        for i in range(count):
+            fn(i)
+        b_.record(st)
+        torch.cuda.synchronize()
+        return a_.elapsed_time(b_) / count
+    # launches of the event-timed side regions: K, but never so few that one clock step decides
+    side_launches = max(args.steps, 500)
+
     # ---- whole-path timing: W warm-up steps, then exactly K steps ----
+    settle(lambda i: step(i % R))
     for s in range(args.warmup):
         step(s % R)
     torch.cuda.synchronize()
@@ -155,7 +185,7 @@ def main():
         for r in range(S):
             outs[r].zero_()
         torch.cuda.synchronize()
-        run(max(Rs, args.warmup // 2, 100))
+        settle(lambda i: run(Rs))
         torch.cuda.synchronize()
         steps2 = max(Rs, args.steps, 1000)          # enough launches whatever --steps is
         steps2 -= steps2 % Rs
@@ -185,7 +215,8 @@ def main():
         with torch.cuda.graph(graph, stream=side):
             for r in range(R):
                 step(r)
-        replays = max(1, args.steps // R)
+        replays = max(1, side_launches // R)
+        settle(lambda i: graph.replay())
         for _ in range(max(1, args.warmup // R)):
             graph.replay()
         torch.cuda.synchronize()
@@ -203,24 +234,15 @@ def main():
         nc.nimbus_cop_stage_shares(Xs[r], m, k, xb, w)
         staged.append(w)
     torch.cuda.synchronize()
-    # One pair of events around the K launches of the timed region, on the stream they are
-    # launched on: average duration per launch = elapsed / K (launch gaps included).  An
+    # One pair of events around all the launches of the timed region, on the stream they are
+    # launched on: average duration per launch = elapsed / launches (launch gaps included).  An
     # event pair around every single launch would add several microseconds of queue
     # draining to each.
     stream = torch.cuda.current_stream()
-    for s in range(args.warmup):
-        nc.nimbus_cop_matmul_staged(staged[s % R], m, k, xb, preps[s % R], n, N, L, moduli,
-                                    masks[s % R], outs[s % R])
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record(stream)
-    for s in range(args.steps):
-        r = s % R
-        nc.nimbus_cop_matmul_staged(staged[r], m, k, xb, preps[r], n, N, L, moduli, masks[r],
-                                    outs[r])
-    e1.record(stream)
-    torch.cuda.synchronize()
-    kernel_ms_avg = e0.elapsed_time(e1) / args.steps
+    kernel_launches = side_launches
+    kernel_ms_avg = event_timed(
+        lambda i: nc.nimbus_cop_matmul_staged(staged[i % R], m, k, xb, preps[i % R], n, N, L, moduli,
+                                              masks[i % R], outs[i % R]), kernel_launches, stream)
     alg_bytes = cfg.alg_bytes              # 8 B/residue: ctW once + mask + out + X
     achieved_gbps = alg_bytes / (kernel_ms_avg * 1e-3) / 1e9
     # byte-digit MACs the kernel issues: DX x DQ int8 MACs per modular MAC (k padded to 32)
@@ -253,7 +275,7 @@ def main():
         "hbm_gbps_achieved": round(achieved_gbps, 1),
         "hbm_frac_of_peak": round(achieved_gbps / HBM_PEAK_GBPS, 4),
         "kernel_ms_avg": round(kernel_ms_avg, 5),
-        "launches_timed": args.steps,
+        "launches_timed": kernel_launches,
         "mfma_int8_tops_achieved": round(i8_tops, 1),
         "mfma_int8_frac_of_peak": round(i8_tops / INT8_PEAK_TOPS, 4),
     })
@@ -269,7 +291,7 @@ def main():
                 nc.nimbus_cop_matmul_staged(staged[r], m, k, xb, preps[r], n, N, L, moduli, masks[r],
                                             outs[r], stream=streams[r % S])
 
-        run_kernel(max(Rs, args.warmup // 2, 100))
+        settle(lambda i: run_kernel(Rs))
         torch.cuda.synchronize()
         launches2 = max(Rs, args.steps, 1000)
         launches2 -= launches2 % Rs
@@ -303,19 +325,10 @@ def main():
         torch.cuda.synchronize()
         same = all(bool(torch.equal(outs[r], want[r])) for r in range(Bn))
         del want
-        reps_b = max(10, min(args.steps, 2000) // Bn)
+        reps_b = max(10, min(side_launches, 2000) // Bn)
 
         def timed_b(fn):
-            for _ in range(max(3, reps_b // 10)):
-                fn()
-            eb0, eb1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            eb0.record(stream)
-            for _ in range(reps_b):
-                fn()
-            eb1.record(stream)
-            torch.cuda.synchronize()
-            return eb0.elapsed_time(eb1) / reps_b / Bn
+            return event_timed(lambda i: fn(), reps_b, stream) / Bn
         bstep_ms, bkern_ms = timed_b(batch_step), timed_b(batch_kernel)
         batched = {
             "problems_per_launch": Bn,
@@ -341,17 +354,9 @@ def main():
                              for _ in range(Rc - 1)]
 
     def timed_entry(fn, reps):
-        for s_ in range(min(reps, 20)):
-            fn(Xs[0], m, k, xb, dWs[s_ % Rc], n, N, L, moduli, masks[0], outs[0])
-        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        ea.record(stream)
-        for s_ in range(reps):
-            fn(Xs[0], m, k, xb, dWs[s_ % Rc], n, N, L, moduli, masks[0], outs[0])
-        eb.record(stream)
-        torch.cuda.synchronize()
-        return ea.elapsed_time(eb) / reps
-    canon_ms = timed_entry(nc.nimbus_cop_matmul, max(100, min(args.steps, 1000)))
+        return event_timed(lambda i: fn(Xs[0], m, k, xb, dWs[i % Rc], n, N, L, moduli, masks[0], outs[0]),
+                           reps, stream)
+    canon_ms = timed_entry(nc.nimbus_cop_matmul, min(side_launches, 1000))
     valu_ms = timed_entry(nc.nimbus_cop_matmul_valu, 10)
     # digits of the centred residue only where seven or eight signed digits cannot express q - 1
     centre = any(q - 1 > int("7f" * DQ, 16) for q in moduli)
@@ -385,18 +390,15 @@ def main():
         T = nc.nimbus_cop_packed_count(m, cfg.n, N)
         packed = [torch.empty((T, 2, L, N), dtype=torch.int64, device="cuda") for _ in range(R)]
         pmask = [masks[r].reshape(-1)[:T * 2 * L * N] for r in range(R)]     # T <= m rows of residues
-        for s in range(20):
-            nc.nimbus_cop_pack(outs[s % R], m, cfg.n, N, L, moduli, pmask[s % R], packed[s % R])
-        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        def pack_call(i):
+            nc.nimbus_cop_pack(outs[i % R], m, cfg.n, N, L, moduli, pmask[i % R], packed[i % R])
+        pack_ms = event_timed(pack_call, side_launches, stream)
         torch.cuda.synchronize()
-        p0.record(stream)
         h0 = time.perf_counter()
-        for s in range(args.steps):
-            nc.nimbus_cop_pack(outs[s % R], m, cfg.n, N, L, moduli, pmask[s % R], packed[s % R])
-        pack_host_us = (time.perf_counter() - h0) * 1e6 / args.steps
-        p1.record(stream)
+        for s in range(200):
+            pack_call(s)
+        pack_host_us = (time.perf_counter() - h0) * 1e6 / 200
         torch.cuda.synchronize()
-        pack_ms = p0.elapsed_time(p1) / args.steps
         pack_bytes = 8 * 2 * L * N * (m + 2 * T)       # rows read, mask read, packed written
 
         # Algorithm 1 steps 2-4 as a caller who packs runs them: matmul without mask, then the
@@ -404,28 +406,12 @@ def main():
         def layer(r):
             nc.nimbus_cop_matmul_prepared(Xs[r], m, k, xb, preps[r], n, N, L, moduli, None, outs[r], ws)
             nc.nimbus_cop_pack(outs[r], m, cfg.n, N, L, moduli, pmask[r], packed[r])
-        for s in range(max(20, args.warmup)):
-            layer(s % R)
-        torch.cuda.synchronize()
-        p0.record(stream)
-        for s in range(args.steps):
-            layer(s % R)
-        p1.record(stream)
-        torch.cuda.synchronize()
-        layer_ms = p0.elapsed_time(p1) / args.steps
+        layer_ms = event_timed(lambda i: layer(i % R), side_launches, stream)
         # the matmul kernel of that sequence alone: no mask to read (Algorithm 1 masks after the
         # packing), so 8 bytes per output less than the masked call of the roofline object
-        for s in range(max(20, args.warmup)):
-            nc.nimbus_cop_matmul_staged(staged[s % R], m, k, xb, preps[s % R], n, N, L, moduli, None,
-                                        outs[s % R])
-        torch.cuda.synchronize()
-        p0.record(stream)
-        for s in range(args.steps):
-            nc.nimbus_cop_matmul_staged(staged[s % R], m, k, xb, preps[s % R], n, N, L, moduli, None,
-                                        outs[s % R])
-        p1.record(stream)
-        torch.cuda.synchronize()
-        nomask_ms = p0.elapsed_time(p1) / args.steps
+        nomask_ms = event_timed(
+            lambda i: nc.nimbus_cop_matmul_staged(staged[i % R], m, k, xb, preps[i % R], n, N, L, moduli,
+                                                  None, outs[i % R]), side_launches, stream)
         nomask_bytes = alg_bytes - 8 * m * C
         pack = {
             "kernel": "cop_pack_kernel",
@@ -468,15 +454,7 @@ def main():
         phi_big = torch.empty((Tb, L, N), dtype=torch.int64, device="cuda")
 
         def timed_ms(launch, reps):
-            launch()
-            a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            a_.record(stream)
-            for _ in range(reps):
-                launch()
-            b_.record(stream)
-            torch.cuda.synchronize()
-            return a_.elapsed_time(b_) / reps
+            return event_timed(lambda i: launch(), reps, stream)
         enc_ms = timed_ms(lambda: nc.nimbus_rlwe_encrypt(Wp, k, n, xb, N, L, moduli, tables, a_dev,
                                                          e_dev, ct_enc), 20)
         dec_ms = timed_ms(lambda: nc.nimbus_rlwe_decrypt(outs[0].view(rows, 2, L, N), rows, N, L,
@@ -564,7 +542,7 @@ def main():
     # (register-only int8 matrix-core loop with zero and with random operand bytes; streaming
     # read of one prepared weight buffer per launch, rotating over all of them)
     def timed(launch, reps):
-        launch(0)
+        settle(launch)
         a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         a_.record(stream)
