@@ -51,15 +51,67 @@ struct RlweLimb {
     uint64_t psi_inv;   // its inverse (setup only)
     uint64_t n_inv;     // N^-1 mod q (setup only)
     uint64_t delta;     // floor(Q / t) mod q (encryption only)
+    uint32_t fold_m;    // floor(2^(64 + fold_k) / q), below 2^32 (see fold(); q >= 2^34 only)
+    uint32_t fold_k;    // bit length of q minus 33
 };
 
 struct RlweArgs {
     RlweLimb limb[kMaxLimbs];
 };
 
-__device__ __forceinline__ uint64_t mul_lazy(uint64_t x, const Twiddle &t, uint64_t q)
+// With nq = 2^64 - q the same value is  x w + floor(x w' / 2^64) nq  (mod 2^64): the multiply-add
+// chain of the second product takes the first as its addend, and no borrow travels through a
+// scalar register.  nq comes from negated(), which keeps the compiler from turning the sum
+// back into a difference.
+__device__ __forceinline__ uint64_t negated(uint64_t q)
 {
-    return x * t.w - __umul64hi(x, t.ws) * q;
+    uint64_t nq = 0 - q;
+    asm volatile("" : "+s"(nq));
+    return nq;
+}
+__device__ __forceinline__ uint64_t mul_lazy(uint64_t x, const Twiddle &t, uint64_t nq)
+{
+    return x * t.w + __umul64hi(x, t.ws) * nq;
+}
+
+// The same product with a quotient estimate from three of the four partial products,
+//   h = x1 w1' + floor(x0 w1' / 2^32) + floor(x1 w0' / 2^32)   (x = x1 2^32 + x0, w' = w1' 2^32 + w0'),
+// which falls short of floor(x w' / 2^64) by at most 2: the result lies in [0, 4q).  Five
+// instructions fewer; for moduli that leave the room (see group_butterflies).
+__device__ __forceinline__ uint64_t mul_loose(uint64_t x, const Twiddle &t, uint64_t nq)
+{
+    const uint32_t x0 = (uint32_t)x, x1 = (uint32_t)(x >> 32);
+    const uint32_t w0 = (uint32_t)t.ws, w1 = (uint32_t)(t.ws >> 32);
+    const uint64_t h = (uint64_t)x1 * w1 + __umulhi(x0, w1) + __umulhi(x1, w0);
+    return x * t.w + h * nq;
+}
+
+// u >= m ? u - m : u  for  m <= 2^63 and u < m + 2^63, given nm = negated(m): decided by the
+// sign of the sum, one 64-bit add and a test of the upper word
+__device__ __forceinline__ uint64_t cond_sub(uint64_t u, uint64_t nm)
+{
+    const uint64_t d = u + nm;
+    return (int32_t)(d >> 32) < 0 ? u : d;
+}
+
+// One modulus as the butterflies use it.
+struct Mod {
+    uint64_t q, two_q;
+    uint64_t nq, n2q;           // 2^64 - q, 2^64 - 2q
+    uint32_t fold_m, fold_k;
+};
+__device__ __forceinline__ Mod make_mod(const RlweLimb &P)
+{
+    return Mod{P.red.q, 2 * P.red.q, negated(P.red.q), negated(2 * P.red.q), P.fold_m, P.fold_k};
+}
+
+// Any 64-bit x -> a value below 2q congruent to it, for 2^34 <= q: the quotient estimate
+//   h = floor(floor(x / 2^32) m / 2^(32+k)),  m = floor(2^(64+k) / q),  k = bitlen(q) - 33 >= 1,
+// falls short of x / q by less than  x / 2^(64+k) + 2^32 / q + 1 <= 2, and never exceeds it.
+__device__ __forceinline__ uint64_t fold(uint64_t x, const Mod &md)
+{
+    const uint32_t h = __umulhi((uint32_t)(x >> 32), md.fold_m) >> md.fold_k;
+    return x + (uint64_t)h * md.nq;
 }
 
 // a, b < q  ->  a b mod q
@@ -149,6 +201,11 @@ struct Group {
     __device__ __forceinline__ explicit Group(int g)
         : i0(g >> LT), base(((g >> LT) << (LOGN - P0)) + (g & ((1 << LT) - 1))) {}
     __device__ __forceinline__ int at(int r) const { return base + (r << LT); }
+    // pad(at(r) - index0) = pad(base - index0) + a constant: r << LT has no bits below LT, the
+    // rest of the index none between LT and LT + S, and index0 and the block's start are
+    // multiples of 2^(LT+S); needs LT >= 4 or LT + S >= 4
+    static constexpr bool kSeparable = LT + S >= 4;
+    static constexpr int padded_step(int r) { return (r << LT) + ((r << LT) >> 4); }
     // table index of entry j (j < 2^st) of stage st
     __device__ __forceinline__ int entry(int st, int j) const { return (1 << (P0 + st)) + (i0 << st) + j; }
 };
@@ -186,13 +243,61 @@ __device__ __forceinline__ RoundTable<S, KIND> load_round_table(const Twiddle *_
     return t;
 }
 
-// the butterflies of one group; F(st, j), I(st, j), Sh(r) hand out the table entries
-template <int S, RoundKind KIND, typename FwdT, typename InvT, typename SecT>
-__device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], uint64_t q, FwdT F, InvT I,
+// Two ways of keeping the values inside 64 bits.
+//
+// Any modulus below 2^62 (LAZY = false): forward values stay below 4q (one conditional
+// subtraction of 2q per butterfly), inverse values below 2q (one per sum).
+//
+// Moduli from 2^34 to 2^58 (LAZY = true) leave room for kLazyUnits = 64 multiples of q in a word.
+// Then the products take the cheaper quotient estimate of mul_loose() (below 4q instead of 2q)
+// and the conditional subtractions go:
+//   forward: a value that enters a stage below B q leaves it below (B + 4) q; inputs below 3q
+//            (q, or 3q behind the stage done on the way in) and at most 14 more stages, or q
+//            and 15 stages: below 61q;
+//   inverse: the bound of every register is known when the code is compiled: a product is
+//            below 4q, a sum below the sum of its operands' bounds, u - v is made non-negative
+//            by adding (bound of v) q; the first register of a group of 2^S doubles S times.
+//            At the end of a round the registers whose bound exceeds `tout` are folded below 2q
+//            (five instructions each, fold()); tout is 64 / 2^(stages of the next round), so
+//            that the next round cannot overflow, and 2 in the last round, whose results are
+//            all below 2q.
+constexpr unsigned kLazyUnits = 64;
+constexpr unsigned kLooseUnits = 4;     // bound of mul_loose()
+constexpr unsigned kFoldUnits = 2;      // bound of fold()
+
+// bound (in multiples of q) of the largest register of a group after an inverse round of S
+// stages that starts from `bin` everywhere and folds what exceeds `tout`
+constexpr unsigned inverse_round_out(int S, unsigned bin, unsigned tout)
+{
+    unsigned b[16] = {};
+    const int R = 1 << S;
+    for (int r = 0; r < R; ++r) b[r] = bin;
+    for (int st = S - 1; st >= 0; --st) {
+        const int half = R >> (st + 1);
+        for (int r = 0; r < R; ++r) {
+            if (r & half) continue;
+            b[r] += b[r + half];
+            b[r + half] = kLooseUnits;
+        }
+    }
+    unsigned most = 0;
+    for (int r = 0; r < R; ++r) {
+        const unsigned v = b[r] > tout ? kFoldUnits : b[r];
+        most = v > most ? v : most;
+    }
+    return most;
+}
+
+// the butterflies of one group; F(st, j), I(st, j), Sh(r) hand out the table entries.
+// BIN, TOUT: with LAZY, bound of the registers at the start of the inverse stages, and the
+// bound above which a register is folded after them (both in multiples of q).
+template <int S, RoundKind KIND, bool LAZY, unsigned BIN, unsigned TOUT, typename FwdT, typename InvT,
+          typename SecT>
+__device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], const Mod &md, FwdT F, InvT I,
                                                   SecT Sh)
 {
     constexpr int R = 1 << S;
-    const uint64_t two_q = 2 * q;
+    static_assert(S <= 4, "bounds are tracked for up to 16 registers");
     if constexpr (KIND != kInverse) {
 #pragma unroll
         for (int st = 0; st < S; ++st) {
@@ -201,31 +306,54 @@ __device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], uint64_
             for (int r = 0; r < R; ++r) {
                 if (r & half) continue;
                 const Twiddle t = F(st, r >> (S - st));
-                uint64_t u = x[r];
-                u = u >= two_q ? u - two_q : u;
-                const uint64_t v = mul_lazy(x[r + half], t, q);
+                const uint64_t u = LAZY ? x[r] : cond_sub(x[r], md.n2q);
+                const uint64_t v = LAZY ? mul_loose(x[r + half], t, md.nq) : mul_lazy(x[r + half], t, md.nq);
                 x[r] = u + v;
-                x[r + half] = u - v + two_q;
+                x[r + half] = u + (LAZY ? kLooseUnits * md.q : md.two_q) - v;
             }
         }
     }
     if constexpr (KIND == kMiddle) {
         // bit-reversed position = LDS index: the transformed secret uses the same order
 #pragma unroll
-        for (int r = 0; r < R; ++r) x[r] = mul_lazy(x[r], Sh(r), q);
+        for (int r = 0; r < R; ++r)
+            x[r] = LAZY ? mul_loose(x[r], Sh(r), md.nq) : mul_lazy(x[r], Sh(r), md.nq);
     }
     if constexpr (KIND != kForward) {
+        if constexpr (LAZY) {
+            static_assert(((KIND == kMiddle ? kLooseUnits : BIN) << S) <= kLazyUnits, "inverse round overflows");
+            unsigned b[R];          // folded away: every index below is a constant after unrolling
 #pragma unroll
-        for (int st = S - 1; st >= 0; --st) {
-            const int half = R >> (st + 1);
+            for (int r = 0; r < R; ++r) b[r] = KIND == kMiddle ? kLooseUnits : BIN;
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (r & half) continue;
-                const Twiddle t = I(st, r >> (S - st));
-                const uint64_t u = x[r], v = x[r + half];
-                const uint64_t sum = u + v;
-                x[r] = sum >= two_q ? sum - two_q : sum;
-                x[r + half] = mul_lazy(u - v + two_q, t, q);
+            for (int st = S - 1; st >= 0; --st) {
+                const int half = R >> (st + 1);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (r & half) continue;
+                    const Twiddle t = I(st, r >> (S - st));
+                    const uint64_t u = x[r], v = x[r + half];
+                    x[r] = u + v;
+                    x[r + half] = mul_loose(u + b[r + half] * md.q - v, t, md.nq);
+                    b[r] += b[r + half];
+                    b[r + half] = kLooseUnits;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (b[r] > TOUT) x[r] = fold(x[r], md);
+        } else {
+#pragma unroll
+            for (int st = S - 1; st >= 0; --st) {
+                const int half = R >> (st + 1);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (r & half) continue;
+                    const Twiddle t = I(st, r >> (S - st));
+                    const uint64_t u = x[r], v = x[r + half];
+                    x[r] = cond_sub(u + v, md.n2q);
+                    x[r + half] = mul_lazy(u + md.two_q - v, t, md.nq);
+                }
             }
         }
     }
@@ -247,46 +375,70 @@ __device__ __forceinline__ Part part_of(int h)
     return Part{h * (((1 << LOGN) >> S) >> PRE), h << (LOGN - PRE)};
 }
 
+// Where a round's coefficients come from and go to.  The first and the last round of a product
+// (stages from 0, one group per thread) use the very coefficients a thread loads from and
+// stores to memory in coalesced order (group g: g + r * threads), so they can take them from
+// and leave them in registers `xio` instead of the LDS.
+enum RoundIo { kLdsToLds, kRegsToLds, kLdsToRegs };
+
 // a round with the table entries read from memory inside it (any number of groups per thread)
-template <int LOGN, int PRE, int P0, int S, RoundKind KIND, int NT>
+template <int LOGN, int PRE, int P0, int S, RoundKind KIND, int NT, bool LAZY = false, unsigned BIN = 2,
+          unsigned TOUT = 2, RoundIo IO = kLdsToLds>
 __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restrict__ fwd,
                                           const Twiddle *__restrict__ inv,
-                                          const Twiddle *__restrict__ shat, uint64_t q, int tid,
-                                          int h)
+                                          const Twiddle *__restrict__ shat, const Mod &md, int tid,
+                                          int h, uint64_t *xio = nullptr)
 {
     using Grp = Group<LOGN, P0, S>;
+    static_assert(IO == kLdsToLds || (PRE == 0 && P0 == 0 && Grp::G == NT), "one group per thread");
     const Part part = part_of<LOGN, PRE, S>(h);
     for (int g = tid; g < (Grp::G >> PRE); g += NT) {
         const Grp grp(part.group0 + g);
         uint64_t x[Grp::R];
+        const int p0 = pad(grp.base - part.index0);
+        auto slot = [&](int r) {
+            return Grp::kSeparable ? p0 + Grp::padded_step(r) : pad(grp.at(r) - part.index0);
+        };
 #pragma unroll
-        for (int r = 0; r < Grp::R; ++r) x[r] = lds[pad(grp.at(r) - part.index0)];
-        group_butterflies<S, KIND>(
-            x, q, [&](int st, int j) { return fwd[grp.entry(st, j)]; },
+        for (int r = 0; r < Grp::R; ++r) x[r] = IO == kRegsToLds ? xio[r] : lds[slot(r)];
+        group_butterflies<S, KIND, LAZY, BIN, TOUT>(
+            x, md, [&](int st, int j) { return fwd[grp.entry(st, j)]; },
             [&](int st, int j) { return inv[grp.entry(st, j)]; },
             [&](int r) { return shat[grp.at(r)]; });
 #pragma unroll
-        for (int r = 0; r < Grp::R; ++r) lds[pad(grp.at(r) - part.index0)] = x[r];
+        for (int r = 0; r < Grp::R; ++r) {
+            if constexpr (IO == kLdsToRegs) xio[r] = x[r];
+            else lds[slot(r)] = x[r];
+        }
     }
 }
 
 // a round of at most one group per thread with the table entries already in registers
-template <int LOGN, int PRE, int P0, int S, RoundKind KIND>
+template <int LOGN, int PRE, int P0, int S, RoundKind KIND, bool LAZY, unsigned BIN, unsigned TOUT,
+          RoundIo IO = kLdsToLds>
 __device__ __forceinline__ void ntt_round_preloaded(uint64_t *lds, const RoundTable<S, KIND> &t,
-                                                    uint64_t q, int tid, int h)
+                                                    const Mod &md, int tid, int h,
+                                                    uint64_t *xio = nullptr)
 {
     using Grp = Group<LOGN, P0, S>;
     if (tid >= (Grp::G >> PRE)) return;
     const Part part = part_of<LOGN, PRE, S>(h);
     const Grp grp(part.group0 + tid);
     uint64_t x[Grp::R];
+    const int p0 = pad(grp.base - part.index0);
+    auto slot = [&](int r) {
+        return Grp::kSeparable ? p0 + Grp::padded_step(r) : pad(grp.at(r) - part.index0);
+    };
 #pragma unroll
-    for (int r = 0; r < Grp::R; ++r) x[r] = lds[pad(grp.at(r) - part.index0)];
-    group_butterflies<S, KIND>(
-        x, q, [&](int st, int j) { return t.f[(1 << st) - 1 + j]; },
+    for (int r = 0; r < Grp::R; ++r) x[r] = IO == kRegsToLds ? xio[r] : lds[slot(r)];
+    group_butterflies<S, KIND, LAZY, BIN, TOUT>(
+        x, md, [&](int st, int j) { return t.f[(1 << st) - 1 + j]; },
         [&](int st, int j) { return t.i[(1 << st) - 1 + j]; }, [&](int r) { return t.s[r]; });
 #pragma unroll
-    for (int r = 0; r < Grp::R; ++r) lds[pad(grp.at(r) - part.index0)] = x[r];
+    for (int r = 0; r < Grp::R; ++r) {
+        if constexpr (IO == kLdsToRegs) xio[r] = x[r];
+        else lds[slot(r)] = x[r];
+    }
 }
 
 // The rounds of a product by the secret over the stages PRE .. LOGN-1, in order: forward
@@ -296,17 +448,33 @@ template <int LOGN, int PRE, int MAXS, int IDX>
 struct RoundOf {
     static constexpr int F = rounds_for(LOGN - PRE, MAXS);
     static constexpr int TOTAL = 2 * F - 1;
-    static constexpr int J = IDX < F ? IDX : 2 * F - 2 - IDX;       // forward round it mirrors
+    static constexpr int mirror(int idx) { return idx < F ? idx : 2 * F - 2 - idx; }   // forward round
     static constexpr int start_of(int j)
     {
         int p = PRE;
         for (int i = 0; i < j; ++i) p += round_stages(LOGN - p, MAXS);
         return p;
     }
+    static constexpr int stages_of(int idx) { return round_stages(LOGN - start_of(mirror(idx)), MAXS); }
+    static constexpr int J = mirror(IDX);
     static constexpr int P0 = start_of(J);
-    static constexpr int S = round_stages(LOGN - P0, MAXS);
+    static constexpr int S = stages_of(IDX);
     static constexpr RoundKind KIND = IDX == F - 1 ? kMiddle : (IDX < F ? kForward : kInverse);
     static constexpr int G = ((1 << LOGN) >> S) >> PRE;             // groups of one part
+    // Lazy bounds of the rounds with inverse stages (idx >= F - 1), in multiples of q: what a
+    // round folds behind its stages, and what its registers start from.
+    static constexpr unsigned tout_of(int idx)
+    {
+        return idx + 1 < TOTAL ? kLazyUnits >> stages_of(idx + 1) : kFoldUnits;
+    }
+    static constexpr unsigned bin_of(int idx)
+    {
+        unsigned b = kLooseUnits;                                   // behind the pointwise product
+        for (int i = F - 1; i < idx; ++i) b = inverse_round_out(stages_of(i), b, tout_of(i));
+        return b;
+    }
+    static constexpr unsigned TOUT = IDX >= F - 1 ? tout_of(IDX) : 2u;
+    static constexpr unsigned BIN = IDX >= F - 1 ? bin_of(IDX) : 2u;
 };
 
 struct NoTable {};
@@ -329,64 +497,91 @@ constexpr bool preload_round()
            Rd::S <= 2 && Rd::G <= NT;
 }
 
+// The first and the last round can work from and to registers (see RoundIo) when the first
+// round has one group per thread and there are rounds between them.
+template <int LOGN, int PRE, int MAXS, int NT>
+constexpr bool direct_ends()
+{
+    using First = RoundOf<LOGN, PRE, MAXS, 0>;
+    return PRE == 0 && First::G == NT && First::TOTAL >= 3;
+}
+
 // Round IDX and everything after it.  Where preload_round() says so, the next round's table
 // entries are asked for before the barrier between the two rounds.
-template <int LOGN, int PRE, int MAXS, int IDX, int NT, typename Table>
+// `before_last()` runs in front of the last round: the caller asks there for what it needs from
+// memory behind the product, and the round hides the latency.
+// DIRECT: round 0 takes its coefficients from xio, the last round leaves its own there (below
+// 2q) and no barrier follows it.
+template <int LOGN, int PRE, int MAXS, bool LAZY, bool DIRECT, int IDX, int NT, typename Table,
+          typename Hook>
 __device__ __forceinline__ void rounds_from(uint64_t *lds, const Twiddle *fwd, const Twiddle *inv,
-                                            const Twiddle *shat, uint64_t q, int tid, int h,
-                                            const Table &mine)
+                                            const Twiddle *shat, const Mod &md, int tid, int h,
+                                            const Table &mine, Hook before_last, uint64_t *xio)
 {
     using Me = RoundOf<LOGN, PRE, MAXS, IDX>;
+    constexpr RoundIo IO = !DIRECT ? kLdsToLds
+                                   : (IDX == 0 ? kRegsToLds : (IDX == Me::TOTAL - 1 ? kLdsToRegs : kLdsToLds));
+    if constexpr (IDX == Me::TOTAL - 1) before_last();
     if constexpr (preload_round<LOGN, PRE, MAXS, IDX, NT>())
-        ntt_round_preloaded<LOGN, PRE, Me::P0, Me::S, Me::KIND>(lds, mine, q, tid, h);
+        ntt_round_preloaded<LOGN, PRE, Me::P0, Me::S, Me::KIND, LAZY, Me::BIN, Me::TOUT, IO>(lds, mine, md, tid,
+                                                                                           h, xio);
     else
-        ntt_round<LOGN, PRE, Me::P0, Me::S, Me::KIND, NT>(lds, fwd, inv, shat, q, tid, h);
+        ntt_round<LOGN, PRE, Me::P0, Me::S, Me::KIND, NT, LAZY, Me::BIN, Me::TOUT, IO>(lds, fwd, inv, shat,
+                                                                                     md, tid, h, xio);
     if constexpr (IDX + 1 < Me::TOTAL) {
         using Next = RoundOf<LOGN, PRE, MAXS, IDX + 1>;
         if constexpr (preload_round<LOGN, PRE, MAXS, IDX + 1, NT>()) {
             const int g = tid < Next::G ? tid : Next::G - 1;        // idle threads: any valid group
             const auto next = load_round_table<LOGN, Next::P0, Next::S, Next::KIND>(fwd, inv, shat, g);
             __syncthreads();
-            rounds_from<LOGN, PRE, MAXS, IDX + 1, NT>(lds, fwd, inv, shat, q, tid, h, next);
+            rounds_from<LOGN, PRE, MAXS, LAZY, DIRECT, IDX + 1, NT>(lds, fwd, inv, shat, md, tid, h, next,
+                                                                    before_last, xio);
         } else {
             __syncthreads();
-            rounds_from<LOGN, PRE, MAXS, IDX + 1, NT>(lds, fwd, inv, shat, q, tid, h, NoTable{});
+            rounds_from<LOGN, PRE, MAXS, LAZY, DIRECT, IDX + 1, NT>(lds, fwd, inv, shat, md, tid, h,
+                                                                    NoTable{}, before_last, xio);
         }
-    } else {
+    } else if constexpr (!DIRECT) {
         __syncthreads();
     }
 }
 
-// The part in the LDS times the secret (stages PRE .. LOGN-1 and back); ends with a barrier.
-// The caller has not yet passed the barrier behind its own writes to the LDS: the first
-// round's table entries are asked for in front of it.
-template <int LOGN, int PRE, int MAXS, int NT>
+// The part times the secret (stages PRE .. LOGN-1 and back).
+// Not DIRECT: the part is in the LDS and the caller has not yet passed the barrier behind its
+// own writes (the first round's table entries are asked for in front of it); ends with a
+// barrier, values below 2q in the LDS.
+// DIRECT: thread `tid` brings coefficient tid + i NT in xio[i] and finds the product there
+// afterwards, below 2q.
+template <int LOGN, int PRE, int MAXS, bool LAZY, bool DIRECT, int NT, typename Hook>
 __device__ __forceinline__ void multiply_by_secret(uint64_t *lds, const Twiddle *fwd,
                                                    const Twiddle *inv, const Twiddle *shat,
-                                                   uint64_t q, int tid, int h)
+                                                   const Mod &md, int tid, int h, Hook before_last,
+                                                   uint64_t *xio)
 {
     using First = RoundOf<LOGN, PRE, MAXS, 0>;
     if constexpr (preload_round<LOGN, PRE, MAXS, 0, NT>()) {
         const int g = tid < First::G ? tid : First::G - 1;
         const auto first = load_round_table<LOGN, First::P0, First::S, First::KIND>(fwd, inv, shat, g);
-        __syncthreads();
-        rounds_from<LOGN, PRE, MAXS, 0, NT>(lds, fwd, inv, shat, q, tid, h, first);
+        if constexpr (!DIRECT) __syncthreads();
+        rounds_from<LOGN, PRE, MAXS, LAZY, DIRECT, 0, NT>(lds, fwd, inv, shat, md, tid, h, first,
+                                                          before_last, xio);
     } else {
-        __syncthreads();
-        rounds_from<LOGN, PRE, MAXS, 0, NT>(lds, fwd, inv, shat, q, tid, h, NoTable{});
+        if constexpr (!DIRECT) __syncthreads();
+        rounds_from<LOGN, PRE, MAXS, LAZY, DIRECT, 0, NT>(lds, fwd, inv, shat, md, tid, h, NoTable{},
+                                                          before_last, xio);
     }
 }
 
 // forward stages P0 .. LOGN-1 of the part in the LDS; ends with a barrier
 template <int LOGN, int PRE, int MAXS, int P0, int NT>
-__device__ __forceinline__ void forward_only(uint64_t *lds, const Twiddle *fwd, uint64_t q, int tid,
+__device__ __forceinline__ void forward_only(uint64_t *lds, const Twiddle *fwd, const Mod &md, int tid,
                                              int h)
 {
     if constexpr (P0 < LOGN) {
         constexpr int S = round_stages(LOGN - P0, MAXS);
-        ntt_round<LOGN, PRE, P0, S, kForward, NT>(lds, fwd, nullptr, nullptr, q, tid, h);
+        ntt_round<LOGN, PRE, P0, S, kForward, NT>(lds, fwd, nullptr, nullptr, md, tid, h);
         __syncthreads();
-        forward_only<LOGN, PRE, MAXS, P0 + S, NT>(lds, fwd, q, tid, h);
+        forward_only<LOGN, PRE, MAXS, P0 + S, NT>(lds, fwd, md, tid, h);
     }
 }
 
@@ -397,12 +592,12 @@ __device__ __forceinline__ void forward_only(uint64_t *lds, const Twiddle *fwd, 
 // the first PRE (0 or 1) forward stages on a pair (u, v) of coefficients N/2 apart: what part h
 // of the ring starts from.  u, v < q; result below 3q.
 template <int PRE>
-__device__ __forceinline__ uint64_t enter_part(uint64_t u, uint64_t v, const Twiddle &w0, uint64_t q,
+__device__ __forceinline__ uint64_t enter_part(uint64_t u, uint64_t v, const Twiddle &w0, const Mod &md,
                                                int h)
 {
     static_assert(PRE == 1, "one stage ahead of the parts");
-    const uint64_t wv = mul_lazy(v, w0, q);                 // [0, 2q)
-    return h == 0 ? u + wv : u + 2 * q - wv;
+    const uint64_t wv = mul_lazy(v, w0, md.nq);             // [0, 2q)
+    return h == 0 ? u + wv : u + md.two_q - wv;
 }
 
 template <int LOGN, int PRE>
@@ -414,6 +609,7 @@ __global__ __launch_bounds__(threads_for(LOGN - PRE, 4)) void rlwe_secret_kernel
     const int tid = threadIdx.x, l = blockIdx.x >> PRE, h = blockIdx.x & ((1 << PRE) - 1);
     const RlweLimb &P = a.limb[l];
     const uint64_t q = P.red.q;
+    const Mod md = make_mod(P);
     Twiddle *const t = tables + (size_t)l * limb_table_entries(N);
     auto lifted = [&](int c) -> uint64_t {
         const int v = s[c];
@@ -424,10 +620,10 @@ __global__ __launch_bounds__(threads_for(LOGN - PRE, 4)) void rlwe_secret_kernel
     } else {
         const Twiddle w0 = t[1];                            // stage 0 has one block: entry 1
         for (int c = tid; c < NP; c += NT)
-            lds[pad(c)] = enter_part<PRE>(lifted(c), lifted(c + NP), w0, q, h);
+            lds[pad(c)] = enter_part<PRE>(lifted(c), lifted(c + NP), w0, md, h);
     }
     __syncthreads();
-    forward_only<LOGN, PRE, 4, PRE, NT>(lds, t, q, tid, h);
+    forward_only<LOGN, PRE, 4, PRE, NT>(lds, t, md, tid, h);
     for (int c = tid; c < NP; c += NT) {
         uint64_t v = lds[pad(c)];               // [0, 4q)
         v = v >= 2 * q ? v - 2 * q : v;
@@ -462,15 +658,17 @@ __device__ __forceinline__ uint64_t finish_phase(uint64_t as, uint64_t c0, uint6
 }
 
 // Eq. (2) with chunking: coefficient c of chunk ch is column ch N + c, zero past n
-__device__ __forceinline__ uint64_t finish_encrypt(uint64_t as, const PolyArgs &a, const RlweLimb &P,
-                                                   uint32_t row, uint32_t c, int N)
+__device__ __forceinline__ uint64_t encrypt_weight(const PolyArgs &a, uint32_t row, uint32_t c, int N)
 {
-    const uint64_t q = P.red.q;
     const uint32_t i = row / (uint32_t)a.Ch, ch = row % (uint32_t)a.Ch;
     const uint32_t col = ch * (uint32_t)N + c;
-    const uint64_t w = col < (uint32_t)a.n ? a.W[(size_t)i * a.n + col] : 0;
+    return col < (uint32_t)a.n ? a.W[(size_t)i * a.n + col] : 0;
+}
+// c0 = Delta w + e - a s  for the weight w and the error ev of the coefficient, as < q
+__device__ __forceinline__ uint64_t finish_encrypt(uint64_t as, uint64_t w, int ev, const RlweLimb &P)
+{
+    const uint64_t q = P.red.q;
     uint64_t v = barrett128(__umul64hi(P.delta, w), P.delta * w, P.red);       // w < t < q
-    const int ev = a.e[(size_t)row * N + c];
     v += ev < 0 ? q - (uint64_t)(-ev) : (uint64_t)ev;
     v += q - as;                                // < 3q
     v = v >= q ? v - q : v;
@@ -482,7 +680,8 @@ __device__ __forceinline__ uint64_t finish_encrypt(uint64_t as, const PolyArgs &
 // stages 1 .. LOGN-1 and back in the LDS, and leaves its half of the not yet joined product
 // where the result will be (phi, or the c0 half of the ciphertext); rlwe_join_kernel does
 // the last inverse stage and what follows.
-template <int LOGN, int PRE, int MAXS, bool ENCRYPT>
+// LAZY: every modulus of the call lies in [2^34, 2^58) (see group_butterflies).
+template <int LOGN, int PRE, int MAXS, bool ENCRYPT, bool LAZY>
 __global__ __launch_bounds__(threads_for(LOGN - PRE, MAXS)) void rlwe_poly_kernel(PolyArgs a)
 {
     constexpr int N = 1 << LOGN, NP = N >> PRE, NT = threads_for(LOGN - PRE, MAXS);
@@ -493,6 +692,7 @@ __global__ __launch_bounds__(threads_for(LOGN - PRE, MAXS)) void rlwe_poly_kerne
     const uint32_t row = poly / (uint32_t)a.L, l = poly % (uint32_t)a.L;
     const RlweLimb &P = a.limbs.limb[l];
     const uint64_t q = P.red.q;
+    const Mod md = make_mod(P);
     const Twiddle *const t = a.tables + (size_t)l * limb_table_entries(N);
     // the polynomial that is multiplied by s
     const uint64_t *const mul_in =
@@ -503,30 +703,67 @@ __global__ __launch_bounds__(threads_for(LOGN - PRE, MAXS)) void rlwe_poly_kerne
                                   : a.dst + ((size_t)row * a.L + l) * N;
     // c1 = a is copied while a is on its way into the LDS (one read of a in all)
     uint64_t *const c1 = a.dst + (((size_t)row * 2 + 1) * a.L + l) * N;
+    // Coefficient mine(i) of the part is this thread's on the way in and on the way out.  All
+    // the loads of a pass are issued before the first of them is waited for.
+    constexpr int IT = (NP + NT - 1) / NT;
+    constexpr bool kRagged = NP % NT != 0;          // rings below the 64 threads of a wave
+    constexpr bool DIRECT = direct_ends<LOGN, PRE, MAXS, NT>();
+    auto mine = [&](int i) { return tid + i * NT; };
+    auto have = [&](int i) { return !kRagged || mine(i) < NP; };
+    uint64_t x[IT];                                 // DIRECT: in and out of the product
     if constexpr (PRE == 0) {
-        for (int c = tid; c < N; c += NT) {
-            const uint64_t v = mul_in[c];
-            lds[pad(c)] = v;
-            if constexpr (ENCRYPT) c1[c] = v;
+#pragma unroll
+        for (int i = 0; i < IT; ++i) x[i] = have(i) ? mul_in[mine(i)] : 0;
+#pragma unroll
+        for (int i = 0; i < IT; ++i) {
+            if (!have(i)) continue;
+            if constexpr (!DIRECT) lds[pad(mine(i))] = x[i];
+            if constexpr (ENCRYPT) c1[mine(i)] = x[i];
         }
     } else {
         const Twiddle w0 = t[1];
-        for (int c = tid; c < NP; c += NT) {
-            const uint64_t u = mul_in[c], v = mul_in[c + NP];
-            lds[pad(c)] = enter_part<PRE>(u, v, w0, q, h);
-            if constexpr (ENCRYPT) c1[h * NP + c] = h == 0 ? u : v;
+        uint64_t v[IT];
+#pragma unroll
+        for (int i = 0; i < IT; ++i) {
+            x[i] = have(i) ? mul_in[mine(i)] : 0;
+            v[i] = have(i) ? mul_in[mine(i) + NP] : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < IT; ++i) {
+            if (!have(i)) continue;
+            lds[pad(mine(i))] = enter_part<PRE>(x[i], v[i], w0, md, h);
+            if constexpr (ENCRYPT) c1[h * NP + mine(i)] = h == 0 ? x[i] : v[i];
         }
     }
-    multiply_by_secret<LOGN, PRE, MAXS, NT>(lds, t, t + N, t + 2 * N, q, tid, h);
-    for (int c = tid; c < NP; c += NT) {
-        uint64_t as = lds[pad(c)];              // [0, 2q)
-        as = as >= q ? as - q : as;
+    // what is added to the product: c0 (phase), or the weight and the error (encryption);
+    // asked for in front of the last round
+    uint64_t addend[IT];
+    int err[IT];
+    auto before_last = [&]() {
+        if constexpr (PRE == 0) {
+#pragma unroll
+            for (int i = 0; i < IT; ++i) {
+                if constexpr (ENCRYPT) {
+                    addend[i] = have(i) ? encrypt_weight(a, row, (uint32_t)mine(i), N) : 0;
+                    err[i] = have(i) ? a.e[(size_t)row * N + mine(i)] : 0;
+                } else {
+                    addend[i] = have(i) ? a.src[(((size_t)row * 2 + 0) * a.L + l) * N + mine(i)] : 0;
+                }
+            }
+        }
+    };
+    multiply_by_secret<LOGN, PRE, MAXS, LAZY, DIRECT, NT>(lds, t, t + N, t + 2 * N, md, tid, h, before_last,
+                                                          x);
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+        if (!have(i)) continue;
+        const uint64_t as = cond_sub(DIRECT ? x[i] : lds[pad(mine(i))], md.nq);     // [0, 2q) -> [0, q)
         if constexpr (PRE != 0) {
-            out[h * NP + c] = as;
+            out[h * NP + mine(i)] = as;
         } else if constexpr (ENCRYPT) {
-            out[c] = finish_encrypt(as, a, P, row, (uint32_t)c, N);
+            out[mine(i)] = finish_encrypt(as, addend[i], err[i], P);
         } else {
-            out[c] = finish_phase(as, a.src[(((size_t)row * 2 + 0) * a.L + l) * N + c], q);
+            out[mine(i)] = finish_phase(as, addend[i], q);
         }
     }
 }
@@ -550,11 +787,11 @@ __global__ __launch_bounds__(256) void rlwe_join_kernel(PolyArgs a, int logN, ui
     const uint64_t u = out[c], v = out[c + NP];             // < q
     uint64_t lo = u + v;
     lo = lo >= q ? lo - q : lo;
-    uint64_t hi = mul_lazy(u + q - v, w0_inv, q);           // [0, 2q)
+    uint64_t hi = mul_lazy(u + q - v, w0_inv, 0 - q);       // [0, 2q)
     hi = hi >= q ? hi - q : hi;
     if constexpr (ENCRYPT) {
-        out[c] = finish_encrypt(lo, a, P, row, c, N);
-        out[c + NP] = finish_encrypt(hi, a, P, row, c + NP, N);
+        out[c] = finish_encrypt(lo, encrypt_weight(a, row, c, N), a.e[(size_t)row * N + c], P);
+        out[c + NP] = finish_encrypt(hi, encrypt_weight(a, row, c + NP, N), a.e[(size_t)row * N + c + NP], P);
     } else {
         const uint64_t *const c0 = a.src + (((size_t)row * 2 + 0) * a.L + l) * N;
         out[c] = finish_phase(lo, c0[c], q);
@@ -796,6 +1033,10 @@ static int rlwe_check(int N, int L, const uint64_t *moduli, RlweArgs *out)
         P.s1 = (uint32_t)(b - 1);
         P.mu = (uint64_t)((((u128)1) << (b + 63)) / q);
         P.pad = 0;
+        if (b >= 35) {                  // fold(): only the kernels for moduli from 2^34 use it
+            a.limb[l].fold_k = (uint32_t)(b - 33);
+            a.limb[l].fold_m = (uint32_t)((((u128)1) << (64 + (b - 33))) / q);
+        }
     }
     if (N > (1 << kRlweMaxLogN)) return NIMBUS_COP_ERR_UNSUPPORTED;
     *out = a;
@@ -903,10 +1144,20 @@ static hipError_t launch_secret(const RlweArgs &a, int logN, int L, const int8_t
                                       dim3(threads_for(LOGN, 4)), stream, a, s, tables));
 }
 
-template <bool ENCRYPT, int MAXS>
+// every modulus in [2^34, 2^58): the kernels without conditional subtractions apply
+static bool lazy_moduli(const PolyArgs &a)
+{
+    for (int l = 0; l < a.L; ++l) {
+        const uint64_t q = a.limbs.limb[l].red.q;
+        if (q < (1ull << 34) || q >= (1ull << 58)) return false;
+    }
+    return true;
+}
+
+template <bool ENCRYPT, int MAXS, bool LAZY>
 static hipError_t launch_poly_with(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
 {
-    NIMBUS_RLWE_DISPATCH(logN, launch(rlwe_poly_kernel<LOGN, 0, MAXS, ENCRYPT>, dim3((unsigned)polys),
+    NIMBUS_RLWE_DISPATCH(logN, launch(rlwe_poly_kernel<LOGN, 0, MAXS, ENCRYPT, LAZY>, dim3((unsigned)polys),
                                       dim3(threads_for(LOGN, MAXS)), stream, a));
 }
 
@@ -914,7 +1165,10 @@ static hipError_t launch_poly_with(const PolyArgs &a, int logN, size_t polys, hi
 template <bool ENCRYPT>
 static hipError_t launch_poly_in_parts(const PolyArgs &a, size_t polys, hipStream_t stream)
 {
-    const hipError_t e = launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT>, dim3(2u * (unsigned)polys),
+    const hipError_t e =
+        lazy_moduli(a) ? launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT, true>, dim3(2u * (unsigned)polys),
+                                dim3(threads_for(14, 4)), stream, a)
+                       : launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT, false>, dim3(2u * (unsigned)polys),
                                 dim3(threads_for(14, 4)), stream, a);
     if (e != hipSuccess) return e;
     const uint64_t pairs = (uint64_t)polys << 14;
@@ -932,9 +1186,14 @@ static hipError_t launch_poly(const PolyArgs &a, int logN, size_t polys, hipStre
 {
     if (logN == 15) return launch_poly_in_parts<ENCRYPT>(a, polys, stream);
     const int maxs = polys >= 1024 ? stages_large_batch(logN) : stages_small_batch(logN);
-    if (maxs == 4) return launch_poly_with<ENCRYPT, 4>(a, logN, polys, stream);
-    if (maxs == 3) return launch_poly_with<ENCRYPT, 3>(a, logN, polys, stream);
-    return launch_poly_with<ENCRYPT, 2>(a, logN, polys, stream);
+    if (lazy_moduli(a)) {
+        if (maxs == 4) return launch_poly_with<ENCRYPT, 4, true>(a, logN, polys, stream);
+        if (maxs == 3) return launch_poly_with<ENCRYPT, 3, true>(a, logN, polys, stream);
+        return launch_poly_with<ENCRYPT, 2, true>(a, logN, polys, stream);
+    }
+    if (maxs == 4) return launch_poly_with<ENCRYPT, 4, false>(a, logN, polys, stream);
+    if (maxs == 3) return launch_poly_with<ENCRYPT, 3, false>(a, logN, polys, stream);
+    return launch_poly_with<ENCRYPT, 2, false>(a, logN, polys, stream);
 }
 
 }  // namespace nimbus

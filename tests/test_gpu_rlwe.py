@@ -79,6 +79,16 @@ PHASE_SHAPES = [
     (1024, 1, 50, 1100),     # config 1 ring in a large batch: 2 stages per round
     (32768, 2, 54, 2),       # ring that does not fit the LDS: two halves and a joining pass
     (32768, 1, 62, 3),
+    # moduli from 2^34 to 2^58 take the kernels without conditional subtractions: both ends of
+    # that range, and the first moduli outside it on either side, at the longest transforms
+    (1024, 1, 35, 8),        # smallest moduli of the range
+    (1024, 1, 34, 8),        # just below it
+    (2048, 2, 59, 3),        # just above it
+    (4096, 2, 58, 512),      # largest moduli of the range: least room, 4 + 4 + 4
+    (8192, 2, 58, 3),        # 3 + 3 + 3 + 2 + 2
+    (16384, 1, 58, 2),       # 14 stages
+    (16384, 2, 58, 520),     # two groups per thread and round
+    (32768, 1, 58, 2),       # a stage on the way in, 14 in the LDS
 ]
 
 
@@ -122,11 +132,12 @@ def test_phase_with_degenerate_secrets(oracle, kind):
         assert np.array_equal(got, ct[:, 0])
 
 
-def test_phase_with_extreme_residues(oracle):
+@pytest.mark.parametrize("N,q_bits", [(1024, 62), (1024, 58), (16384, 58), (32768, 58)])
+def test_phase_with_extreme_residues(oracle, N, q_bits):
     """c1 = q - 1 everywhere and c1 = 0 everywhere: the lazy ranges of the transform at their
-    ends"""
-    N, L = 1024, 2
-    moduli = _primes(62, 16, N, L)
+    ends, for the widest moduli of either kind of kernel"""
+    L = 2
+    moduli = _primes(q_bits, 16, N, L)
     s = ci.gen_secret(5, N)
     ct = np.zeros((2, 2, L, N), dtype=np.uint64)
     for l, q in enumerate(moduli):
