@@ -56,7 +56,9 @@ extern "C" {
 #endif
 
 /* Size in bytes of the per-key table buffer for ring degree N and L limbs (transform
- * constants and the transformed secret, per limb); 0 for arguments out of range. */
+ * constants and the transformed secret, per limb, three times over: in their natural order and
+ * in the two orders in which the kernels for large and for small batches read them;
+ * 144 N L bytes); 0 for arguments out of range. */
 size_t nimbus_rlwe_tables_bytes(int N, int L);
 
 /* KeyGen side of Appendix B.1, once per secret key: fills `tables` (at least

@@ -21,11 +21,21 @@
 // A round keeps 2^S coefficients of a thread in registers for S <= 4 consecutive stages;
 // between rounds the coefficients go through the LDS.  The last forward round, the
 // pointwise product and the first inverse round work on the same coefficients of the same
-// thread and are one round.
+// thread and are one round.  The first round takes its coefficients straight from the
+// coalesced loads and the last one hands its own to the stores (one group per thread: the
+// same coefficients), and rounds that keep every wave inside its own coefficients follow
+// each other without a workgroup barrier.
 //
-// Arithmetic: moduli below 2^62, values kept lazily in [0, 4q) (forward) and [0, 2q)
-// (inverse); a product by a table constant w uses its companion floor(w 2^64 / q):
+// Arithmetic: a product by a table constant w uses its companion w' = floor(w 2^64 / q):
 //   x w - floor(x w' / 2^64) q  lies in [0, 2q) for every 64-bit x.
+// Moduli below 2^62: values kept lazily in [0, 4q) (forward) and [0, 2q) (inverse) by one
+// conditional subtraction per butterfly.  Moduli from 2^34 to 2^58 (every parameter set of
+// the benchmark configurations): no conditional subtractions, bounds tracked at compile time
+// instead, and a cheaper quotient estimate; see group_butterflies.
+//
+// Tables: the constants of a transform are read once per polynomial from the second-level
+// cache; they are stored a second and third time in the order in which the threads of the
+// product kernels read them (neighbouring lanes, neighbouring entries; see power_slot()).
 #include "cop_common.hpp"
 #include "../../include/nimbus_cop.h"
 #include "../../include/nimbus_rlwe.h"
@@ -42,8 +52,13 @@ struct Twiddle {
     uint64_t ws;    // floor(w * 2^64 / q)
 };
 
-// per limb: forward powers | inverse powers | transformed secret (times 1/N), N entries each
-__host__ __device__ inline size_t limb_table_entries(int N) { return (size_t)3 * (size_t)N; }
+// Per limb three sets of  forward powers | inverse powers | transformed secret (times 1/N),
+// N entries each: set 0 in the natural order (bit-reversed powers, secret by coefficient), sets
+// 1 and 2 the same entries in the order in which the product kernels for large and for small
+// batches read them (see table_slot()).
+constexpr int kTableSets = 3;
+__host__ __device__ inline size_t set_entries(int N) { return (size_t)3 * (size_t)N; }
+__host__ __device__ inline size_t limb_table_entries(int N) { return kTableSets * set_entries(N); }
 
 struct RlweLimb {
     Limb red;           // constants of the one-shot reduction of a 128-bit value
@@ -182,6 +197,32 @@ constexpr int threads_for(int logN, int MAXS)
     const int t = (1 << logN) >> MAXS;
     return t < 64 ? 64 : (t > 1024 ? 1024 : t);
 }
+// Order of the table entries a product kernel reads.  A thread of a round over the stages
+// P0 .. P0+S-1 handles block i0 of stage P0 and needs, of stage P0+st, the 2^st entries
+// (i0 << st) + j: in the natural order the threads of a wave read with a stride of 2^st entries,
+// and the late stages cost a cache line per lane.  The kernels' sets hold the entries of such a
+// stage as  (j << P0) + i0  instead: the lanes of a wave read neighbours.  Likewise the
+// transformed secret of the round in the middle, coefficient (g << S) + r of group g, sits
+// at (r << (logN - S)) + g.  The stages below `pre` (done outside the rounds) keep their place.
+__host__ __device__ inline int power_slot(int logN, int pre, int maxs, int e)
+{
+    if (e < (1 << pre) || e < 1) return e;
+    int s = 0;
+    while ((2 << s) <= e) ++s;                      // stage of entry e: 2^s <= e < 2^(s+1)
+    int p0 = pre;
+    while (p0 + round_stages(logN - p0, maxs) <= s) p0 += round_stages(logN - p0, maxs);
+    const int st = s - p0, b = e - (1 << s);
+    const int i0 = b >> st, j = b & ((1 << st) - 1);
+    return (1 << s) + (j << p0) + i0;
+}
+__host__ __device__ inline int secret_slot(int logN, int pre, int maxs, int c)
+{
+    int p0 = pre;
+    while (p0 + round_stages(logN - p0, maxs) < logN) p0 += round_stages(logN - p0, maxs);
+    const int S = logN - p0;                        // stages of the round in the middle
+    return ((c & ((1 << S) - 1)) << (logN - S)) + (c >> S);
+}
+
 // LDS index of coefficient i: one word of padding after every 16, so that the strides of
 // 16 and 256 words of the later rounds spread over the banks
 __device__ __forceinline__ int pad(int i) { return i + (i >> 4); }
@@ -206,8 +247,19 @@ struct Group {
     // multiples of 2^(LT+S); needs LT >= 4 or LT + S >= 4
     static constexpr bool kSeparable = LT + S >= 4;
     static constexpr int padded_step(int r) { return (r << LT) + ((r << LT) >> 4); }
-    // table index of entry j (j < 2^st) of stage st
-    __device__ __forceinline__ int entry(int st, int j) const { return (1 << (P0 + st)) + (i0 << st) + j; }
+    // table index of entry j (j < 2^st) of stage st: in the natural order, and in a kernel's set
+    // (power_slot())
+    template <bool OWN_SET>
+    __device__ __forceinline__ int entry(int st, int j) const
+    {
+        return OWN_SET ? (1 << (P0 + st)) + (j << P0) + i0 : (1 << (P0 + st)) + (i0 << st) + j;
+    }
+    // index of the transformed secret for coefficient r of group g (round in the middle: LT = 0)
+    template <bool OWN_SET>
+    __device__ __forceinline__ int secret(int r, int g) const
+    {
+        return OWN_SET ? (r << (LOGN - S)) + g : at(r);
+    }
 };
 
 // The table entries one group needs in one round, in registers: loaded before the barrier
@@ -227,18 +279,19 @@ __device__ __forceinline__ RoundTable<S, KIND> load_round_table(const Twiddle *_
                                                                 const Twiddle *__restrict__ shat,
                                                                 int g)
 {
+    // (only the product kernels ask ahead: the tables are their own set)
     const Group<LOGN, P0, S> grp(g);
     RoundTable<S, KIND> t;
 #pragma unroll
     for (int st = 0; st < S; ++st)
 #pragma unroll
         for (int j = 0; j < (1 << st); ++j) {
-            if constexpr (KIND != kInverse) t.f[(1 << st) - 1 + j] = fwd[grp.entry(st, j)];
-            if constexpr (KIND != kForward) t.i[(1 << st) - 1 + j] = inv[grp.entry(st, j)];
+            if constexpr (KIND != kInverse) t.f[(1 << st) - 1 + j] = fwd[grp.template entry<true>(st, j)];
+            if constexpr (KIND != kForward) t.i[(1 << st) - 1 + j] = inv[grp.template entry<true>(st, j)];
         }
     if constexpr (KIND == kMiddle) {
 #pragma unroll
-        for (int r = 0; r < (1 << S); ++r) t.s[r] = shat[grp.at(r)];
+        for (int r = 0; r < (1 << S); ++r) t.s[r] = shat[grp.template secret<true>(r, g)];
     }
     return t;
 }
@@ -382,8 +435,9 @@ __device__ __forceinline__ Part part_of(int h)
 enum RoundIo { kLdsToLds, kRegsToLds, kLdsToRegs };
 
 // a round with the table entries read from memory inside it (any number of groups per thread)
+// OWN_SET: the tables are the kernel's own set (see power_slot()), else the natural order.
 template <int LOGN, int PRE, int P0, int S, RoundKind KIND, int NT, bool LAZY = false, unsigned BIN = 2,
-          unsigned TOUT = 2, RoundIo IO = kLdsToLds>
+          unsigned TOUT = 2, RoundIo IO = kLdsToLds, bool OWN_SET = false>
 __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restrict__ fwd,
                                           const Twiddle *__restrict__ inv,
                                           const Twiddle *__restrict__ shat, const Mod &md, int tid,
@@ -402,9 +456,9 @@ __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restri
 #pragma unroll
         for (int r = 0; r < Grp::R; ++r) x[r] = IO == kRegsToLds ? xio[r] : lds[slot(r)];
         group_butterflies<S, KIND, LAZY, BIN, TOUT>(
-            x, md, [&](int st, int j) { return fwd[grp.entry(st, j)]; },
-            [&](int st, int j) { return inv[grp.entry(st, j)]; },
-            [&](int r) { return shat[grp.at(r)]; });
+            x, md, [&](int st, int j) { return fwd[grp.template entry<OWN_SET>(st, j)]; },
+            [&](int st, int j) { return inv[grp.template entry<OWN_SET>(st, j)]; },
+            [&](int r) { return shat[grp.template secret<OWN_SET>(r, part.group0 + g)]; });
 #pragma unroll
         for (int r = 0; r < Grp::R; ++r) {
             if constexpr (IO == kLdsToRegs) xio[r] = x[r];
@@ -506,6 +560,31 @@ constexpr bool direct_ends()
     return PRE == 0 && First::G == NT && First::TOTAL >= 3;
 }
 
+// Two consecutive rounds whose groups are 2^S coefficients at a stride of at most 64, one group
+// per thread, keep every wave inside its own 64 * 2^S consecutive coefficients: wave w's 64
+// groups are whole blocks of the round's first stage.  Between such rounds the workgroup need
+// not meet: a wave's own LDS accesses complete in order.
+template <int LOGN, int PRE, int MAXS, int IDX, int NT>
+constexpr bool wave_local_after()
+{
+    using Me = RoundOf<LOGN, PRE, MAXS, IDX>;
+    using Next = RoundOf<LOGN, PRE, MAXS, IDX + 1>;
+    constexpr int lt_me = LOGN - Me::P0 - Me::S, lt_next = LOGN - Next::P0 - Next::S;
+    return PRE == 0 && Me::S == Next::S && Me::G == NT && lt_me <= 6 && lt_next <= 6;
+}
+// what separates round IDX from round IDX + 1
+template <int LOGN, int PRE, int MAXS, int IDX, int NT>
+__device__ __forceinline__ void between_rounds()
+{
+    if constexpr (wave_local_after<LOGN, PRE, MAXS, IDX, NT>()) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+        __syncthreads();
+    }
+}
+
 // Round IDX and everything after it.  Where preload_round() says so, the next round's table
 // entries are asked for before the barrier between the two rounds.
 // `before_last()` runs in front of the last round: the caller asks there for what it needs from
@@ -526,18 +605,18 @@ __device__ __forceinline__ void rounds_from(uint64_t *lds, const Twiddle *fwd, c
         ntt_round_preloaded<LOGN, PRE, Me::P0, Me::S, Me::KIND, LAZY, Me::BIN, Me::TOUT, IO>(lds, mine, md, tid,
                                                                                            h, xio);
     else
-        ntt_round<LOGN, PRE, Me::P0, Me::S, Me::KIND, NT, LAZY, Me::BIN, Me::TOUT, IO>(lds, fwd, inv, shat,
-                                                                                     md, tid, h, xio);
+        ntt_round<LOGN, PRE, Me::P0, Me::S, Me::KIND, NT, LAZY, Me::BIN, Me::TOUT, IO, true>(
+            lds, fwd, inv, shat, md, tid, h, xio);
     if constexpr (IDX + 1 < Me::TOTAL) {
         using Next = RoundOf<LOGN, PRE, MAXS, IDX + 1>;
         if constexpr (preload_round<LOGN, PRE, MAXS, IDX + 1, NT>()) {
             const int g = tid < Next::G ? tid : Next::G - 1;        // idle threads: any valid group
             const auto next = load_round_table<LOGN, Next::P0, Next::S, Next::KIND>(fwd, inv, shat, g);
-            __syncthreads();
+            between_rounds<LOGN, PRE, MAXS, IDX, NT>();
             rounds_from<LOGN, PRE, MAXS, LAZY, DIRECT, IDX + 1, NT>(lds, fwd, inv, shat, md, tid, h, next,
                                                                     before_last, xio);
         } else {
-            __syncthreads();
+            between_rounds<LOGN, PRE, MAXS, IDX, NT>();
             rounds_from<LOGN, PRE, MAXS, LAZY, DIRECT, IDX + 1, NT>(lds, fwd, inv, shat, md, tid, h,
                                                                     NoTable{}, before_last, xio);
         }
@@ -633,11 +712,29 @@ __global__ __launch_bounds__(threads_for(LOGN - PRE, 4)) void rlwe_secret_kernel
     }
 }
 
+// setup: set 0 of every limb copied into the order of the product kernels with `maxs` stages
+// per round (see power_slot()); one thread per entry
+__global__ __launch_bounds__(256) void rlwe_table_set_kernel(Twiddle *__restrict__ tables, int logN, int L,
+                                                             int pre, int maxs, int set)
+{
+    const uint32_t N = 1u << logN;
+    const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
+    if (gid >= N * (uint32_t)L) return;
+    const uint32_t l = gid >> logN, e = gid & (N - 1u);
+    const Twiddle *const from = tables + (size_t)l * limb_table_entries((int)N);
+    Twiddle *const to = tables + (size_t)l * limb_table_entries((int)N) + (size_t)set * set_entries((int)N);
+    const int p = power_slot(logN, pre, maxs, (int)e);
+    to[p] = from[e];
+    to[N + p] = from[N + e];
+    to[2 * N + secret_slot(logN, pre, maxs, (int)e)] = from[2 * N + e];
+}
+
 // ---------------------------------------------------------------------------
 // c1 * s per (ciphertext, limb), then either the phase or the assembly of c0
 // ---------------------------------------------------------------------------
 struct PolyArgs {
     const Twiddle *tables;
+    int set;        // table set of the product kernel that is launched (1 or 2)
     int L;
     // phase: src = ct [T][2][L][N], dst = phi [T][L][N]
     // encrypt: src = a [rows][L][N], dst = ctW [rows][2][L][N]
@@ -693,7 +790,7 @@ __global__ __launch_bounds__(threads_for(LOGN - PRE, MAXS)) void rlwe_poly_kerne
     const RlweLimb &P = a.limbs.limb[l];
     const uint64_t q = P.red.q;
     const Mod md = make_mod(P);
-    const Twiddle *const t = a.tables + (size_t)l * limb_table_entries(N);
+    const Twiddle *const t = a.tables + (size_t)l * limb_table_entries(N) + (size_t)a.set * set_entries(N);
     // the polynomial that is multiplied by s
     const uint64_t *const mul_in =
         ENCRYPT ? a.src + ((size_t)row * a.L + l) * N
@@ -1144,6 +1241,9 @@ static hipError_t launch_secret(const RlweArgs &a, int logN, int L, const int8_t
                                       dim3(threads_for(LOGN, 4)), stream, a, s, tables));
 }
 
+// Table sets: 1 for the kernels of large batches (and the ring of 2^15), 2 for small batches.
+constexpr int kSetLargeBatch = 1, kSetSmallBatch = 2;
+
 // every modulus in [2^34, 2^58): the kernels without conditional subtractions apply
 static bool lazy_moduli(const PolyArgs &a)
 {
@@ -1163,8 +1263,9 @@ static hipError_t launch_poly_with(const PolyArgs &a, int logN, size_t polys, hi
 
 // ring of 2^15 coefficients: two workgroups per polynomial, then the joining pass
 template <bool ENCRYPT>
-static hipError_t launch_poly_in_parts(const PolyArgs &a, size_t polys, hipStream_t stream)
+static hipError_t launch_poly_in_parts(PolyArgs a, size_t polys, hipStream_t stream)
 {
+    a.set = kSetLargeBatch;
     const hipError_t e =
         lazy_moduli(a) ? launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT, true>, dim3(2u * (unsigned)polys),
                                 dim3(threads_for(14, 4)), stream, a)
@@ -1182,10 +1283,12 @@ static hipError_t launch_poly_in_parts(const PolyArgs &a, size_t polys, hipStrea
 // smaller batch runs up to 1024 threads per polynomial, because then one workgroup has the
 // compute unit to itself and its own waves are all there is to overlap.
 template <bool ENCRYPT>
-static hipError_t launch_poly(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
+static hipError_t launch_poly(PolyArgs a, int logN, size_t polys, hipStream_t stream)
 {
     if (logN == 15) return launch_poly_in_parts<ENCRYPT>(a, polys, stream);
-    const int maxs = polys >= 1024 ? stages_large_batch(logN) : stages_small_batch(logN);
+    const bool large = polys >= 1024;
+    const int maxs = large ? stages_large_batch(logN) : stages_small_batch(logN);
+    a.set = large ? kSetLargeBatch : kSetSmallBatch;
     if (lazy_moduli(a)) {
         if (maxs == 4) return launch_poly_with<ENCRYPT, 4, true>(a, logN, polys, stream);
         if (maxs == 3) return launch_poly_with<ENCRYPT, 3, true>(a, logN, polys, stream);
@@ -1231,8 +1334,18 @@ int nimbus_rlwe_setup(int N, int L, const uint64_t *moduli, const int8_t *s,
     if (launch(rlwe_powers_kernel, dim3((total + 255u) / 256u), dim3(256), (hipStream_t)stream,
                a, logN, L, (Twiddle *)tables) != hipSuccess)
         return NIMBUS_COP_ERR_LAUNCH;
-    const hipError_t e = launch_secret(a, logN, L, s, (Twiddle *)tables, (hipStream_t)stream);
-    return e == hipSuccess ? NIMBUS_COP_OK : NIMBUS_COP_ERR_LAUNCH;
+    if (launch_secret(a, logN, L, s, (Twiddle *)tables, (hipStream_t)stream) != hipSuccess)
+        return NIMBUS_COP_ERR_LAUNCH;
+    // the same entries in the order of the product kernels: large batches, small batches
+    const int pre = logN == 15 ? 1 : 0;
+    const int maxs_of[kTableSets] = {0, logN == 15 ? 4 : stages_large_batch(logN),
+                                     logN == 15 ? 4 : stages_small_batch(logN)};
+    for (int set = 1; set < kTableSets; ++set) {
+        if (launch(rlwe_table_set_kernel, dim3((total + 255u) / 256u), dim3(256), (hipStream_t)stream,
+                   (Twiddle *)tables, logN, L, pre, maxs_of[set], set) != hipSuccess)
+            return NIMBUS_COP_ERR_LAUNCH;
+    }
+    return NIMBUS_COP_OK;
 }
 
 int nimbus_rlwe_phase(const uint64_t *ct, int T, int N, int L, const uint64_t *moduli,

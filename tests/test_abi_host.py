@@ -233,10 +233,12 @@ def test_rlwe_argument_checks_on_the_host():
     N, L = 64, 2
     good = ci.limb_primes(54, 20, L)                      # = 1 mod 2^20, so also mod 2N
     mod = (ctypes.c_uint64 * L)(*good)
-    assert nc.nimbus_rlwe_tables_bytes(N, L) == L * 3 * N * 16
+    # per limb three sets (natural order, large batches, small batches) of three tables of N
+    # entries of 16 bytes
+    assert nc.nimbus_rlwe_tables_bytes(N, L) == L * 3 * 3 * N * 16
     assert nc.nimbus_rlwe_tables_bytes(48, 1) == 0
     assert nc.nimbus_rlwe_tables_bytes(16, 1) == 0
-    assert nc.nimbus_rlwe_tables_bytes(32768, 1) == 3 * 32768 * 16
+    assert nc.nimbus_rlwe_tables_bytes(32768, 1) == 3 * 3 * 32768 * 16
     assert nc.nimbus_rlwe_tables_bytes(65536, 1) == 0
     assert nc.nimbus_rlwe_tables_bytes(64, 5) == 0
     big = nc.nimbus_rlwe_tables_bytes(N, L)
