@@ -39,9 +39,12 @@ long long nimbus_calib_stream_read(const void *src, size_t bytes, void *sink, vo
 /*
  * Register-only loop of the transform butterfly of the server side (Algorithm 1 steps 1
  * and 5 multiply polynomials in the number-theoretic-transform domain, Appendix B.1): every
- * thread of `workgroups` workgroups of 256 runs `iters` rounds of 12 lazy butterflies
- * (three stages over eight values) modulo the odd q < 2^62, with no memory access in the
- * loop.  sink: at least workgroups * 2048 bytes, written once.
+ * thread of `workgroups` workgroups of 256 runs `iters` rounds of 12 butterflies (three
+ * stages over eight values) modulo the odd q < 2^62, with no memory access in the loop.
+ * The butterfly is the one the transform kernels run for this modulus: without conditional
+ * subtractions and with the shorter quotient estimate for 2^34 <= q < 2^58, the lazy
+ * butterfly with one conditional subtraction otherwise.  sink: at least workgroups * 2048
+ * bytes, written once.
  * Returns the number of butterflies enqueued.
  */
 long long nimbus_calib_butterflies(int workgroups, int iters, unsigned long long q, void *sink,

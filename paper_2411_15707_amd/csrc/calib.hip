@@ -65,18 +65,35 @@ __global__ __launch_bounds__(256) void calib_read_kernel(const u32x4 *__restrict
     if (acc == 0x9e3779b9u) sink[0] = acc;      // keeps the loads alive, (almost) never taken
 }
 
-// Harvey-style lazy butterfly on values < 4q, q < 2^62: w a table value, ws = floor(w 2^64 / q).
-// The same arithmetic as the transform kernels, written out here so that the calibration
-// stands on its own.
+// The butterflies of the transform kernels, the same arithmetic written out here so that the
+// calibration stands on its own; w a table value, ws = floor(w 2^64 / q).
+//   LOOSE = false: Harvey-style lazy butterfly on values < 4q for any q < 2^62, one conditional
+//                  subtraction;
+//   LOOSE = true:  what the kernels do for 2^34 <= q < 2^58: no conditional subtraction, and the
+//                  quotient of the product estimated from three of the four partial products
+//                  (nq = 2^64 - q: the difference becomes a sum that the multiply-add chain
+//                  absorbs).  Values are left to wrap in this loop: it measures a rate, its
+//                  results mean nothing.
+template <bool LOOSE>
 __device__ __forceinline__ void butterfly(uint64_t &a, uint64_t &b, uint64_t w, uint64_t ws,
-                                          uint64_t q, uint64_t two_q)
+                                          uint64_t q, uint64_t two_q, uint64_t nq)
 {
-    const uint64_t u = a >= two_q ? a - two_q : a;
-    const uint64_t v = b * w - __umul64hi(b, ws) * q;
-    a = u + v;
-    b = u - v + two_q;
+    if constexpr (LOOSE) {
+        const uint32_t b0 = (uint32_t)b, b1 = (uint32_t)(b >> 32);
+        const uint32_t w0 = (uint32_t)ws, w1 = (uint32_t)(ws >> 32);
+        const uint64_t h = (uint64_t)b1 * w1 + __umulhi(b0, w1) + __umulhi(b1, w0);
+        const uint64_t u = a, v = b * w + h * nq;
+        a = u + v;
+        b = u + 2 * two_q - v;
+    } else {
+        const uint64_t u = a >= two_q ? a - two_q : a;
+        const uint64_t v = b * w - __umul64hi(b, ws) * q;
+        a = u + v;
+        b = u - v + two_q;
+    }
 }
 
+template <bool LOOSE>
 __global__ __launch_bounds__(256) void calib_butterfly_kernel(int iters, uint64_t q, uint64_t *sink)
 {
     const uint32_t seed = blockIdx.x * 256u + threadIdx.x;
@@ -87,6 +104,8 @@ __global__ __launch_bounds__(256) void calib_butterfly_kernel(int iters, uint64_
         ws[i] = (uint64_t)(((unsigned __int128)w[i] << 64) / q);
     }
     const uint64_t two_q = 2 * q;
+    uint64_t nq = 0 - q;
+    asm volatile("" : "+s"(nq));        // keeps the sum a sum
     for (int it = 0; it < iters; ++it) {
         // stages of distance 4, 2, 1 over the thread's eight values: 12 butterflies
 #pragma unroll
@@ -96,7 +115,7 @@ __global__ __launch_bounds__(256) void calib_butterfly_kernel(int iters, uint64_
             for (int r = 0; r < 8; ++r) {
                 if (r & half) continue;
                 const int t = (1 << st) - 1 + (r >> (3 - st));
-                butterfly(x[r], x[r + half], w[t], ws[t], q, two_q);
+                butterfly<LOOSE>(x[r], x[r + half], w[t], ws[t], q, two_q, nq);
             }
         }
     }
@@ -137,8 +156,12 @@ long long nimbus_calib_butterflies(int workgroups, int iters, unsigned long long
     if (workgroups < 1 || workgroups > 65535 || iters < 1 || !sink) return -1;
     if (q < 3 || (q & 1u) == 0 || q >= (1ull << 62)) return -1;
     if (sink_bytes < (size_t)workgroups * 256u * sizeof(uint64_t)) return -1;
-    if (nimbus::launch(calib_butterfly_kernel, dim3((uint32_t)workgroups), dim3(256), (hipStream_t)stream,
-                       iters, (uint64_t)q, (uint64_t *)sink) != hipSuccess)
+    // the butterfly that the transform kernels run for this modulus
+    const bool loose = q >= (1ull << 34) && q < (1ull << 58);
+    void (*const kernel)(int, uint64_t, uint64_t *) =
+        loose ? calib_butterfly_kernel<true> : calib_butterfly_kernel<false>;
+    if (nimbus::launch(kernel, dim3((uint32_t)workgroups), dim3(256), (hipStream_t)stream, iters,
+                       (uint64_t)q, (uint64_t *)sink) != hipSuccess)
         return -1;
     return (long long)workgroups * 256ll * iters * 12ll;
 }
