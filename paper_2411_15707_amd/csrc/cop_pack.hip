@@ -22,31 +22,53 @@ struct PackArgs {
     uint64_t q[kMaxLimbs];
 };
 
+// W consecutive words per thread (1, or 2 as one 16-byte access where every shift u n is even
+// and the buffers are 16-byte aligned: both words of a pair then move together and wrap
+// together).
+template <int W>
 __global__ __launch_bounds__(256) void cop_pack_kernel(const PackArgs a)
 {
+    typedef uint64_t Words __attribute__((ext_vector_type(W)));
     // grid: x covers the 2 L N words of one packed ciphertext, y = theta
-    const uint32_t w = blockIdx.x * 256u + threadIdx.x;       // word inside the ciphertext
+    const uint32_t w = (blockIdx.x * 256u + threadIdx.x) * (uint32_t)W;       // first word inside the ciphertext
     const uint32_t words = 2u * (uint32_t)a.L * (uint32_t)a.N;
     if (w >= words) return;
     const int theta = (int)blockIdx.y;
     const uint32_t c = w & (uint32_t)(a.N - 1);               // N is a power of two
     const uint32_t block = w - c;                              // (poly, limb) offset
     const uint64_t q = a.q[(w / (uint32_t)a.N) % (uint32_t)a.L];
+    auto words_at = [](const uint64_t *p) { return *(const Words *)p; };
 
-    uint64_t acc = a.mask ? a.mask[(size_t)theta * words + w] : 0;
-    if (acc >= q) acc -= q;                                    // tolerate an unreduced mask word
-    for (int u = 0; u < a.P; ++u) {
-        const int j = theta * a.P + u;
-        if (j >= a.m) break;
+    uint64_t acc[W];
+    {
+        Words v = 0;
+        if (a.mask) v = words_at(a.mask + (size_t)theta * words + w);
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            acc[i] = v[i];
+            if (acc[i] >= q) acc[i] -= q;                      // tolerate an unreduced mask word
+        }
+    }
+    const int first = theta * a.P;
+    const int count = a.m - first < a.P ? a.m - first : a.P;   // rows of this packed ciphertext
+#pragma unroll 4
+    for (int u = 0; u < count; ++u) {
         const uint32_t shift = (uint32_t)u * (uint32_t)a.n;   // < N
         const bool wrapped = c < shift;
         const uint32_t src = wrapped ? c + (uint32_t)a.N - shift : c - shift;
-        uint64_t v = a.rows[(size_t)j * words + block + src];
-        if (wrapped && v != 0) v = q - v;
-        acc += v;                                              // both below q < 2^62
-        if (acc >= q) acc -= q;
+        const Words v = words_at(a.rows + (size_t)(first + u) * words + block + src);
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            uint64_t t = v[i];
+            if (wrapped && t != 0) t = q - t;
+            acc[i] += t;                                       // both below q < 2^62
+            if (acc[i] >= q) acc[i] -= q;
+        }
     }
-    a.packed[(size_t)theta * words + w] = acc;
+    Words r;
+#pragma unroll
+    for (int i = 0; i < W; ++i) r[i] = acc[i];
+    *(Words *)(a.packed + (size_t)theta * words + w) = r;
 }
 
 hipError_t launch_cop_pack(const Problem &p, const uint64_t *rows, const uint64_t *mask,
@@ -64,7 +86,11 @@ hipError_t launch_cop_pack(const Problem &p, const uint64_t *rows, const uint64_
     a.T = (p.m + a.P - 1) / a.P;
     for (int l = 0; l < p.L; ++l) a.q[l] = p.limbs.limb[l].q;
     const uint32_t words = 2u * (uint32_t)p.L * (uint32_t)p.N;
-    return launch(cop_pack_kernel, dim3((words + 255) / 256, (uint32_t)a.T), dim3(256), stream, a);
+    const bool pairs = p.n % 2 == 0 &&
+                       (((uintptr_t)rows | (uintptr_t)mask | (uintptr_t)packed) & 15u) == 0;
+    if (pairs)
+        return launch(cop_pack_kernel<2>, dim3((words / 2 + 255) / 256, (uint32_t)a.T), dim3(256), stream, a);
+    return launch(cop_pack_kernel<1>, dim3((words + 255) / 256, (uint32_t)a.T), dim3(256), stream, a);
 }
 
 }  // namespace nimbus

@@ -379,6 +379,8 @@ PACK_SHAPES = [
     (33, 64, 64, 3, 24, 55),        # n = N
     (128, 768, 4096, 2, 20, 54),    # config 4: five per ciphertext, 26 ciphertexts
     (512, 4096, 8192, 3, 24, 55),   # config 5: two per ciphertext
+    (9, 7, 32, 2, 20, 54),          # odd n: odd shifts, one word per thread
+    (20, 333, 1024, 1, 16, 50),     # odd n, three per ciphertext
 ]
 
 
@@ -402,6 +404,19 @@ def test_pack_matches_the_oracle(oracle, m, n, N, L, t_bits, q_bits):
         got = gu.host(d_out)
         want = oracle.pack_ref(rows, n, moduli, msk)
         assert np.array_equal(got, want), gu.first_mismatch(got, want)
+    # the same call on buffers that start 8 bytes off a 16-byte boundary (one word per thread)
+    import torch
+    def off8(a):
+        big = torch.empty(a.size + 1, dtype=torch.int64, device="cuda")
+        view = big[1:].view(a.shape)
+        view.copy_(gu.dev(a))
+        return view
+    d_rows, d_mask, d_out = off8(rows), off8(mask), off8(np.zeros((T, 2, L, N), dtype=np.uint64))
+    assert d_rows.data_ptr() % 16 == 8
+    nc.nimbus_cop_pack(d_rows, m, n, N, L, moduli, d_mask, d_out)
+    got = gu.host(d_out)
+    want = oracle.pack_ref(rows, n, moduli, mask)
+    assert np.array_equal(got, want), gu.first_mismatch(got, want)
 
 
 def test_config1_matmul_then_pack_decrypts_to_side_by_side_payloads(oracle):
