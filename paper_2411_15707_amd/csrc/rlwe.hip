@@ -298,10 +298,10 @@ __device__ __forceinline__ RoundTable<S, KIND> load_round_table(const Twiddle *_
 
 // Two ways of keeping the values inside 64 bits.
 //
-// Any modulus below 2^62 (LAZY = false): forward values stay below 4q (one conditional
+// Any modulus below 2^62 (LAZY = kNever): forward values stay below 4q (one conditional
 // subtraction of 2q per butterfly), inverse values below 2q (one per sum).
 //
-// Moduli from 2^34 to 2^58 (LAZY = true) leave room for kLazyUnits = 64 multiples of q in a word.
+// Moduli from 2^34 to 2^58 (LAZY = kLoose) leave room for 64 multiples of q in a word.
 // Then the products take the cheaper quotient estimate of mul_loose() (below 4q instead of 2q)
 // and the conditional subtractions go:
 //   forward: a value that enters a stage below B q leaves it below (B + 4) q; inputs below 3q
@@ -314,13 +314,17 @@ __device__ __forceinline__ RoundTable<S, KIND> load_round_table(const Twiddle *_
 //            (five instructions each, fold()); tout is 64 / 2^(stages of the next round), so
 //            that the next round cannot overflow, and 2 in the last round, whose results are
 //            all below 2q.
-constexpr unsigned kLazyUnits = 64;
-constexpr unsigned kLooseUnits = 4;     // bound of mul_loose()
+// Moduli from 2^58 to 2^59 (LAZY = kTight; the 59-bit limb of the paper's 64-bit setting): room
+// for 32 multiples; the same scheme with the exact product (below 2q): forward below 31q, and
+// tout = 32 / 2^(stages of the next round).
+enum Lazy { kNever = 0, kLoose = 1, kTight = 2 };
+constexpr unsigned lazy_units(int lazy) { return lazy == kLoose ? 64 : 32; }
+constexpr unsigned product_units(int lazy) { return lazy == kLoose ? 4 : 2; }   // mul_loose() / mul_lazy()
 constexpr unsigned kFoldUnits = 2;      // bound of fold()
 
 // bound (in multiples of q) of the largest register of a group after an inverse round of S
 // stages that starts from `bin` everywhere and folds what exceeds `tout`
-constexpr unsigned inverse_round_out(int S, unsigned bin, unsigned tout)
+constexpr unsigned inverse_round_out(int S, unsigned bin, unsigned tout, unsigned prod)
 {
     unsigned b[16] = {};
     const int R = 1 << S;
@@ -330,7 +334,7 @@ constexpr unsigned inverse_round_out(int S, unsigned bin, unsigned tout)
         for (int r = 0; r < R; ++r) {
             if (r & half) continue;
             b[r] += b[r + half];
-            b[r + half] = kLooseUnits;
+            b[r + half] = prod;
         }
     }
     unsigned most = 0;
@@ -344,13 +348,17 @@ constexpr unsigned inverse_round_out(int S, unsigned bin, unsigned tout)
 // the butterflies of one group; F(st, j), I(st, j), Sh(r) hand out the table entries.
 // BIN, TOUT: with LAZY, bound of the registers at the start of the inverse stages, and the
 // bound above which a register is folded after them (both in multiples of q).
-template <int S, RoundKind KIND, bool LAZY, unsigned BIN, unsigned TOUT, typename FwdT, typename InvT,
+template <int S, RoundKind KIND, int LAZY, unsigned BIN, unsigned TOUT, typename FwdT, typename InvT,
           typename SecT>
 __device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], const Mod &md, FwdT F, InvT I,
                                                   SecT Sh)
 {
     constexpr int R = 1 << S;
     static_assert(S <= 4, "bounds are tracked for up to 16 registers");
+    constexpr unsigned PROD = product_units(LAZY);
+    auto product = [&](uint64_t v, const Twiddle &t) {
+        return LAZY == kLoose ? mul_loose(v, t, md.nq) : mul_lazy(v, t, md.nq);
+    };
     if constexpr (KIND != kInverse) {
 #pragma unroll
         for (int st = 0; st < S; ++st) {
@@ -359,10 +367,10 @@ __device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], const M
             for (int r = 0; r < R; ++r) {
                 if (r & half) continue;
                 const Twiddle t = F(st, r >> (S - st));
-                const uint64_t u = LAZY ? x[r] : cond_sub(x[r], md.n2q);
-                const uint64_t v = LAZY ? mul_loose(x[r + half], t, md.nq) : mul_lazy(x[r + half], t, md.nq);
+                const uint64_t u = LAZY != kNever ? x[r] : cond_sub(x[r], md.n2q);
+                const uint64_t v = product(x[r + half], t);
                 x[r] = u + v;
-                x[r + half] = u + (LAZY ? kLooseUnits * md.q : md.two_q) - v;
+                x[r + half] = u + PROD * md.q - v;
             }
         }
     }
@@ -370,14 +378,14 @@ __device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], const M
         // bit-reversed position = LDS index: the transformed secret uses the same order
 #pragma unroll
         for (int r = 0; r < R; ++r)
-            x[r] = LAZY ? mul_loose(x[r], Sh(r), md.nq) : mul_lazy(x[r], Sh(r), md.nq);
+            x[r] = product(x[r], Sh(r));
     }
     if constexpr (KIND != kForward) {
-        if constexpr (LAZY) {
-            static_assert(((KIND == kMiddle ? kLooseUnits : BIN) << S) <= kLazyUnits, "inverse round overflows");
+        if constexpr (LAZY != kNever) {
+            static_assert(((KIND == kMiddle ? PROD : BIN) << S) <= lazy_units(LAZY), "inverse round overflows");
             unsigned b[R];          // folded away: every index below is a constant after unrolling
 #pragma unroll
-            for (int r = 0; r < R; ++r) b[r] = KIND == kMiddle ? kLooseUnits : BIN;
+            for (int r = 0; r < R; ++r) b[r] = KIND == kMiddle ? PROD : BIN;
 #pragma unroll
             for (int st = S - 1; st >= 0; --st) {
                 const int half = R >> (st + 1);
@@ -387,9 +395,9 @@ __device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], const M
                     const Twiddle t = I(st, r >> (S - st));
                     const uint64_t u = x[r], v = x[r + half];
                     x[r] = u + v;
-                    x[r + half] = mul_loose(u + b[r + half] * md.q - v, t, md.nq);
+                    x[r + half] = product(u + b[r + half] * md.q - v, t);
                     b[r] += b[r + half];
-                    b[r + half] = kLooseUnits;
+                    b[r + half] = PROD;
                 }
             }
 #pragma unroll
@@ -436,7 +444,7 @@ enum RoundIo { kLdsToLds, kRegsToLds, kLdsToRegs };
 
 // a round with the table entries read from memory inside it (any number of groups per thread)
 // OWN_SET: the tables are the kernel's own set (see power_slot()), else the natural order.
-template <int LOGN, int PRE, int P0, int S, RoundKind KIND, int NT, bool LAZY = false, unsigned BIN = 2,
+template <int LOGN, int PRE, int P0, int S, RoundKind KIND, int NT, int LAZY = kNever, unsigned BIN = 2,
           unsigned TOUT = 2, RoundIo IO = kLdsToLds, bool OWN_SET = false>
 __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restrict__ fwd,
                                           const Twiddle *__restrict__ inv,
@@ -468,7 +476,7 @@ __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restri
 }
 
 // a round of at most one group per thread with the table entries already in registers
-template <int LOGN, int PRE, int P0, int S, RoundKind KIND, bool LAZY, unsigned BIN, unsigned TOUT,
+template <int LOGN, int PRE, int P0, int S, RoundKind KIND, int LAZY, unsigned BIN, unsigned TOUT,
           RoundIo IO = kLdsToLds>
 __device__ __forceinline__ void ntt_round_preloaded(uint64_t *lds, const RoundTable<S, KIND> &t,
                                                     const Mod &md, int tid, int h,
@@ -517,18 +525,18 @@ struct RoundOf {
     static constexpr int G = ((1 << LOGN) >> S) >> PRE;             // groups of one part
     // Lazy bounds of the rounds with inverse stages (idx >= F - 1), in multiples of q: what a
     // round folds behind its stages, and what its registers start from.
-    static constexpr unsigned tout_of(int idx)
+    static constexpr unsigned tout_of(int idx, int lazy)
     {
-        return idx + 1 < TOTAL ? kLazyUnits >> stages_of(idx + 1) : kFoldUnits;
+        return idx + 1 < TOTAL ? lazy_units(lazy) >> stages_of(idx + 1) : kFoldUnits;
     }
-    static constexpr unsigned bin_of(int idx)
+    static constexpr unsigned bin_of(int idx, int lazy)
     {
-        unsigned b = kLooseUnits;                                   // behind the pointwise product
-        for (int i = F - 1; i < idx; ++i) b = inverse_round_out(stages_of(i), b, tout_of(i));
+        unsigned b = product_units(lazy);                           // behind the pointwise product
+        for (int i = F - 1; i < idx; ++i)
+            b = inverse_round_out(stages_of(i), b, tout_of(i, lazy), product_units(lazy));
         return b;
     }
-    static constexpr unsigned TOUT = IDX >= F - 1 ? tout_of(IDX) : 2u;
-    static constexpr unsigned BIN = IDX >= F - 1 ? bin_of(IDX) : 2u;
+    static constexpr bool kInverseStages = IDX >= F - 1;
 };
 
 struct NoTable {};
@@ -591,7 +599,7 @@ __device__ __forceinline__ void between_rounds()
 // memory behind the product, and the round hides the latency.
 // DIRECT: round 0 takes its coefficients from xio, the last round leaves its own there (below
 // 2q) and no barrier follows it.
-template <int LOGN, int PRE, int MAXS, bool LAZY, bool DIRECT, int IDX, int NT, typename Table,
+template <int LOGN, int PRE, int MAXS, int LAZY, bool DIRECT, int IDX, int NT, typename Table,
           typename Hook>
 __device__ __forceinline__ void rounds_from(uint64_t *lds, const Twiddle *fwd, const Twiddle *inv,
                                             const Twiddle *shat, const Mod &md, int tid, int h,
@@ -600,13 +608,15 @@ __device__ __forceinline__ void rounds_from(uint64_t *lds, const Twiddle *fwd, c
     using Me = RoundOf<LOGN, PRE, MAXS, IDX>;
     constexpr RoundIo IO = !DIRECT ? kLdsToLds
                                    : (IDX == 0 ? kRegsToLds : (IDX == Me::TOTAL - 1 ? kLdsToRegs : kLdsToLds));
+    constexpr unsigned BIN = Me::kInverseStages ? Me::bin_of(IDX, LAZY) : 2u;
+    constexpr unsigned TOUT = Me::kInverseStages ? Me::tout_of(IDX, LAZY) : 2u;
     if constexpr (IDX == Me::TOTAL - 1) before_last();
     if constexpr (preload_round<LOGN, PRE, MAXS, IDX, NT>())
-        ntt_round_preloaded<LOGN, PRE, Me::P0, Me::S, Me::KIND, LAZY, Me::BIN, Me::TOUT, IO>(lds, mine, md, tid,
-                                                                                           h, xio);
+        ntt_round_preloaded<LOGN, PRE, Me::P0, Me::S, Me::KIND, LAZY, BIN, TOUT, IO>(lds, mine, md, tid, h,
+                                                                                   xio);
     else
-        ntt_round<LOGN, PRE, Me::P0, Me::S, Me::KIND, NT, LAZY, Me::BIN, Me::TOUT, IO, true>(
-            lds, fwd, inv, shat, md, tid, h, xio);
+        ntt_round<LOGN, PRE, Me::P0, Me::S, Me::KIND, NT, LAZY, BIN, TOUT, IO, true>(lds, fwd, inv, shat, md,
+                                                                                   tid, h, xio);
     if constexpr (IDX + 1 < Me::TOTAL) {
         using Next = RoundOf<LOGN, PRE, MAXS, IDX + 1>;
         if constexpr (preload_round<LOGN, PRE, MAXS, IDX + 1, NT>()) {
@@ -631,7 +641,7 @@ __device__ __forceinline__ void rounds_from(uint64_t *lds, const Twiddle *fwd, c
 // barrier, values below 2q in the LDS.
 // DIRECT: thread `tid` brings coefficient tid + i NT in xio[i] and finds the product there
 // afterwards, below 2q.
-template <int LOGN, int PRE, int MAXS, bool LAZY, bool DIRECT, int NT, typename Hook>
+template <int LOGN, int PRE, int MAXS, int LAZY, bool DIRECT, int NT, typename Hook>
 __device__ __forceinline__ void multiply_by_secret(uint64_t *lds, const Twiddle *fwd,
                                                    const Twiddle *inv, const Twiddle *shat,
                                                    const Mod &md, int tid, int h, Hook before_last,
@@ -777,8 +787,9 @@ __device__ __forceinline__ uint64_t finish_encrypt(uint64_t as, uint64_t w, int 
 // stages 1 .. LOGN-1 and back in the LDS, and leaves its half of the not yet joined product
 // where the result will be (phi, or the c0 half of the ciphertext); rlwe_join_kernel does
 // the last inverse stage and what follows.
-// LAZY: every modulus of the call lies in [2^34, 2^58) (see group_butterflies).
-template <int LOGN, int PRE, int MAXS, bool ENCRYPT, bool LAZY>
+// LAZY: kLoose where every modulus of the call lies in [2^34, 2^58), kTight where in [2^34, 2^59),
+// else kNever (see group_butterflies).
+template <int LOGN, int PRE, int MAXS, bool ENCRYPT, int LAZY>
 __global__ __launch_bounds__(threads_for(LOGN - PRE, MAXS)) void rlwe_poly_kernel(PolyArgs a)
 {
     constexpr int N = 1 << LOGN, NP = N >> PRE, NT = threads_for(LOGN - PRE, MAXS);
@@ -1244,21 +1255,33 @@ static hipError_t launch_secret(const RlweArgs &a, int logN, int L, const int8_t
 // Table sets: 1 for the kernels of large batches (and the ring of 2^15), 2 for small batches.
 constexpr int kSetLargeBatch = 1, kSetSmallBatch = 2;
 
-// every modulus in [2^34, 2^58): the kernels without conditional subtractions apply
-static bool lazy_moduli(const PolyArgs &a)
+// which of the kernels applies: without conditional subtractions where every modulus leaves
+// the room (see group_butterflies)
+static int lazy_kind(const PolyArgs &a)
 {
+    int kind = kLoose;
     for (int l = 0; l < a.L; ++l) {
         const uint64_t q = a.limbs.limb[l].red.q;
-        if (q < (1ull << 34) || q >= (1ull << 58)) return false;
+        if (q < (1ull << 34) || q >= (1ull << 59)) return kNever;
+        if (q >= (1ull << 58)) kind = kTight;
     }
-    return true;
+    return kind;
 }
 
-template <bool ENCRYPT, int MAXS, bool LAZY>
+template <bool ENCRYPT, int MAXS, int LAZY>
 static hipError_t launch_poly_with(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
 {
     NIMBUS_RLWE_DISPATCH(logN, launch(rlwe_poly_kernel<LOGN, 0, MAXS, ENCRYPT, LAZY>, dim3((unsigned)polys),
                                       dim3(threads_for(LOGN, MAXS)), stream, a));
+}
+template <bool ENCRYPT, int MAXS>
+static hipError_t launch_poly_stages(const PolyArgs &a, int logN, size_t polys, hipStream_t stream)
+{
+    switch (lazy_kind(a)) {
+    case kLoose: return launch_poly_with<ENCRYPT, MAXS, kLoose>(a, logN, polys, stream);
+    case kTight: return launch_poly_with<ENCRYPT, MAXS, kTight>(a, logN, polys, stream);
+    default: return launch_poly_with<ENCRYPT, MAXS, kNever>(a, logN, polys, stream);
+    }
 }
 
 // ring of 2^15 coefficients: two workgroups per polynomial, then the joining pass
@@ -1266,11 +1289,13 @@ template <bool ENCRYPT>
 static hipError_t launch_poly_in_parts(PolyArgs a, size_t polys, hipStream_t stream)
 {
     a.set = kSetLargeBatch;
-    const hipError_t e =
-        lazy_moduli(a) ? launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT, true>, dim3(2u * (unsigned)polys),
-                                dim3(threads_for(14, 4)), stream, a)
-                       : launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT, false>, dim3(2u * (unsigned)polys),
-                                dim3(threads_for(14, 4)), stream, a);
+    const dim3 grid(2u * (unsigned)polys), block(threads_for(14, 4));
+    hipError_t e;
+    switch (lazy_kind(a)) {
+    case kLoose: e = launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT, kLoose>, grid, block, stream, a); break;
+    case kTight: e = launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT, kTight>, grid, block, stream, a); break;
+    default: e = launch(rlwe_poly_kernel<15, 1, 4, ENCRYPT, kNever>, grid, block, stream, a); break;
+    }
     if (e != hipSuccess) return e;
     const uint64_t pairs = (uint64_t)polys << 14;
     return launch(rlwe_join_kernel<ENCRYPT>, dim3((unsigned)((pairs + 255u) / 256u)), dim3(256),
@@ -1289,14 +1314,9 @@ static hipError_t launch_poly(PolyArgs a, int logN, size_t polys, hipStream_t st
     const bool large = polys >= 1024;
     const int maxs = large ? stages_large_batch(logN) : stages_small_batch(logN);
     a.set = large ? kSetLargeBatch : kSetSmallBatch;
-    if (lazy_moduli(a)) {
-        if (maxs == 4) return launch_poly_with<ENCRYPT, 4, true>(a, logN, polys, stream);
-        if (maxs == 3) return launch_poly_with<ENCRYPT, 3, true>(a, logN, polys, stream);
-        return launch_poly_with<ENCRYPT, 2, true>(a, logN, polys, stream);
-    }
-    if (maxs == 4) return launch_poly_with<ENCRYPT, 4, false>(a, logN, polys, stream);
-    if (maxs == 3) return launch_poly_with<ENCRYPT, 3, false>(a, logN, polys, stream);
-    return launch_poly_with<ENCRYPT, 2, false>(a, logN, polys, stream);
+    if (maxs == 4) return launch_poly_stages<ENCRYPT, 4>(a, logN, polys, stream);
+    if (maxs == 3) return launch_poly_stages<ENCRYPT, 3>(a, logN, polys, stream);
+    return launch_poly_stages<ENCRYPT, 2>(a, logN, polys, stream);
 }
 
 }  // namespace nimbus

@@ -83,7 +83,10 @@ PHASE_SHAPES = [
     # that range, and the first moduli outside it on either side, at the longest transforms
     (1024, 1, 35, 8),        # smallest moduli of the range
     (1024, 1, 34, 8),        # just below it
-    (2048, 2, 59, 3),        # just above it
+    (2048, 2, 59, 3),        # 58 to 59 bits: the same without the cheaper quotient estimate
+    (16384, 2, 59, 520),     # ... at 14 stages, two groups per thread and round
+    (32768, 1, 59, 2),       # ... a stage on the way in and 14 in the LDS: 31 q in a word
+    (2048, 1, 60, 3),        # just above: conditional subtractions
     (4096, 2, 58, 512),      # largest moduli of the range: least room, 4 + 4 + 4
     (8192, 2, 58, 3),        # 3 + 3 + 3 + 2 + 2
     (16384, 1, 58, 2),       # 14 stages
@@ -132,7 +135,7 @@ def test_phase_with_degenerate_secrets(oracle, kind):
         assert np.array_equal(got, ct[:, 0])
 
 
-@pytest.mark.parametrize("N,q_bits", [(1024, 62), (1024, 58), (16384, 58), (32768, 58)])
+@pytest.mark.parametrize("N,q_bits", [(1024, 62), (1024, 58), (16384, 58), (32768, 58), (32768, 59)])
 def test_phase_with_extreme_residues(oracle, N, q_bits):
     """c1 = q - 1 everywhere and c1 = 0 everywhere: the lazy ranges of the transform at their
     ends, for the widest moduli of either kind of kernel"""
@@ -146,6 +149,22 @@ def test_phase_with_extreme_residues(oracle, N, q_bits):
     got = _gpu_phase(ct, moduli, _tables(N, moduli, s))
     for r in range(2):
         assert np.array_equal(got[r], oracle.phase(ct[r], s, moduli))
+
+
+def test_phase_with_the_moduli_of_the_64_bit_setting(oracle):
+    """N = 8192 with one 59-bit and one 55-bit limb (Section 5, experimental setup): the limbs of
+    one call take the same kernel, the one the wider modulus allows; small and large batch"""
+    N = 8192
+    moduli = (ci.limb_primes(59, 14, 1)[0], ci.limb_primes(55, 14, 1)[0])
+    assert [q.bit_length() for q in moduli] == [59, 55]
+    s = ci.gen_secret(64, N)
+    tables = _tables(N, moduli, s)
+    for T in (3, 520):
+        ct = ci.uniform_residues(6400 + T, 43, (T, 2), moduli, N)
+        _say(f"[rlwe] phase N={N} moduli of 59 and 55 bits T={T}")
+        got = _gpu_phase(ct, moduli, tables)
+        for r in sorted({0, T // 2, T - 1}):
+            assert np.array_equal(got[r], oracle.phase(ct[r], s, moduli)), f"ciphertext {r}"
 
 
 # N, L, q_bits, t_bits, T
