@@ -414,7 +414,7 @@ def main():
                                                   None, outs[i % R]), side_launches, stream)
         nomask_bytes = alg_bytes - 8 * m * C
         pack = {
-            "kernel": "cop_pack_kernel<%d>" % (2 if cfg.n % 2 == 0 else 1),
+            "kernel": "cop_pack_kernel<%d,%d>" % (2 if cfg.n % 2 == 0 else 1, 2 if P <= 2 else 4),
             "rows_per_ciphertext": P,
             "packed_ciphertexts": T,
             "kernel_ms_avg": round(pack_ms, 5),

@@ -24,8 +24,8 @@ struct PackArgs {
 
 // W consecutive words per thread (1, or 2 as one 16-byte access where every shift u n is even
 // and the buffers are 16-byte aligned: both words of a pair then move together and wrap
-// together).
-template <int W>
+// together).  CH rows are loaded at a time (2 where a packed ciphertext holds at most two).
+template <int W, int CH>
 __global__ __launch_bounds__(256) void cop_pack_kernel(const PackArgs a)
 {
     typedef uint64_t Words __attribute__((ext_vector_type(W)));
@@ -39,31 +39,43 @@ __global__ __launch_bounds__(256) void cop_pack_kernel(const PackArgs a)
     const uint64_t q = a.q[(w / (uint32_t)a.N) % (uint32_t)a.L];
     auto words_at = [](const uint64_t *p) { return *(const Words *)p; };
 
+    // every load of a thread is on its way before the first one is used: the mask's now, the
+    // rows' CH at a time (a row past the last one reads the last one again and counts as zero)
+    Words mk = 0;
+    if (a.mask) mk = words_at(a.mask + (size_t)theta * words + w);
     uint64_t acc[W];
-    {
-        Words v = 0;
-        if (a.mask) v = words_at(a.mask + (size_t)theta * words + w);
 #pragma unroll
-        for (int i = 0; i < W; ++i) {
-            acc[i] = v[i];
-            if (acc[i] >= q) acc[i] -= q;                      // tolerate an unreduced mask word
+    for (int i = 0; i < W; ++i) acc[i] = 0;
+    const int first = theta * a.P;
+    const int count = a.m - first < a.P ? a.m - first : a.P;   // rows of this packed ciphertext, >= 1
+    for (int u0 = 0; u0 < count; u0 += CH) {
+        Words v[CH];
+        bool wrapped[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            const int u = u0 + j < count ? u0 + j : count - 1;
+            const uint32_t shift = (uint32_t)u * (uint32_t)a.n;   // < N
+            wrapped[j] = c < shift;
+            const uint32_t src = wrapped[j] ? c + (uint32_t)a.N - shift : c - shift;
+            v[j] = words_at(a.rows + (size_t)(first + u) * words + block + src);
+        }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+#pragma unroll
+            for (int i = 0; i < W; ++i) {
+                uint64_t t = u0 + j < count ? v[j][i] : 0;
+                if (wrapped[j] && t != 0) t = q - t;
+                acc[i] += t;                                   // both below q < 2^62
+                if (acc[i] >= q) acc[i] -= q;
+            }
         }
     }
-    const int first = theta * a.P;
-    const int count = a.m - first < a.P ? a.m - first : a.P;   // rows of this packed ciphertext
-#pragma unroll 4
-    for (int u = 0; u < count; ++u) {
-        const uint32_t shift = (uint32_t)u * (uint32_t)a.n;   // < N
-        const bool wrapped = c < shift;
-        const uint32_t src = wrapped ? c + (uint32_t)a.N - shift : c - shift;
-        const Words v = words_at(a.rows + (size_t)(first + u) * words + block + src);
 #pragma unroll
-        for (int i = 0; i < W; ++i) {
-            uint64_t t = v[i];
-            if (wrapped && t != 0) t = q - t;
-            acc[i] += t;                                       // both below q < 2^62
-            if (acc[i] >= q) acc[i] -= q;
-        }
+    for (int i = 0; i < W; ++i) {
+        uint64_t t = mk[i];
+        if (t >= q) t -= q;                                    // tolerate an unreduced mask word
+        acc[i] += t;
+        if (acc[i] >= q) acc[i] -= q;
     }
     Words r;
 #pragma unroll
@@ -88,9 +100,12 @@ hipError_t launch_cop_pack(const Problem &p, const uint64_t *rows, const uint64_
     const uint32_t words = 2u * (uint32_t)p.L * (uint32_t)p.N;
     const bool pairs = p.n % 2 == 0 &&
                        (((uintptr_t)rows | (uintptr_t)mask | (uintptr_t)packed) & 15u) == 0;
-    if (pairs)
-        return launch(cop_pack_kernel<2>, dim3((words / 2 + 255) / 256, (uint32_t)a.T), dim3(256), stream, a);
-    return launch(cop_pack_kernel<1>, dim3((words + 255) / 256, (uint32_t)a.T), dim3(256), stream, a);
+    const dim3 grid((words / (pairs ? 2 : 1) + 255) / 256, (uint32_t)a.T), block(256);
+    if (a.P <= 2)
+        return pairs ? launch(cop_pack_kernel<2, 2>, grid, block, stream, a)
+                     : launch(cop_pack_kernel<1, 2>, grid, block, stream, a);
+    return pairs ? launch(cop_pack_kernel<2, 4>, grid, block, stream, a)
+                 : launch(cop_pack_kernel<1, 4>, grid, block, stream, a);
 }
 
 }  // namespace nimbus
