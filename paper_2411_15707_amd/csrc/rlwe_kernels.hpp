@@ -164,8 +164,10 @@ template <int LOGN, int P0, int S>
 struct Group {
     static constexpr int N = 1 << LOGN, R = 1 << S, LT = LOGN - P0 - S, G = N / R;
     int i0, base;
+    // (a round from stage 0 has one block: written out, so that its table indices are constants)
     __device__ __forceinline__ explicit Group(int g)
-        : i0(g >> LT), base(((g >> LT) << (LOGN - P0)) + (g & ((1 << LT) - 1))) {}
+        : i0(P0 == 0 ? 0 : g >> LT),
+          base(P0 == 0 ? g : ((g >> LT) << (LOGN - P0)) + (g & ((1 << LT) - 1))) {}
     __device__ __forceinline__ int at(int r) const { return base + (r << LT); }
     // pad(at(r) - index0) = pad(base - index0) + a constant: r << LT has no bits below LT, the
     // rest of the index none between LT and LT + S, and index0 and the block's start are
@@ -379,6 +381,19 @@ __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restri
     using Grp = Group<LOGN, P0, S>;
     static_assert(IO == kLdsToLds || (PRE == 0 && P0 == 0 && Grp::G == NT), "one group per thread");
     const Part part = part_of<LOGN, PRE, S>(h);
+    // In a round from stage 0 every thread needs the same table entries: read through the
+    // scalar cache.  Apart from the registers this keeps them out of the queue of the vector
+    // loads, which completes in order: the loads from HBM that the caller has issued in front of
+    // its last round (what is added to the product) then hold up nothing in that round.
+    auto entry_of = [](const Twiddle *table, int index) -> Twiddle {
+        if constexpr (PRE == 0 && P0 == 0) {
+            typedef const __attribute__((address_space(4))) Twiddle *Uniform;
+            const Uniform at = (Uniform)table + index;
+            return Twiddle{at->w, at->ws};
+        } else {
+            return table[index];
+        }
+    };
     for (int g = tid; g < (Grp::G >> PRE); g += NT) {
         const Grp grp(part.group0 + g);
         uint64_t x[Grp::R];
@@ -389,8 +404,8 @@ __device__ __forceinline__ void ntt_round(uint64_t *lds, const Twiddle *__restri
 #pragma unroll
         for (int r = 0; r < Grp::R; ++r) x[r] = IO == kRegsToLds ? xio[r] : lds[slot(r)];
         group_butterflies<S, KIND, LAZY, BIN, TOUT>(
-            x, md, [&](int st, int j) { return fwd[grp.template entry<OWN_SET>(st, j)]; },
-            [&](int st, int j) { return inv[grp.template entry<OWN_SET>(st, j)]; },
+            x, md, [&](int st, int j) { return entry_of(fwd, grp.template entry<OWN_SET>(st, j)); },
+            [&](int st, int j) { return entry_of(inv, grp.template entry<OWN_SET>(st, j)); },
             [&](int r) { return shat[grp.template secret<OWN_SET>(r, part.group0 + g)]; });
 #pragma unroll
         for (int r = 0; r < Grp::R; ++r) {
