@@ -180,6 +180,9 @@ DECRYPT_SHAPES = [
     (512, 4, 62, 32, 2),         # four limbs of 62 bits: Q just below 2^248
     (64, 3, 30, 7, 3),           # three small limbs
     (32768, 2, 55, 24, 2),       # largest ring
+    (4096, 2, 58, 20, 5),        # widest moduli of the kernels with the cheaper quotient estimate
+    (2048, 2, 59, 20, 3),        # 59 bits: no conditional subtractions, exact quotient
+    (1024, 1, 35, 7, 4),         # smallest moduli without conditional subtractions
 ]
 
 
@@ -254,6 +257,9 @@ ENCRYPT_SHAPES = [
     (3, 4096, 8192, 3, 55, 24),      # config 5 row with its three limbs
     (5, 200, 128, 4, 54, 20),        # four limbs, two chunks
     (2, 40000, 32768, 2, 55, 24),    # largest ring, two chunks: the joining pass assembles c0
+    (3, 5000, 4096, 2, 58, 20),      # moduli at the upper edges of the two kernels without conditional
+    (3, 5000, 4096, 2, 59, 20),      # subtractions, two chunks
+    (600, 100, 256, 2, 59, 20),      # 1200 polynomials: the large-batch kernel at 59 bits
 ]
 
 
