@@ -302,7 +302,8 @@ __device__ __forceinline__ void group_butterflies(uint64_t (&x)[1 << S], const M
         }
     }
     if constexpr (KIND == kMiddle) {
-        // bit-reversed position = LDS index: the transformed secret uses the same order
+        // Sh(r): the transformed secret at the group's coefficient r (bit-reversed position = index
+        // in the LDS; where in the table that is, the caller knows)
 #pragma unroll
         for (int r = 0; r < R; ++r)
             x[r] = product(x[r], Sh(r));
